@@ -1,0 +1,182 @@
+"""Plain fp64 CPU oracle of the randomized SVD with power iterations, walked in row blocks.
+
+TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  Written from the paper, not from the
+HIP code; shares nothing with it.
+
+What it computes (Alg. 1; Sec. 2 Eqs. (1)-(2); the two-sweep block structure of Alg. 2):
+    l = k + p
+    Y = A Omega                      sketch                     (Alg. 1 step 2 with q = 0, Eq. (1))
+    Q = orth(Y)                                                 (Alg. 1 step 3)
+    q times:  Z = A^T Q, W = orth(Z);  Y = A W, Q = orth(Y)     (power iteration, Eq. (2); factors
+                                                                 applied right to left, Eq. (4))
+    B = Q^T A                                                   (Alg. 1 step 4 / Alg. 2 second sweep)
+    B = Ut Sigma V^T  (dense SVD)                               (Alg. 1 step 5)
+    U = Q Ut                                                    (Alg. 1 step 6)
+A is only ever touched one row block at a time (the paper blocks the columns of a
+column-major A; a row block of a row-major A is the same memory pattern).
+
+Readings of the paper taken here:
+  * the power iteration is the global one of Alg. 1, (A A^T)^q A Omega, not the
+    block-local variant printed in Alg. 2;
+  * the panel is re-orthonormalised after every half step; in exact arithmetic this leaves
+    range(Y), and hence U Sigma V^T, unchanged (switchable with reorth=False for the pin);
+  * Omega is an input (one n x l matrix; stacking Alg. 2's per-block draws gives the same);
+  * all l = k+p triplets are returned, sigma descending; callers truncate to k.
+
+Pins (tests/test_oracle_*.py): dense SVD special case (Omega = I), exact recovery of a
+rank <= k matrix, block-size / orth-method / Omega-mixing invariances, Pythagoras identity,
+interlacing sigma_i(B) <= sigma_i(A), projector closed form for q = 0, the
+Halko-Martinsson-Tropp average error bound, and a loop-level twin (oracle/loops.py).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def row_blocks(m: int, b: int):
+    """Index ranges [r0, r1) of the row blocks; the last one is ragged."""
+    b = m if b <= 0 else b
+    return [(r0, min(m, r0 + b)) for r0 in range(0, m, b)]
+
+
+def orth_householder(Y: np.ndarray) -> np.ndarray:
+    """Orthonormal basis of range(Y) by Householder thin QR (LAPACK geqrf/orgqr)."""
+    Q, _ = np.linalg.qr(Y, mode="reduced")
+    return Q
+
+
+def orth_cholqr2(Y: np.ndarray) -> np.ndarray:
+    """CholeskyQR applied twice (used only to pin invariance to the orth method)."""
+    for _ in range(2):
+        R = np.linalg.cholesky(Y.T @ Y).T
+        Y = np.linalg.solve(R.T, Y.T).T
+    return Y
+
+
+def orth_mgs2(Y: np.ndarray) -> np.ndarray:
+    """Modified Gram-Schmidt with one re-orthogonalisation (invariance pin only)."""
+    Q = np.array(Y, dtype=np.float64, copy=True)
+    for j in range(Q.shape[1]):
+        for _ in range(2):
+            for i in range(j):
+                Q[:, j] -= (Q[:, i] @ Q[:, j]) * Q[:, i]
+        Q[:, j] /= np.linalg.norm(Q[:, j])
+    return Q
+
+
+def a_times(A, X: np.ndarray, b: int) -> np.ndarray:
+    """Y[I,:] = A[I,:] X for every row block I (A promoted to fp64 a block at a time)."""
+    m = A.shape[0]
+    Y = np.empty((m, X.shape[1]), dtype=np.float64)
+    for r0, r1 in row_blocks(m, b):
+        Y[r0:r1] = np.asarray(A[r0:r1], dtype=np.float64) @ X
+    return Y
+
+
+def at_times(A, Q: np.ndarray, b: int) -> np.ndarray:
+    """Z = sum over row blocks I of A[I,:]^T Q[I,:], accumulated in block order."""
+    m, n = A.shape
+    Z = np.zeros((n, Q.shape[1]), dtype=np.float64)
+    for r0, r1 in row_blocks(m, b):
+        Z += np.asarray(A[r0:r1], dtype=np.float64).T @ Q[r0:r1]
+    return Z
+
+
+def range_finder(A, Omega, q: int, row_block: int = 0, orth=orth_householder, reorth: bool = True):
+    """Stage (1): orthonormal Q (m x l) with range(Q) = range((A A^T)^q A Omega)."""
+    Om = np.asarray(Omega, dtype=np.float64)
+    Y = a_times(A, Om, row_block)
+    for _ in range(q):
+        if reorth:
+            Y = orth(Y)
+        Z = at_times(A, Y, row_block)
+        if reorth:
+            Z = orth(Z)
+        Y = a_times(A, Z, row_block)
+    return orth(Y)
+
+
+def brsvd(A, Omega, k: int, p: int, q: int, row_block: int = 0, orth=orth_householder,
+          reorth: bool = True):
+    """Rank-l randomized SVD of A (m x n, any float dtype; values are promoted exactly to fp64).
+
+    Returns U (m x l), s (l,), Vt (l x n) in fp64 with s descending and non-negative."""
+    m, n = A.shape
+    l = k + p
+    if not (1 <= l <= min(m, n)) or k < 1 or p < 0 or q < 0:
+        raise ValueError("need 1 <= k, 0 <= p, 0 <= q and k+p <= min(m, n)")
+    if tuple(Omega.shape) != (n, l):
+        raise ValueError("Omega must be n x (k+p)")
+    Q = range_finder(A, Omega, q, row_block, orth, reorth)
+    Bt = at_times(A, Q, row_block)                 # B^T = A^T Q  (n x l)
+    Ut, s, Vt = np.linalg.svd(Bt.T, full_matrices=False)
+    U = Q @ Ut
+    return U, s, Vt
+
+
+# --------------------------------------------------------------------------------------
+# Metrics applied identically to the oracle's and to the HIP path's results (fp64).
+# --------------------------------------------------------------------------------------
+
+def orth_defect(U: np.ndarray) -> float:
+    """Spectral norm of U^T U - I."""
+    U = np.asarray(U, dtype=np.float64)
+    return float(np.linalg.norm(U.T @ U - np.eye(U.shape[1]), 2))
+
+
+def recon_error(A, U, s, Vt, k: int | None = None, row_block: int = 4096) -> float:
+    """||A - U_k diag(s_k) V_k^T||_F / ||A||_F (the accuracy measure of Sec. 4 "Results"),
+    streamed over row blocks of A in fp64."""
+    U = np.asarray(U, dtype=np.float64)
+    s = np.asarray(s, dtype=np.float64)
+    Vt = np.asarray(Vt, dtype=np.float64)
+    if k is not None:
+        U, s, Vt = U[:, :k], s[:k], Vt[:k]
+    SV = s[:, None] * Vt
+    num = 0.0
+    den = 0.0
+    for r0, r1 in row_blocks(A.shape[0], row_block):
+        blk = np.asarray(A[r0:r1], dtype=np.float64)
+        den += float(np.sum(blk * blk))
+        blk = blk - U[r0:r1] @ SV
+        num += float(np.sum(blk * blk))
+    return float(np.sqrt(num / den))
+
+
+# --------------------------------------------------------------------------------------
+# Robust PCA by the inexact augmented Lagrange multiplier method (Alg. 3).
+# --------------------------------------------------------------------------------------
+
+def shrink(x: np.ndarray, eps: float) -> np.ndarray:
+    """Shrinkage (soft-threshold) operator of Sec. 4: x-eps if x>eps, x+eps if x<-eps, else 0."""
+    return np.where(x > eps, x - eps, np.where(x < -eps, x + eps, 0.0))
+
+
+def rpca_ialm(M, Omegas, k: int, p: int, q: int, iters: int, lam: float, mu0: float, rho: float,
+              row_block: int = 0):
+    """Alg. 3 with a fixed number of iterations.
+
+    Readings: S_0 = 0 (the listing initialises "E_0"); mu_i everywhere mu appears; the
+    multiplier starts at Y_0 = M / max(||M||_2, ||M||_max / lam) where ||M||_max is the largest
+    absolute entry; all l triplets enter L after shrinking the singular values by 1/mu_i;
+    a fresh Omega (Omegas[i]) is used in iteration i.  Returns L, S, and the per-iteration
+    residuals ||M - L - S||_F / ||M||_F.
+    """
+    M = np.asarray(M, dtype=np.float64)
+    normM = np.linalg.norm(M)
+    J = max(np.linalg.norm(M, 2), np.max(np.abs(M)) / lam)
+    Y = M / J
+    S = np.zeros_like(M)
+    L = np.zeros_like(M)
+    mu = float(mu0)
+    res = []
+    for i in range(iters):
+        X = M - S + Y / mu
+        U, s, Vt = brsvd(X, Omegas[i], k, p, q, row_block)
+        L = (U * shrink(s, 1.0 / mu)) @ Vt
+        S = shrink(M - L + Y / mu, lam / mu)
+        Z = M - L - S
+        Y = Y + mu * Z
+        res.append(float(np.linalg.norm(Z) / normM))
+        mu *= rho
+    return L, S, np.array(res)
