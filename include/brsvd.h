@@ -1,0 +1,162 @@
+/*
+ * brsvd.h -- C ABI of the MI355X (gfx950) block randomized SVD library.
+ *
+ * The library computes the rank-l (l = k + p) randomized SVD of an m x n fp32 matrix A
+ * by the two-stage scheme of Alg. 1 of the paper (sketch Y = A*Omega, q power iterations
+ * with A*A^T, orthonormal basis Q, projection B = Q^T*A, small SVD of B, lift U = Q*Ut),
+ * with A visited one row block at a time and only the thin panels (m x l, n x l) kept on
+ * the device, as in the block method of Alg. 2 / Sec. 3.  A may live in device memory or in
+ * pinned host memory; in the latter case row blocks are streamed through two staging
+ * buffers on a copy stream while the previous block is being multiplied.
+ *
+ * All matrices are ROW-MAJOR.  All entry points return an int status (0 = success,
+ * negative = error), never throw, and never abort.  The library is not re-entrant per
+ * handle: one brsvd_run / brsvd_rpca_ialm at a time per handle.
+ */
+#ifndef BRSVD_H_
+#define BRSVD_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct brsvd_handle_s* brsvd_handle;
+
+enum {
+  BRSVD_OK = 0,
+  BRSVD_ERR_ARG = -1,            /* null / inconsistent argument                              */
+  BRSVD_ERR_BUDGET = -2,         /* device_budget_bytes (or workspace) below the working set  */
+  BRSVD_ERR_ALLOC = -3,          /* hipMalloc / hipHostMalloc failed                          */
+  BRSVD_ERR_HIP = -4,            /* a HIP runtime call or kernel launch failed                */
+  BRSVD_ERR_ORTH_BREAKDOWN = -5, /* panel numerically rank deficient for the chosen method    */
+  BRSVD_ERR_SVD_NOCONV = -6      /* Jacobi sweeps exhausted without convergence               */
+};
+
+enum { BRSVD_A_DEVICE = 0, BRSVD_A_HOST_PINNED = 1 };
+enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
+
+/* Problem statement of Alg. 1 / Alg. 2 (inputs A, k, p, q and the partition), plus where A
+ * lives and how much device memory may be used (Sec. 4: the block size is chosen from the
+ * memory available at run time). */
+typedef struct {
+  int64_t m, n;                 /* A is m x n                                                  */
+  int32_t k, p, q;              /* target rank, oversampling, power exponent; l = k + p,
+                                   1 <= l <= min(m, n, 512), k >= 1, p >= 0, q >= 0            */
+  int32_t a_location;           /* BRSVD_A_DEVICE or BRSVD_A_HOST_PINNED                       */
+  int64_t row_block;            /* rows per block b (last block ragged); 0 = largest block
+                                   that fits the budget                                        */
+  uint64_t device_budget_bytes; /* cap on all device memory owned by the handle; 0 = no cap    */
+  int32_t orth_method;          /* BRSVD_ORTH_*                                                */
+  int32_t reserved;             /* must be 0                                                   */
+  void* compute_stream;         /* hipStream_t for all kernels; NULL = the null stream         */
+  void* copy_stream;            /* hipStream_t for host->device block copies (host-resident A);
+                                   NULL = the library creates one (default priority)           */
+} brsvd_params;
+
+/* Timings are measured with HIP events recorded on compute_stream (copy_stream for the
+ * copies); *_launches count kernel launches of that class during the call. */
+typedef struct {
+  double total_seconds;        /* whole call, first launch to last kernel completed            */
+  double gemm_an_seconds;      /* Y_I = A_I * X   (sketch and power steps)                     */
+  double gemm_at_seconds;      /* Z += A_I^T * Q_I (power half steps and the projection)       */
+  double orth_seconds;         /* Gram, Cholesky, triangular apply (and TSQR when taken)       */
+  double svd_seconds;          /* small SVD of the l x l factor                                */
+  double lift_seconds;         /* U = Q*Ut, V = W*U_R, transposed store of V^T                 */
+  double copy_seconds;         /* host->device block copies (sum over blocks, copy stream)     */
+  double elementwise_seconds;  /* robust-PCA elementwise kernels                               */
+  int64_t gemm_an_launches;
+  int64_t gemm_at_launches;
+  int64_t passes_over_A;       /* number of full reads of A                                    */
+  int64_t bytes_A_streamed;    /* passes * 4*m*n                                               */
+  int32_t orth_fallbacks;      /* panels that took the TSQR route after a Cholesky breakdown   */
+  int32_t jacobi_sweeps;       /* sweeps of the last small SVD                                 */
+  int32_t row_block;           /* rows per block actually used                                 */
+  int32_t n_blocks;
+} brsvd_stats;
+
+/* Device bytes brsvd_create will allocate for these parameters (panels, partial-sum
+ * scratch, small factors, and for host-resident A the two staging blocks).  Host memory. */
+int brsvd_workspace_bytes(const brsvd_params* params, uint64_t* bytes_out);
+
+/* Validates params, resolves row_block (0 => from the budget), allocates every device
+ * buffer, stream and event the handle needs on the CURRENT device.  Fails with
+ * BRSVD_ERR_BUDGET when device_budget_bytes is below the working set.  params is host
+ * memory and is copied. */
+int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out);
+
+/* One randomized SVD (Alg. 1 steps 2-6, with Omega of step 1 supplied by the caller).
+ *   A      m x n fp32, leading dimension lda >= n (elements); DEVICE pointer when
+ *          a_location == BRSVD_A_DEVICE, PINNED HOST pointer otherwise.  Never written.
+ *   Omega  DEVICE, n x l fp32, dense (leading dimension l), i.i.d. N(0,1).  Never written.
+ *   U      DEVICE out, m x l (leading dimension l): left singular vectors.
+ *   S      DEVICE out, l singular values, descending, non-negative.
+ *   Vt     DEVICE out, l x n (leading dimension n): right singular vectors, transposed.
+ *   stats  HOST out, may be NULL.
+ * Callers wanting the rank-k truncation take the first k columns / values / rows.
+ * The call returns after all results are complete (it synchronises compute_stream).
+ * On error the outputs are unspecified; the handle stays usable and destroyable. */
+int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega,
+              float* U, float* S, float* Vt, brsvd_stats* stats);
+
+/* Robust PCA by the inexact augmented Lagrange multiplier method, Alg. 3 / Eq. (3), with a
+ * FIXED number of iterations; each iteration calls the randomized SVD above on
+ * M - S_i + Y_i/mu_i, shrinks the singular values by 1/mu_i and the residual entries by
+ * lambda/mu_i (shrinkage operator of Sec. 4), updates the multiplier and mu <- rho*mu.
+ * The handle must have been created with a_location == BRSVD_A_DEVICE for an m x n problem.
+ *   M        DEVICE, m x n fp32 dense (leading dimension n).  Never written.
+ *   Omegas   DEVICE, iters x n x l fp32: one Gaussian test matrix per iteration.
+ *   norm2_M  spectral norm of M (multiplier initialisation Y_0 = M / max(||M||_2,
+ *            max|M_ij| / lambda)); pass <= 0 to have it estimated by one randomized SVD
+ *            using Omegas[0].
+ *   L, S     DEVICE out, m x n: low-rank and sparse parts.
+ *   residuals HOST out (may be NULL), iters doubles: ||M-L-S||_F / ||M||_F per iteration.
+ *   work     DEVICE scratch of 2*m*n floats owned by the caller (multiplier and the
+ *            matrix handed to the SVD), so the handle's budget stays panel-sized.
+ */
+int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t iters,
+                    float lambda, float mu0, float rho, double norm2_M,
+                    float* L, float* S, float* work, double* residuals, brsvd_stats* stats);
+
+/* Frees everything the handle owns (never the caller's buffers).  NULL is allowed. */
+int brsvd_destroy(brsvd_handle h);
+
+/* Static, NUL-terminated description of a status code. */
+const char* brsvd_status_string(int status);
+
+/* ---- Individual steps of the path, exported for kernel-level parity tests and profiling.
+ * All pointers are DEVICE pointers, all panels dense row-major; every call is asynchronous
+ * on `stream` (a hipStream_t or NULL) except where noted.  ------------------------------ */
+
+/* Y (rows x l) = A (rows x n, leading dimension lda) * X (n x l).  Alg. 1 step 2 / Alg. 2
+ * line 4 for one row block.  scratch: DEVICE, at least brsvd_gemm_scratch_bytes(rows, n, l). */
+int brsvd_gemm_an(const float* A, int64_t lda, int64_t rows, int64_t n, const float* X, int32_t l,
+                  float* Y, void* scratch, uint64_t scratch_bytes, void* stream);
+
+/* Z (n x l) (+)= A^T (A is rows x n, lda) * Q (rows x l).  Power half step Z = A^T Q and the
+ * projection B^T = A^T Q (Alg. 1 step 4, Alg. 2 line 9) for one row block; accumulate != 0
+ * adds to the existing Z (block-ordered accumulation). */
+int brsvd_gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int32_t l,
+                  float* Z, int32_t accumulate, void* scratch, uint64_t scratch_bytes, void* stream);
+
+uint64_t brsvd_gemm_scratch_bytes(int64_t rows, int64_t n, int32_t l);
+
+/* In-place orthonormalisation of a tall panel P (rows x l, rows >= l) -- Alg. 1 step 3.
+ * method is BRSVD_ORTH_*.  Optionally returns the l x l upper-triangular factor R (fp64,
+ * row-major, DEVICE, may be NULL) with P_in = P_out * R.  Synchronises `stream`.
+ * *fallback_taken (HOST, may be NULL) is set to 1 when AUTO switched to TSQR. */
+int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R,
+               int32_t* fallback_taken, void* stream);
+
+/* One-sided Jacobi SVD of an l x l fp64 matrix R (row-major, DEVICE): R = Ur diag(S) Vr^T.
+ * Outputs (DEVICE): S (l doubles, descending), Ur and Vr (l x l fp64, row-major, columns are
+ * the singular vectors).  Alg. 1 step 5 applied to the triangular factor of B^T.
+ * Synchronises `stream`; *sweeps (HOST, may be NULL) receives the sweep count. */
+int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr,
+                    int32_t* sweeps, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRSVD_H_ */

@@ -1,0 +1,245 @@
+"""Thin ctypes binding of libbrsvd (hand-written HIP for MI355X / gfx950).
+
+Only argument marshalling lives here: torch provides device memory and streams, every step of
+the block randomized SVD runs inside the shared library.  The functions carry the same names
+as the C entry points declared in include/brsvd.h.  There is no CPU fallback: if the shared
+library has not been built (python -m paper_1706_07191_amd.build) importing `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbrsvd.so")
+
+BRSVD_OK = 0
+BRSVD_ERR_ARG = -1
+BRSVD_ERR_BUDGET = -2
+BRSVD_ERR_ALLOC = -3
+BRSVD_ERR_HIP = -4
+BRSVD_ERR_ORTH_BREAKDOWN = -5
+BRSVD_ERR_SVD_NOCONV = -6
+BRSVD_A_DEVICE = 0
+BRSVD_A_HOST_PINNED = 1
+BRSVD_ORTH_AUTO = 0
+BRSVD_ORTH_CHOLQR2 = 1
+BRSVD_ORTH_TSQR = 2
+
+
+class brsvd_params(C.Structure):
+    _fields_ = [("m", C.c_int64), ("n", C.c_int64),
+                ("k", C.c_int32), ("p", C.c_int32), ("q", C.c_int32), ("a_location", C.c_int32),
+                ("row_block", C.c_int64), ("device_budget_bytes", C.c_uint64),
+                ("orth_method", C.c_int32), ("reserved", C.c_int32),
+                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
+
+
+class brsvd_stats(C.Structure):
+    _fields_ = [("total_seconds", C.c_double), ("gemm_an_seconds", C.c_double),
+                ("gemm_at_seconds", C.c_double), ("orth_seconds", C.c_double),
+                ("svd_seconds", C.c_double), ("lift_seconds", C.c_double),
+                ("copy_seconds", C.c_double), ("elementwise_seconds", C.c_double),
+                ("gemm_an_launches", C.c_int64), ("gemm_at_launches", C.c_int64),
+                ("passes_over_A", C.c_int64), ("bytes_A_streamed", C.c_int64),
+                ("orth_fallbacks", C.c_int32), ("jacobi_sweeps", C.c_int32),
+                ("row_block", C.c_int32), ("n_blocks", C.c_int32)]
+
+    def as_dict(self):
+        return {f: getattr(self, f) for f, _ in self._fields_}
+
+
+EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_destroy",
+           "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
+           "brsvd_orth", "brsvd_small_svd"]
+
+_lib = None
+
+
+class BrsvdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where} failed: {status} ({brsvd_status_string(status)})")
+
+
+def lib() -> C.CDLL:
+    """Loads libbrsvd.so (raises if it was not built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1706_07191_amd.build`; "
+                          "there is no fallback implementation")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64, dbl, flt = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double, C.c_float
+    L.brsvd_workspace_bytes.argtypes = [C.POINTER(brsvd_params), C.POINTER(u64)]
+    L.brsvd_create.argtypes = [C.POINTER(brsvd_params), C.POINTER(vp)]
+    L.brsvd_run.argtypes = [vp, vp, i64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
+    L.brsvd_rpca_ialm.argtypes = [vp, vp, vp, i32, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
+                                  C.POINTER(brsvd_stats)]
+    L.brsvd_destroy.argtypes = [vp]
+    L.brsvd_status_string.argtypes = [C.c_int]
+    L.brsvd_status_string.restype = C.c_char_p
+    L.brsvd_gemm_an.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, u64, vp]
+    L.brsvd_gemm_at.argtypes = [vp, i64, i64, i64, vp, i32, vp, i32, vp, u64, vp]
+    L.brsvd_gemm_scratch_bytes.argtypes = [i64, i64, i32]
+    L.brsvd_gemm_scratch_bytes.restype = u64
+    L.brsvd_orth.argtypes = [vp, i64, i32, i32, vp, C.POINTER(i32), vp]
+    L.brsvd_small_svd.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
+    for name in EXPORTS:
+        if name not in ("brsvd_status_string", "brsvd_gemm_scratch_bytes"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def brsvd_status_string(status: int) -> str:
+    return lib().brsvd_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != BRSVD_OK:
+        raise BrsvdError(status, where)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev(t, dtype, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous CUDA tensor of dtype {dtype}")
+    return t.data_ptr()
+
+
+def make_params(m, n, k, p, q, row_block=0, device_budget_bytes=0, a_location=BRSVD_A_DEVICE,
+                orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None) -> brsvd_params:
+    return brsvd_params(m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
+                        device_budget_bytes=device_budget_bytes, orth_method=orth_method, reserved=0,
+                        compute_stream=_stream_ptr(compute_stream),
+                        copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None)
+
+
+def brsvd_workspace_bytes(params: brsvd_params) -> int:
+    out = C.c_uint64(0)
+    _check(lib().brsvd_workspace_bytes(C.byref(params), C.byref(out)), "brsvd_workspace_bytes")
+    return out.value
+
+
+def brsvd_create(params: brsvd_params) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(lib().brsvd_create(C.byref(params), C.byref(h)), "brsvd_create")
+    return h
+
+
+def brsvd_destroy(handle) -> None:
+    _check(lib().brsvd_destroy(handle), "brsvd_destroy")
+
+
+def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = None, want_stats=True):
+    """A: (m, n) fp32 CUDA tensor (or pinned host tensor for a host-resident handle), row stride
+    lda; Omega: (n, l) fp32 CUDA.  Returns (U, S, Vt, stats) as CUDA tensors m x l, l, l x n."""
+    import torch
+    m, n = A.shape
+    l = Omega.shape[1]
+    if A.dtype != torch.float32 or A.stride(1) != 1:
+        raise TypeError("A must be fp32 with unit column stride")
+    if not A.is_cuda and not A.is_pinned():
+        raise TypeError("a host-resident A must be pinned")
+    lda = lda if lda is not None else A.stride(0)
+    dev = Omega.device
+    U = torch.empty(m, l, device=dev) if U is None else U
+    S = torch.empty(l, device=dev) if S is None else S
+    Vt = torch.empty(l, n, device=dev) if Vt is None else Vt
+    st = brsvd_stats()
+    status = lib().brsvd_run(handle, A.data_ptr(), lda, _dev(Omega, torch.float32, "Omega"),
+                             _dev(U, torch.float32, "U"), _dev(S, torch.float32, "S"),
+                             _dev(Vt, torch.float32, "Vt"), C.byref(st) if want_stats else None)
+    _check(status, "brsvd_run")
+    return U, S, Vt, (st.as_dict() if want_stats else None)
+
+
+def brsvd_rpca_ialm(handle, M, Omegas, iters, lam, mu0, rho, norm2_M=0.0, L=None, S=None, work=None):
+    import torch
+    m, n = M.shape
+    L = torch.empty_like(M) if L is None else L
+    S = torch.empty_like(M) if S is None else S
+    work = torch.empty(2 * m * n, device=M.device) if work is None else work
+    res = (C.c_double * iters)()
+    st = brsvd_stats()
+    status = lib().brsvd_rpca_ialm(handle, _dev(M, torch.float32, "M"), _dev(Omegas, torch.float32, "Omegas"),
+                                   iters, lam, mu0, rho, norm2_M, _dev(L, torch.float32, "L"),
+                                   _dev(S, torch.float32, "S"), _dev(work, torch.float32, "work"), res,
+                                   C.byref(st))
+    _check(status, "brsvd_rpca_ialm")
+    return L, S, list(res), st.as_dict()
+
+
+def brsvd_gemm_scratch_bytes(rows, n, l) -> int:
+    return lib().brsvd_gemm_scratch_bytes(rows, n, l)
+
+
+def _scratch(rows, n, l, device):
+    import torch
+    nbytes = brsvd_gemm_scratch_bytes(rows, n, l)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device), nbytes
+
+
+def brsvd_gemm_an(A, X, Y=None, rows=None, lda=None, stream=None):
+    """Y = A[:rows] @ X on the HIP path.  A (rows, n) fp32 CUDA (row stride lda), X (n, l)."""
+    import torch
+    rows = A.shape[0] if rows is None else rows
+    n = A.shape[1]
+    l = X.shape[1]
+    lda = A.stride(0) if lda is None else lda
+    Y = torch.empty(rows, l, device=X.device) if Y is None else Y
+    scr, nbytes = _scratch(rows, n, l, X.device)
+    _check(lib().brsvd_gemm_an(A.data_ptr(), lda, rows, n, _dev(X, torch.float32, "X"), l,
+                               _dev(Y, torch.float32, "Y"), scr.data_ptr(), nbytes, _stream_ptr(stream)),
+           "brsvd_gemm_an")
+    return Y
+
+
+def brsvd_gemm_at(A, Q, Z=None, accumulate=False, lda=None, stream=None):
+    """Z (+)= A^T @ Q on the HIP path.  A (rows, n), Q (rows, l), Z (n, l)."""
+    import torch
+    rows, n = A.shape
+    l = Q.shape[1]
+    lda = A.stride(0) if lda is None else lda
+    Z = torch.zeros(n, l, device=Q.device) if Z is None else Z
+    scr, nbytes = _scratch(rows, n, l, Q.device)
+    _check(lib().brsvd_gemm_at(A.data_ptr(), lda, rows, n, _dev(Q, torch.float32, "Q"), l,
+                               _dev(Z, torch.float32, "Z"), 1 if accumulate else 0, scr.data_ptr(), nbytes,
+                               _stream_ptr(stream)), "brsvd_gemm_at")
+    return Z
+
+
+def brsvd_orth(P, method=BRSVD_ORTH_AUTO, want_R=False, stream=None):
+    """In-place orthonormalisation of the columns of P (rows, l).  Returns (P, R or None, fallback)."""
+    import torch
+    rows, l = P.shape
+    R = torch.empty(l, l, dtype=torch.float64, device=P.device) if want_R else None
+    fb = C.c_int32(0)
+    _check(lib().brsvd_orth(_dev(P, torch.float32, "P"), rows, l, method, R.data_ptr() if want_R else None,
+                            C.byref(fb), _stream_ptr(stream)), "brsvd_orth")
+    return P, R, bool(fb.value)
+
+
+def brsvd_small_svd(R, stream=None):
+    """One-sided Jacobi SVD of an l x l fp64 CUDA matrix: returns (S, Ur, Vr, sweeps)."""
+    import torch
+    l = R.shape[0]
+    S = torch.empty(l, dtype=torch.float64, device=R.device)
+    Ur = torch.empty(l, l, dtype=torch.float64, device=R.device)
+    Vr = torch.empty(l, l, dtype=torch.float64, device=R.device)
+    sw = C.c_int32(0)
+    _check(lib().brsvd_small_svd(_dev(R, torch.float64, "R"), l, S.data_ptr(), Ur.data_ptr(), Vr.data_ptr(),
+                                 C.byref(sw), _stream_ptr(stream)), "brsvd_small_svd")
+    return S, Ur, Vr, sw.value

@@ -1,0 +1,662 @@
+// Driver and C ABI of libbrsvd: the block randomized SVD of Alg. 1 / Alg. 2 on one MI355X.
+//
+// Pass structure (l = k + p, A visited in row blocks; "pass" = one full read of A):
+//   pass 0          Y = A * Omega                 gemm_an     Q = orth(Y)
+//   q times         Z = A^T * Q                   gemm_at     W = orth(Z)
+//                   Y = A * W                     gemm_an     Q = orth(Y)
+//   last pass       B^T = A^T * Q                 gemm_at     B^T = W_B * R_B (orth, R kept)
+//   small SVD       R_B = Ur diag(s) Vr^T         Jacobi
+//   lifts           U = Q * Vr,  V = W_B * Ur, V^T stored
+// Device-resident A: each pass is one launch over all row blocks (the blocks only shape the
+// order of the partial sums of A^T * Q).  Host-resident A: each block is copied into one of two
+// staging buffers on the copy stream while the other is being multiplied on the compute stream.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace brsvd;
+
+namespace {
+
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+enum Cat { CAT_AN = 0, CAT_AT, CAT_ORTH, CAT_SVD, CAT_LIFT, CAT_COPY, CAT_ELEM, CAT_TOTAL, CAT_COUNT };
+
+struct Layout {
+  // offsets into the arena
+  uint64_t Pm[2], Pn[2], gemm_scratch, gram_part, G, R0, R1, Xinv, Rinv, Rtot, XV, XU, svdW, svdJ, sig,
+      S32, flags, tsqr, stage[2], scal, total;
+  uint64_t gemm_scratch_bytes, tsqr_bytes, stage_bytes;
+  int gram_chunks;
+};
+
+}  // namespace
+
+struct brsvd_handle_s {
+  brsvd_params prm;
+  int l, Lp;
+  int64_t b;
+  int nblocks;
+  bool host_a;
+  Layout lay;
+  char* arena;
+  hipStream_t compute, copy;
+  bool own_copy;
+  hipEvent_t filled[2], drained[2];
+  int* host_flags;                 // pinned: [0] breakdown, [1] sweeps, [2] converged
+  double* host_scal;               // pinned scalars for the robust-PCA loop
+  std::vector<hipEvent_t> ev;      // timing event pool
+  std::vector<std::pair<int, int>> regions[CAT_COUNT];
+  size_t ev_used;
+  bool timing;
+  int64_t launches[CAT_COUNT];
+
+  float* Pm(int i) { return (float*)(arena + lay.Pm[i]); }
+  float* Pn(int i) { return (float*)(arena + lay.Pn[i]); }
+  template <typename T> T* at(uint64_t off) { return (T*)(arena + off); }
+};
+
+namespace {
+
+int validate(const brsvd_params* p) {
+  if (!p) return BRSVD_ERR_ARG;
+  if (p->m < 1 || p->n < 1 || p->k < 1 || p->p < 0 || p->q < 0) return BRSVD_ERR_ARG;
+  int64_t l = (int64_t)p->k + p->p;
+  if (l > kMaxL || l > p->m || l > p->n) return BRSVD_ERR_ARG;
+  if (p->m > INT32_MAX || p->n > INT32_MAX) return BRSVD_ERR_ARG;
+  if (p->a_location != BRSVD_A_DEVICE && p->a_location != BRSVD_A_HOST_PINNED) return BRSVD_ERR_ARG;
+  if (p->orth_method < BRSVD_ORTH_AUTO || p->orth_method > BRSVD_ORTH_TSQR) return BRSVD_ERR_ARG;
+  if (p->row_block < 0 || p->reserved != 0) return BRSVD_ERR_ARG;
+  return BRSVD_OK;
+}
+
+// Working set for a given row block b.
+Layout make_layout(const brsvd_params& p, int64_t b) {
+  Layout L;
+  std::memset(&L, 0, sizeof(L));
+  const int l = p.k + p.p, Lp = padded_l(l);
+  const int64_t m = p.m, n = p.n;
+  const bool host = p.a_location == BRSVD_A_HOST_PINNED;
+  uint64_t off = 0;
+  auto take = [&](uint64_t bytes) { uint64_t o = off; off += align_up(bytes); return o; };
+  for (int i = 0; i < 2; ++i) L.Pm[i] = take((uint64_t)m * Lp * 4);
+  for (int i = 0; i < 2; ++i) L.Pn[i] = take((uint64_t)n * Lp * 4);
+  // split-sum scratch: the largest of every GEMM shape issued by the driver
+  uint64_t gs = 0;
+  if (host) {
+    gs = std::max(gs, gemm_an_scratch_bytes(b, n, Lp));
+    gs = std::max(gs, gemm_at_scratch_bytes(b, n, Lp, b));
+  } else {
+    gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b));
+  }
+  gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp));
+  gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp));
+  L.gemm_scratch_bytes = gs;
+  L.gemm_scratch = take(gs);
+  L.gram_chunks = (int)std::max(orth_gram_chunks(m), orth_gram_chunks(n));
+  L.gram_part = take((uint64_t)L.gram_chunks * Lp * Lp * 8);
+  const uint64_t sq8 = (uint64_t)Lp * Lp * 8, sq4 = (uint64_t)Lp * Lp * 4;
+  L.G = take(sq8); L.R0 = take(sq8); L.R1 = take(sq8); L.Xinv = take(sq8); L.Rtot = take(sq8);
+  L.Rinv = take(sq4); L.XV = take(sq4); L.XU = take(sq4);
+  L.svdW = take(sq8); L.svdJ = take(sq8);
+  L.sig = take((uint64_t)3 * Lp * 8);
+  L.S32 = take((uint64_t)Lp * 4);
+  L.flags = take(64);
+  L.scal = take(64);
+  L.tsqr_bytes = std::max(tsqr_work_bytes(m, Lp), tsqr_work_bytes(n, Lp));
+  L.tsqr = take(L.tsqr_bytes);
+  if (host) {
+    L.stage_bytes = (uint64_t)b * n * 4;
+    for (int i = 0; i < 2; ++i) L.stage[i] = take(L.stage_bytes);
+  }
+  L.total = off;
+  return L;
+}
+
+// Resolve the row block: the caller's value, or the largest that fits the budget.
+int resolve_block(const brsvd_params& p, int64_t* b_out) {
+  const bool host = p.a_location == BRSVD_A_HOST_PINNED;
+  int64_t b = p.row_block > 0 ? std::min<int64_t>(p.row_block, p.m) : 0;
+  uint64_t budget = p.device_budget_bytes;
+  if (b == 0) {
+    if (!host) {
+      b = p.m;
+    } else {
+      if (budget == 0) {
+        size_t free_b = 0, total_b = 0;
+        if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) return BRSVD_ERR_HIP;
+        budget = (uint64_t)(free_b * 0.8);
+      }
+      // largest multiple of 256 rows whose working set fits
+      int64_t lo = 0, hi = (p.m + 255) / 256;
+      while (lo < hi) {
+        int64_t mid = (lo + hi + 1) / 2;
+        int64_t bb = std::min<int64_t>(mid * 256, p.m);
+        if (make_layout(p, bb).total <= budget) lo = mid; else hi = mid - 1;
+      }
+      if (lo == 0) return BRSVD_ERR_BUDGET;
+      b = std::min<int64_t>(lo * 256, p.m);
+    }
+  }
+  if (p.device_budget_bytes && make_layout(p, b).total > p.device_budget_bytes) return BRSVD_ERR_BUDGET;
+  *b_out = b;
+  return BRSVD_OK;
+}
+
+struct Region {
+  brsvd_handle h;
+  int cat;
+  hipStream_t s;
+  int i0;
+  Region(brsvd_handle h_, int cat_, hipStream_t s_) : h(h_), cat(cat_), s(s_), i0(-1) {
+    if (!h->timing || h->ev_used + 2 > h->ev.size()) return;
+    i0 = (int)h->ev_used;
+    h->ev_used += 2;
+    (void)hipEventRecord(h->ev[i0], s);
+  }
+  ~Region() {
+    if (i0 < 0) return;
+    (void)hipEventRecord(h->ev[i0 + 1], s);
+    h->regions[cat].push_back({i0, i0 + 1});
+  }
+};
+
+// A pair of events from the pool for tight per-kernel timing; registered under `cat`.
+bool kernel_events(brsvd_handle h, int cat, KernelEvents* ke) {
+  h->launches[cat]++;
+  if (!h->timing || h->ev_used + 2 > h->ev.size()) return false;
+  int i0 = (int)h->ev_used;
+  h->ev_used += 2;
+  ke->start = h->ev[i0];
+  ke->stop = h->ev[i0 + 1];
+  h->regions[cat].push_back({i0, i0 + 1});
+  return true;
+}
+
+OrthWork orth_work(brsvd_handle h) {
+  OrthWork w;
+  w.gram_part = h->at<double>(h->lay.gram_part);
+  w.gram_chunks_max = h->lay.gram_chunks;
+  w.G = h->at<double>(h->lay.G);
+  w.R[0] = h->at<double>(h->lay.R0);
+  w.R[1] = h->at<double>(h->lay.R1);
+  w.Xinv = h->at<double>(h->lay.Xinv);
+  w.Rinv = h->at<float>(h->lay.Rinv);
+  w.flags = h->at<int>(h->lay.flags);
+  w.gemm_scratch = h->arena + h->lay.gemm_scratch;
+  w.gemm_scratch_bytes = h->lay.gemm_scratch_bytes;
+  w.tsqr_work = h->arena + h->lay.tsqr;
+  w.tsqr_bytes = h->lay.tsqr_bytes;
+  return w;
+}
+
+// ---- one pass over A ---------------------------------------------------------------------------
+// Host-resident A: software pipeline over the two staging buffers.
+struct Streamer {
+  brsvd_handle h;
+  const float* A;
+  int64_t lda;
+  int issued;   // blocks whose copy has been enqueued in this pass
+  Streamer(brsvd_handle h_, const float* A_, int64_t lda_) : h(h_), A(A_), lda(lda_), issued(0) {}
+  int64_t rows_of(int i) const { return std::min<int64_t>(h->b, h->prm.m - (int64_t)i * h->b); }
+  int enqueue_copy(int i) {
+    const int buf = i & 1;
+    // the buffer must have been consumed by the GEMM that last used it
+    BRSVD_HIP_TRY(hipStreamWaitEvent(h->copy, h->drained[buf], 0));
+    float* dst = h->at<float>(h->lay.stage[buf]);
+    const float* src = A + (int64_t)i * h->b * lda;
+    const int64_t rows = rows_of(i), n = h->prm.n;
+    Region r(h, CAT_COPY, h->copy);
+    if (lda == n) {
+      BRSVD_HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * n * 4, hipMemcpyHostToDevice, h->copy));
+    } else {
+      BRSVD_HIP_TRY(hipMemcpy2DAsync(dst, (size_t)n * 4, src, (size_t)lda * 4, (size_t)n * 4, (size_t)rows,
+                                     hipMemcpyHostToDevice, h->copy));
+    }
+    BRSVD_HIP_TRY(hipEventRecord(h->filled[buf], h->copy));
+    return BRSVD_OK;
+  }
+  // make block i available to the compute stream; prefetch block i+1
+  int acquire(int i, const float** blk) {
+    if (issued == 0) { BRSVD_TRY(enqueue_copy(0)); issued = 1; }
+    if (i + 1 < h->nblocks && issued == i + 1) { BRSVD_TRY(enqueue_copy(i + 1)); issued = i + 2; }
+    BRSVD_HIP_TRY(hipStreamWaitEvent(h->compute, h->filled[i & 1], 0));
+    *blk = h->at<float>(h->lay.stage[i & 1]);
+    return BRSVD_OK;
+  }
+  int release(int i) {
+    BRSVD_HIP_TRY(hipEventRecord(h->drained[i & 1], h->compute));
+    return BRSVD_OK;
+  }
+};
+
+int pass_an(brsvd_handle h, const float* A, int64_t lda, const float* X, float* Y) {
+  const int Lp = h->Lp;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  void* scr = h->arena + h->lay.gemm_scratch;
+  if (!h->host_a) {
+    KernelEvents ke;
+    bool t = kernel_events(h, CAT_AN, &ke);
+    return gemm_an(A, lda, m, n, X, Lp, Y, Lp, Lp, scr, h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr);
+  }
+  Streamer st(h, A, lda);
+  for (int i = 0; i < h->nblocks; ++i) {
+    const float* blk;
+    BRSVD_TRY(st.acquire(i, &blk));
+    KernelEvents ke;
+    bool t = kernel_events(h, CAT_AN, &ke);
+    BRSVD_TRY(gemm_an(blk, n, st.rows_of(i), n, X, Lp, Y + (int64_t)i * h->b * Lp, Lp, Lp, scr,
+                      h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr));
+    BRSVD_TRY(st.release(i));
+  }
+  return BRSVD_OK;
+}
+
+int pass_at(brsvd_handle h, const float* A, int64_t lda, const float* Q, float* Z) {
+  const int Lp = h->Lp;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  void* scr = h->arena + h->lay.gemm_scratch;
+  if (!h->host_a) {
+    KernelEvents ke;
+    bool t = kernel_events(h, CAT_AT, &ke);
+    return gemm_at(A, lda, m, n, Q, Lp, Z, false, h->b, scr, h->lay.gemm_scratch_bytes, h->compute,
+                   t ? &ke : nullptr);
+  }
+  Streamer st(h, A, lda);
+  for (int i = 0; i < h->nblocks; ++i) {
+    const float* blk;
+    BRSVD_TRY(st.acquire(i, &blk));
+    KernelEvents ke;
+    bool t = kernel_events(h, CAT_AT, &ke);
+    BRSVD_TRY(gemm_at(blk, n, st.rows_of(i), n, Q + (int64_t)i * h->b * Lp, Lp, Z, i > 0, st.rows_of(i), scr,
+                      h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr));
+    BRSVD_TRY(st.release(i));
+  }
+  return BRSVD_OK;
+}
+
+// The whole factorisation, enqueued asynchronously on the handle's streams.
+int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S,
+                  float* Vt, int method) {
+  const int l = h->l, Lp = h->Lp, q = h->prm.q;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  hipStream_t cs = h->compute;
+  OrthWork ow = orth_work(h);
+  void* scr = h->arena + h->lay.gemm_scratch;
+  const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
+
+  float* Xn = h->Pn(0);    // current n x Lp panel (Omega, then W)
+  float* Tn = h->Pn(1);
+  float* Ym = h->Pm(0);    // current m x Lp panel
+  float* Tm = h->Pm(1);
+  float* res;
+
+  BRSVD_TRY(pad_panel(Omega, n, l, Xn, Lp, cs));
+  BRSVD_TRY(pass_an(h, A, lda, Xn, Ym));
+  {
+    Region r(h, CAT_ORTH, cs);
+    BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, ow, nullptr, &res, cs));
+    if (res != Ym) std::swap(Ym, Tm);
+  }
+  for (int it = 0; it < q; ++it) {
+    BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+    {
+      Region r(h, CAT_ORTH, cs);
+      BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, ow, nullptr, &res, cs));
+      if (res != Xn) std::swap(Xn, Tn);
+    }
+    BRSVD_TRY(pass_an(h, A, lda, Xn, Tm));
+    std::swap(Ym, Tm);
+    {
+      Region r(h, CAT_ORTH, cs);
+      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, ow, nullptr, &res, cs));
+      if (res != Ym) std::swap(Ym, Tm);
+    }
+  }
+  // projection B^T = A^T Q, its thin QR, the small SVD, the lifts
+  BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+  double* Rtot = h->at<double>(h->lay.Rtot);
+  {
+    Region r(h, CAT_ORTH, cs);
+    BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, ow, Rtot, &res, cs));
+    if (res != Xn) std::swap(Xn, Tn);
+  }
+  SvdWork sw;
+  sw.W = h->at<double>(h->lay.svdW);
+  sw.J = h->at<double>(h->lay.svdJ);
+  sw.sig = h->at<double>(h->lay.sig);
+  sw.info = h->at<int>(h->lay.flags) + 4;
+  float* XV = h->at<float>(h->lay.XV);
+  float* XU = h->at<float>(h->lay.XU);
+  {
+    Region r(h, CAT_SVD, cs);
+    BRSVD_TRY(small_svd(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
+  }
+  {
+    Region r(h, CAT_LIFT, cs);
+    BRSVD_TRY(gemm_an(Ym, Lp, m, Lp, XV, Lp, U, l, l, scr, scr_bytes, cs));          // U = Q * Vr
+    BRSVD_TRY(gemm_an(Xn, Lp, n, Lp, XU, Lp, Tn, Lp, Lp, scr, scr_bytes, cs));       // V = W_B * Ur
+    BRSVD_TRY(transpose_panel(Tn, n, Lp, l, Vt, cs));
+  }
+  return BRSVD_OK;
+}
+
+void reset_timing(brsvd_handle h, bool on) {
+  h->timing = on;
+  h->ev_used = 0;
+  for (int c = 0; c < CAT_COUNT; ++c) { h->regions[c].clear(); h->launches[c] = 0; }
+}
+
+double sum_regions(brsvd_handle h, int cat) {
+  double s = 0.0;
+  for (auto& pr : h->regions[cat]) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, h->ev[pr.first], h->ev[pr.second]) == hipSuccess) s += ms * 1e-3;
+  }
+  return s;
+}
+
+void fill_stats(brsvd_handle h, brsvd_stats* st, int passes, int fallbacks) {
+  std::memset(st, 0, sizeof(*st));
+  st->total_seconds = sum_regions(h, CAT_TOTAL);
+  st->gemm_an_seconds = sum_regions(h, CAT_AN);
+  st->gemm_at_seconds = sum_regions(h, CAT_AT);
+  st->orth_seconds = sum_regions(h, CAT_ORTH);
+  st->svd_seconds = sum_regions(h, CAT_SVD);
+  st->lift_seconds = sum_regions(h, CAT_LIFT);
+  st->copy_seconds = sum_regions(h, CAT_COPY);
+  st->elementwise_seconds = sum_regions(h, CAT_ELEM);
+  st->gemm_an_launches = h->launches[CAT_AN];
+  st->gemm_at_launches = h->launches[CAT_AT];
+  st->passes_over_A = passes;
+  st->bytes_A_streamed = (int64_t)passes * 4 * h->prm.m * h->prm.n;
+  st->orth_fallbacks = fallbacks;
+  st->jacobi_sweeps = h->host_flags[1];
+  st->row_block = (int32_t)h->b;
+  st->n_blocks = h->nblocks;
+}
+
+// Runs one factorisation to completion (synchronises), handling the optimistic CholeskyQR route:
+// the breakdown flag is only inspected at the end, and AUTO then repeats the run with TSQR.
+int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
+             int* fallbacks) {
+  int method = h->prm.orth_method;
+  int* dflags = h->at<int>(h->lay.flags);
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    BRSVD_HIP_TRY(hipMemsetAsync(dflags, 0, 64, h->compute));
+    BRSVD_TRY(enqueue_brsvd(h, A, lda, Omega, U, S, Vt, method));
+    BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags, dflags, sizeof(int), hipMemcpyDeviceToHost, h->compute));
+    BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags + 1, dflags + 4, 2 * sizeof(int), hipMemcpyDeviceToHost,
+                                 h->compute));
+    BRSVD_HIP_TRY(hipStreamSynchronize(h->compute));
+    if (h->host_a) BRSVD_HIP_TRY(hipStreamSynchronize(h->copy));
+    if (h->host_flags[0] == 0) {
+      if (h->host_flags[2] == 0) return BRSVD_ERR_SVD_NOCONV;
+      return BRSVD_OK;
+    }
+    if (method != BRSVD_ORTH_AUTO) return BRSVD_ERR_ORTH_BREAKDOWN;
+    method = BRSVD_ORTH_TSQR;
+    if (fallbacks) ++*fallbacks;
+  }
+  return BRSVD_ERR_ORTH_BREAKDOWN;
+}
+
+}  // namespace
+
+// ================================================================================================
+// C ABI
+// ================================================================================================
+extern "C" {
+
+int brsvd_workspace_bytes(const brsvd_params* params, uint64_t* bytes_out) {
+  if (!bytes_out) return BRSVD_ERR_ARG;
+  BRSVD_TRY(validate(params));
+  int64_t b;
+  BRSVD_TRY(resolve_block(*params, &b));
+  *bytes_out = make_layout(*params, b).total;
+  return BRSVD_OK;
+}
+
+int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
+  if (!handle_out) return BRSVD_ERR_ARG;
+  *handle_out = nullptr;
+  BRSVD_TRY(validate(params));
+  int64_t b;
+  BRSVD_TRY(resolve_block(*params, &b));
+  brsvd_handle h = new (std::nothrow) brsvd_handle_s();
+  if (!h) return BRSVD_ERR_ALLOC;
+  h->prm = *params;
+  h->l = params->k + params->p;
+  h->Lp = padded_l(h->l);
+  h->b = b;
+  h->nblocks = (int)ceil_div(params->m, b);
+  h->host_a = params->a_location == BRSVD_A_HOST_PINNED;
+  h->lay = make_layout(*params, b);
+  h->arena = nullptr;
+  h->compute = (hipStream_t)params->compute_stream;
+  h->copy = (hipStream_t)params->copy_stream;
+  h->own_copy = false;
+  h->host_flags = nullptr;
+  h->host_scal = nullptr;
+  h->ev_used = 0;
+  h->timing = false;
+  for (int i = 0; i < 2; ++i) { h->filled[i] = nullptr; h->drained[i] = nullptr; }
+  int status = BRSVD_OK;
+  do {
+    if (hipMalloc((void**)&h->arena, h->lay.total) != hipSuccess) { status = BRSVD_ERR_ALLOC; break; }
+    if (hipMemset(h->arena + h->lay.gram_part, 0, (size_t)h->lay.gram_chunks * h->Lp * h->Lp * 8) != hipSuccess) {
+      status = BRSVD_ERR_HIP; break;
+    }
+    if (hipHostMalloc((void**)&h->host_flags, 64, hipHostMallocDefault) != hipSuccess) { status = BRSVD_ERR_ALLOC; break; }
+    if (hipHostMalloc((void**)&h->host_scal, 64, hipHostMallocDefault) != hipSuccess) { status = BRSVD_ERR_ALLOC; break; }
+    std::memset(h->host_flags, 0, 64);
+    if (h->host_a) {
+      if (!h->copy) {
+        if (hipStreamCreateWithFlags(&h->copy, hipStreamNonBlocking) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+        h->own_copy = true;
+      }
+      bool ok = true;
+      for (int i = 0; i < 2 && ok; ++i) {
+        ok = hipEventCreateWithFlags(&h->filled[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&h->drained[i], hipEventDisableTiming) == hipSuccess;
+      }
+      if (!ok) { status = BRSVD_ERR_HIP; break; }
+    }
+    const size_t pool = 64 + (size_t)h->nblocks * 8 * (2 * params->q + 2);
+    h->ev.resize(pool, nullptr);
+    bool ok = true;
+    for (size_t i = 0; i < pool && ok; ++i) ok = hipEventCreate(&h->ev[i]) == hipSuccess;
+    if (!ok) { status = BRSVD_ERR_HIP; break; }
+  } while (0);
+  if (status != BRSVD_OK) {
+    brsvd_destroy(h);
+    return status;
+  }
+  *handle_out = h;
+  return BRSVD_OK;
+}
+
+int brsvd_destroy(brsvd_handle h) {
+  if (!h) return BRSVD_OK;
+  if (h->arena) (void)hipDeviceSynchronize();
+  for (auto e : h->ev) if (e) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i) {
+    if (h->filled[i]) (void)hipEventDestroy(h->filled[i]);
+    if (h->drained[i]) (void)hipEventDestroy(h->drained[i]);
+  }
+  if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
+  if (h->host_flags) (void)hipHostFree(h->host_flags);
+  if (h->host_scal) (void)hipHostFree(h->host_scal);
+  if (h->arena) (void)hipFree(h->arena);
+  delete h;
+  return BRSVD_OK;
+}
+
+int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
+              brsvd_stats* stats) {
+  if (!h || !A || !Omega || !U || !S || !Vt) return BRSVD_ERR_ARG;
+  if (lda < h->prm.n) return BRSVD_ERR_ARG;
+  reset_timing(h, stats != nullptr);
+  int fallbacks = 0, status;
+  if (h->host_a) {
+    // the staging buffers start out free
+    for (int i = 0; i < 2; ++i) BRSVD_HIP_TRY(hipEventRecord(h->drained[i], h->compute));
+  }
+  {
+    Region total(h, CAT_TOTAL, h->compute);
+    status = run_sync(h, A, lda, Omega, U, S, Vt, &fallbacks);
+  }
+  if (stats) {
+    (void)hipStreamSynchronize(h->compute);
+    fill_stats(h, stats, (2 * h->prm.q + 2) * (1 + fallbacks), fallbacks);
+  }
+  return status;
+}
+
+const char* brsvd_status_string(int status) {
+  switch (status) {
+    case BRSVD_OK: return "ok";
+    case BRSVD_ERR_ARG: return "invalid argument";
+    case BRSVD_ERR_BUDGET: return "device memory budget or scratch too small for the working set";
+    case BRSVD_ERR_ALLOC: return "memory allocation failed";
+    case BRSVD_ERR_HIP: return "HIP runtime error";
+    case BRSVD_ERR_ORTH_BREAKDOWN: return "panel orthonormalisation broke down (numerically rank deficient)";
+    case BRSVD_ERR_SVD_NOCONV: return "Jacobi SVD did not converge";
+    default: return "unknown status";
+  }
+}
+
+// ---- step-level entry points --------------------------------------------------------------------
+
+uint64_t brsvd_gemm_scratch_bytes(int64_t rows, int64_t n, int32_t l) {
+  if (rows < 1 || n < 1 || l < 1 || l > kMaxL) return 0;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
+  uint64_t part = std::max(gemm_an_scratch_bytes(rows, n, Lp), gemm_at_scratch_bytes(rows, n, Lp, rows));
+  return 2 * panel + align_up(part);
+}
+
+int brsvd_gemm_an(const float* A, int64_t lda, int64_t rows, int64_t n, const float* X, int32_t l, float* Y,
+                  void* scratch, uint64_t scratch_bytes, void* stream) {
+  if (!A || !X || !Y || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
+  if (!scratch || scratch_bytes < brsvd_gemm_scratch_bytes(rows, n, l)) return BRSVD_ERR_BUDGET;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
+  float* Xp = (float*)scratch;
+  char* part = (char*)scratch + 2 * panel;
+  hipStream_t s = (hipStream_t)stream;
+  BRSVD_TRY(pad_panel(X, n, l, Xp, Lp, s));
+  return gemm_an(A, lda, rows, n, Xp, Lp, Y, l, l, part, scratch_bytes - 2 * panel, s);
+}
+
+int brsvd_gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int32_t l, float* Z,
+                  int32_t accumulate, void* scratch, uint64_t scratch_bytes, void* stream) {
+  if (!A || !Q || !Z || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
+  if (!scratch || scratch_bytes < brsvd_gemm_scratch_bytes(rows, n, l)) return BRSVD_ERR_BUDGET;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
+  float* Qp = (float*)scratch;
+  float* Zp = (float*)((char*)scratch + panel);
+  char* part = (char*)scratch + 2 * panel;
+  hipStream_t s = (hipStream_t)stream;
+  BRSVD_TRY(pad_panel(Q, rows, l, Qp, Lp, s));
+  BRSVD_TRY(gemm_at(A, lda, rows, n, Qp, Lp, Zp, false, rows, part, scratch_bytes - 2 * panel, s));
+  return unpad_panel(Zp, n, Lp, l, Z, accumulate != 0, s);
+}
+
+int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int32_t* fallback_taken,
+               void* stream) {
+  if (!P || rows < 1 || l < 1 || l > kMaxL || rows < l) return BRSVD_ERR_ARG;
+  if (method < BRSVD_ORTH_AUTO || method > BRSVD_ORTH_TSQR) return BRSVD_ERR_ARG;
+  if (fallback_taken) *fallback_taken = 0;
+  const int Lp = padded_l(l);
+  hipStream_t s = (hipStream_t)stream;
+  const uint64_t panel = align_up((uint64_t)rows * Lp * 4);
+  const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8), sq4 = align_up((uint64_t)Lp * Lp * 4);
+  const int chunks = (int)orth_gram_chunks(rows);
+  const uint64_t gs = align_up(gemm_an_scratch_bytes(rows, Lp, Lp));
+  const uint64_t tb = align_up(tsqr_work_bytes(rows, Lp));
+  const uint64_t total = 2 * panel + (uint64_t)chunks * sq8 + 5 * sq8 + sq4 + 256 + gs + tb;
+  char* buf = nullptr;
+  if (hipMalloc((void**)&buf, total) != hipSuccess) return BRSVD_ERR_ALLOC;
+  int status = BRSVD_OK;
+  do {
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { char* p = buf + off; off += bytes; return p; };
+    float* P0 = (float*)take(panel);
+    float* P1 = (float*)take(panel);
+    OrthWork w;
+    w.gram_part = (double*)take((uint64_t)chunks * sq8);
+    w.gram_chunks_max = chunks;
+    w.G = (double*)take(sq8); w.R[0] = (double*)take(sq8); w.R[1] = (double*)take(sq8);
+    w.Xinv = (double*)take(sq8);
+    double* Rtot = (double*)take(sq8);
+    w.Rinv = (float*)take(sq4);
+    w.flags = (int*)take(256);
+    w.gemm_scratch = take(gs); w.gemm_scratch_bytes = gs;
+    w.tsqr_work = take(tb); w.tsqr_bytes = tb;
+    if (hipMemsetAsync(buf, 0, total, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+    int m_now = method;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+      float* res = nullptr;
+      if ((status = pad_panel(P, rows, l, P0, Lp, s)) != BRSVD_OK) break;
+      if (hipMemsetAsync(w.flags, 0, 256, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+      if ((status = orth_panel(P0, P1, rows, l, Lp, m_now, w, Rtot, &res, s)) != BRSVD_OK) break;
+      int flag = 0;
+      if (hipMemcpyAsync(&flag, w.flags, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+          hipStreamSynchronize(s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+      if (flag == 0) {
+        if ((status = unpad_panel(res, rows, Lp, l, P, false, s)) != BRSVD_OK) break;
+        if (R) {
+          if (hipMemcpy2DAsync(R, (size_t)l * 8, Rtot, (size_t)Lp * 8, (size_t)l * 8, (size_t)l,
+                               hipMemcpyDeviceToDevice, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+        }
+        if (hipStreamSynchronize(s) != hipSuccess) status = BRSVD_ERR_HIP;
+        break;
+      }
+      if (m_now != BRSVD_ORTH_AUTO) { status = BRSVD_ERR_ORTH_BREAKDOWN; break; }
+      m_now = BRSVD_ORTH_TSQR;
+      if (fallback_taken) *fallback_taken = 1;
+    }
+  } while (0);
+  (void)hipStreamSynchronize(s);
+  (void)hipFree(buf);
+  return status;
+}
+
+int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps, void* stream) {
+  if (!R || !S || !Ur || !Vr || l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
+  const int Lp = padded_l(l);
+  hipStream_t s = (hipStream_t)stream;
+  const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8);
+  const uint64_t total = 2 * sq8 + align_up((uint64_t)3 * Lp * 8) + 256;
+  char* buf = nullptr;
+  if (hipMalloc((void**)&buf, total) != hipSuccess) return BRSVD_ERR_ALLOC;
+  SvdWork w;
+  w.W = (double*)buf;
+  w.J = (double*)(buf + sq8);
+  w.sig = (double*)(buf + 2 * sq8);
+  w.info = (int*)(buf + 2 * sq8 + align_up((uint64_t)3 * Lp * 8));
+  int status = small_svd(R, l, l, Lp, w, nullptr, S, nullptr, nullptr, nullptr, Ur, Vr, s);
+  int info[2] = {0, 0};
+  if (status == BRSVD_OK) {
+    if (hipMemcpyAsync(info, w.info, sizeof(info), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      status = BRSVD_ERR_HIP;
+  }
+  (void)hipStreamSynchronize(s);
+  (void)hipFree(buf);
+  if (status == BRSVD_OK) {
+    if (sweeps) *sweeps = info[0];
+    if (!info[1]) status = BRSVD_ERR_SVD_NOCONV;
+  }
+  return status;
+}
+
+}  // extern "C"

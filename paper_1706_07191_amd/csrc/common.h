@@ -1,0 +1,113 @@
+// Internal declarations shared by the HIP translation units of libbrsvd (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "brsvd.h"
+
+namespace brsvd {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxL = 512;       // largest sketch width l = k + p
+constexpr int kTile = 16;        // MFMA tile edge (v_mfma_f32_16x16x4_f32)
+
+// Padded panel width: every internal thin panel is rows x Lp, row-major, Lp a multiple of 16,
+// columns l..Lp-1 kept at zero, so the GEMM kernels need no column masking on their inputs.
+inline int padded_l(int l) { return (l + kTile - 1) / kTile * kTile; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+#define BRSVD_HIP_TRY(expr)                         \
+  do {                                              \
+    hipError_t e__ = (expr);                        \
+    if (e__ != hipSuccess) return BRSVD_ERR_HIP;    \
+  } while (0)
+
+#define BRSVD_TRY(expr)                 \
+  do {                                  \
+    int s__ = (expr);                   \
+    if (s__ != BRSVD_OK) return s__;    \
+  } while (0)
+
+// ---- thin-panel GEMMs (gemm_thin.hip) ------------------------------------------------------
+// Optional pair of events recorded immediately around the MFMA kernel launch(es) of one call
+// (the split-sum kernel that may follow is outside), for per-kernel timing.
+struct KernelEvents {
+  hipEvent_t start, stop;
+};
+
+// Y (rows x ncols, ldy) = A (rows x K, lda) * X (K x Lp padded panel, ldx = Lp).
+// scratch holds split-K partial sums when the launch is split along K.
+uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp);
+int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp,
+            float* Y, int64_t ldy, int ncols, void* scratch, uint64_t scratch_bytes,
+            hipStream_t stream, const KernelEvents* ev = nullptr);
+
+// Z (n x Lp padded panel) (+)= A^T * Q; A is rows x n (lda), Q is rows x Lp.  The row range is
+// cut at multiples of block_rows (the row blocks of the method) and each block into equal
+// sub-ranges; partial panels are summed in row order, so the result does not depend on timing.
+uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows);
+int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp,
+            float* Z, bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes,
+            hipStream_t stream, const KernelEvents* ev = nullptr);
+
+// dst (rows x Lp, zero padded) <- src (rows x l dense)
+int pad_panel(const float* src, int64_t rows, int l, float* dst, int Lp, hipStream_t stream);
+// dst (rows x l dense) (+)= src (rows x Lp) restricted to the first l columns
+int unpad_panel(const float* src, int64_t rows, int Lp, int l, float* dst, bool accumulate,
+                hipStream_t stream);
+// dst (l x rows, ld = rows) <- transpose of src (rows x Lp) restricted to the first l columns
+int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, hipStream_t stream);
+
+// ---- orthonormalisation (orth.hip, tsqr.hip) -----------------------------------------------
+struct OrthWork {
+  double* gram_part;   // gram_chunks_max x Lp x Lp partial Gram matrices
+  int gram_chunks_max;
+  double* G;           // Lp x Lp
+  double* R[2];        // upper-triangular factors of the two CholeskyQR sweeps (stride Lp)
+  double* Xinv;        // Lp x Lp fp64 scratch for R^-1
+  float* Rinv;         // Lp x Lp fp32 zero-padded inverse factor (right operand of the apply GEMM)
+  int* flags;          // device: [0] = breakdown flag (0 = none, else 1 + column)
+  void* gemm_scratch;
+  uint64_t gemm_scratch_bytes;
+  void* tsqr_work;     // TSQR scratch
+  uint64_t tsqr_bytes;
+};
+uint64_t orth_gram_chunks(int64_t rows);
+uint64_t tsqr_work_bytes(int64_t rows, int Lp);
+// Orthonormalises the columns of P (rows x Lp padded panel, rows >= l).  tmp is a second
+// rows x Lp buffer; *result is set to whichever of P / tmp holds the orthonormal panel.
+// Rtot (stride Lp, fp64, may be null) receives the triangular factor with P_in = Q * Rtot.
+// Asynchronous: a CholeskyQR breakdown is only reported through w.flags[0] on the device.
+int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, OrthWork& w,
+               double* Rtot, float** result, hipStream_t stream);
+
+// ---- small SVD (small_svd.hip) -------------------------------------------------------------
+struct SvdWork {
+  double* W;     // Lp x Lp rows being orthogonalised
+  double* J;     // Lp x Lp accumulated rotations (transposed)
+  double* sig;   // 3 * Lp
+  int* info;     // device: [0] sweeps, [1] converged
+};
+// R (l x l fp64, stride ldr): R = Ur diag(S) Vr^T.  Writes S (descending) as fp64 and/or fp32,
+// the fp32 zero-padded (Lp x Lp) operands XV = Vr and XU = Ur used by the lifts, and optional
+// dense fp64 l x l Ur / Vr.  Skips the work when *breakdown_flag != 0.
+int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag,
+              double* S, float* S32, float* XV, float* XU, double* Ur, double* Vr,
+              hipStream_t stream);
+
+// ---- robust-PCA elementwise kernels (rpca.hip) ---------------------------------------------
+// scal (device doubles): [0] max |M_ij|, [1] ||M||_F^2, [2] residual ||M-L-S||_F^2
+int rpca_norms(const float* M, int64_t count, double* scal, hipStream_t stream);
+// Y0 = M / J, S0 = 0, X0 = M - S0 + Y0/mu0
+int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y, float* S, float* X,
+              hipStream_t stream);
+// Fused update after the SVD of X_i: L = U diag(shrink(s, 1/mu)) V^T (contraction over l),
+// S = shrink(M - L + Y/mu, lambda/mu), Y += mu (M - L - S), residual += ||M-L-S||_F^2, and the
+// next SVD input X = M - S + Y/(rho*mu).  U is m x l (ld l), Vt is l x n (ld n).
+int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n,
+                int l, float mu, float lambda, float rho, float* L, float* S, float* Y, float* X,
+                double* resid2, hipStream_t stream);
+
+}  // namespace brsvd

@@ -1,0 +1,592 @@
+// Thin-panel GEMMs of the randomized range finder on fp32 MFMA (gfx950, wave64).
+//
+//   gemm_an:  Y_I = A_I * X        sketch Y = A*Omega and the power step Y = A*W
+//                                  (Alg. 1 step 2, Alg. 2 line 4, Eq. (4) right-to-left order)
+//   gemm_at:  Z  += A_I^T * Q_I    power half step Z = A^T*Q and the projection B^T = A^T*Q
+//                                  (Alg. 1 step 4, Alg. 2 line 9)
+//
+// Both read each element of the row block A_I exactly once, straight from HBM into the MFMA
+// A-operand registers (no LDS round trip for A), while the thin panel (X or Q) is staged
+// through a double-buffered LDS tile shared by the waves of a workgroup.
+//
+// MFMA used: v_mfma_f32_16x16x4_f32.  Operand layout (lane = 16*g + r, g = 0..3, r = 0..15):
+//   A operand: lane holds a[i = r][k = g];  B operand: lane holds b[k = g][j = r];
+//   D: lane holds d[i = 4*g + v][j = r] in component v = 0..3.
+// Because the contraction index may be visited in any order, a lane's float4 of four
+// consecutive k (gemm_an) or four consecutive columns (gemm_at) feeds four MFMAs directly.
+#include "common.h"
+
+namespace brsvd {
+
+__device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+constexpr int kMaxNT = 17;   // n-tiles (of 16 columns) one launch keeps in registers
+
+// --------------------------------------------------------------------------------------------
+// gemm_an
+// --------------------------------------------------------------------------------------------
+// Workgroup: WAVES waves, wave w owns rows [row0 + w*MT*16, +MT*16) and all NT*16 columns.
+// blockIdx.x = row tile, blockIdx.y = split of the contraction range [0, K).
+template <int NT, int MT, int WAVES, int KC, bool VEC>
+__global__ void __launch_bounds__(WAVES * 64)
+k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
+          const float* __restrict__ X, int ldx,
+          float* __restrict__ Y, int64_t ldy, int ncols, int64_t split_stride, int chunks_per_split) {
+  extern __shared__ float lds[];
+  constexpr int NTHREADS = WAVES * 64;
+  constexpr int LD = NT * 16 + 4;          // +4: the four k-groups of a wave hit distinct banks
+  constexpr int KS = KC / 16;              // 16-wide k steps per chunk
+  constexpr int ROWF4 = NT * 4;
+  constexpr int F4 = KC * ROWF4;
+  constexpr int XPT = (F4 + NTHREADS - 1) / NTHREADS;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int row0 = blockIdx.x * (WAVES * MT * 16) + wave * (MT * 16);
+  const int kbeg = blockIdx.y * chunks_per_split * KC;
+  const int kend = min(K, kbeg + chunks_per_split * KC);
+  const int nchunks = (kend - kbeg + KC - 1) / KC;
+
+  const float* ap[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int row = min(row0 + mt * 16 + r, rows - 1);
+    ap[mt] = A + (int64_t)row * lda;
+  }
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  floatx4 xr[XPT];
+  floatx4 a_cur[MT][KS], a_nxt[MT][KS];
+
+#define LOAD_X(kbase)                                                              \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    int k = (kbase) + kr;                                                          \
+    floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};                                       \
+    if (idx < F4 && k < kend) v = *(const floatx4*)(X + (int64_t)k * ldx + c4 * 4); \
+    xr[i] = v;                                                                     \
+  }
+#define STORE_X(buf)                                                               \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    if (idx < F4) *(floatx4*)((buf) + kr * LD + c4 * 4) = xr[i];                   \
+  }
+#define LOAD_A(dst, kbase)                                                         \
+  _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                \
+  _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                 \
+    int k = (kbase) + s * 16 + 4 * g;                                              \
+    if (VEC) {                                                                     \
+      k = min(k, K - 4);                                                           \
+      dst[mt][s] = *(const floatx4*)(ap[mt] + k);                                  \
+    } else {                                                                       \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
+        dst[mt][s][j] = ap[mt][min(k + j, K - 1)];                                 \
+    }                                                                              \
+  }
+
+  float* buf0 = lds;
+  float* buf1 = lds + KC * LD;
+
+  if (nchunks > 0) {
+    LOAD_X(kbeg);
+    LOAD_A(a_cur, kbeg);
+    STORE_X(buf0);
+  }
+  __syncthreads();
+
+  for (int c = 0; c < nchunks; ++c) {
+    const float* cur = (c & 1) ? buf1 : buf0;
+    float* nxt = (c & 1) ? buf0 : buf1;
+    const bool more = (c + 1 < nchunks);
+    if (more) {
+      LOAD_X(kbeg + (c + 1) * KC);
+      LOAD_A(a_nxt, kbeg + (c + 1) * KC);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float* brow = cur + (s * 16 + 4 * g + j) * LD + r;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          float b = brow[nt * 16];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(a_cur[mt][s][j], b, acc[mt][nt]);
+        }
+      }
+    }
+    if (more) {
+      STORE_X(nxt);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a_cur[mt][s] = a_nxt[mt][s];
+    }
+    __syncthreads();
+  }
+#undef LOAD_X
+#undef STORE_X
+#undef LOAD_A
+
+  float* Yo = Y + (int64_t)blockIdx.y * split_stride;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      int row = row0 + mt * 16 + 4 * g + v;
+      if (row < rows) {
+        float* yr = Yo + (int64_t)row * ldy;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          int col = nt * 16 + r;
+          if (col < ncols) yr[col] = acc[mt][nt][v];
+        }
+      }
+    }
+}
+
+// --------------------------------------------------------------------------------------------
+// gemm_at
+// --------------------------------------------------------------------------------------------
+// Workgroup: WAVES waves, wave w owns MT*16 consecutive columns of A (= rows of Z) and all NT*16
+// panel columns; blockIdx.x = column tile, blockIdx.y = (row block, sub-range) of the contraction.
+// A lane loads MT consecutive columns of one row; component j of that load is the A operand of
+// m-tile j, which therefore holds the interleaved columns {cw + MT*i + j : i = 0..15}.
+template <int NT, int MT, int WAVES, int KC, bool VEC>
+__global__ void __launch_bounds__(WAVES * 64)
+k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
+          const float* __restrict__ Q, int ldq,
+          float* __restrict__ Zpart, int ldz, int64_t split_stride,
+          int64_t block_rows, int sub, int rows_per_sub) {
+  extern __shared__ float lds[];
+  constexpr int NTHREADS = WAVES * 64;
+  constexpr int LD = NT * 16 + ((16 - (NT * 16) % 64) + 64) % 64;   // LD % 64 == 16
+  constexpr int KS = KC / 4;               // 4-row k steps per chunk
+  constexpr int ROWF4 = NT * 4;
+  constexpr int F4 = KC * ROWF4;
+  constexpr int XPT = (F4 + NTHREADS - 1) / NTHREADS;
+  typedef float vecT __attribute__((ext_vector_type(MT)));
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int cw = blockIdx.x * (WAVES * MT * 16) + wave * (MT * 16);
+  const int blk = blockIdx.y / sub, si = blockIdx.y - blk * sub;
+  const int64_t bstart = (int64_t)blk * block_rows;
+  const int64_t rbeg = bstart + (int64_t)si * rows_per_sub;
+  int64_t rend = bstart + min((int64_t)(si + 1) * rows_per_sub, block_rows);
+  rend = min(rend, rows_total);
+  const int nchunks = rbeg < rend ? (int)((rend - rbeg + KC - 1) / KC) : 0;
+
+  int col[MT];
+  if (VEC) {
+    col[0] = min(cw + MT * r, n - MT);
+  } else {
+#pragma unroll
+    for (int j = 0; j < MT; ++j) col[j] = min(cw + MT * r + j, n - 1);
+  }
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int j = 0; j < MT; ++j)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  floatx4 xr[XPT];
+  vecT a_cur[KS], a_nxt[KS];
+
+#define LOAD_Q(rbase)                                                              \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    int64_t row = (rbase) + kr;                                                    \
+    floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};                                       \
+    if (idx < F4 && row < rend) v = *(const floatx4*)(Q + row * ldq + c4 * 4);     \
+    xr[i] = v;                                                                     \
+  }
+#define STORE_Q(buf)                                                               \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    if (idx < F4) *(floatx4*)((buf) + kr * LD + c4 * 4) = xr[i];                   \
+  }
+#define LOAD_A(dst, rbase)                                                         \
+  _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                 \
+    int64_t row = min((rbase) + s * 4 + g, rows_total - 1);                        \
+    const float* p = A + row * lda;                                                \
+    if (VEC) {                                                                     \
+      dst[s] = *(const vecT*)(p + col[0]);                                         \
+    } else {                                                                       \
+      _Pragma("unroll") for (int j = 0; j < MT; ++j) dst[s][j] = p[col[j]];        \
+    }                                                                              \
+  }
+
+  float* buf0 = lds;
+  float* buf1 = lds + KC * LD;
+
+  if (nchunks > 0) {
+    LOAD_Q(rbeg);
+    LOAD_A(a_cur, rbeg);
+    STORE_Q(buf0);
+  }
+  __syncthreads();
+
+  for (int c = 0; c < nchunks; ++c) {
+    const float* cur = (c & 1) ? buf1 : buf0;
+    float* nxt = (c & 1) ? buf0 : buf1;
+    const bool more = (c + 1 < nchunks);
+    if (more) {
+      LOAD_Q(rbeg + (int64_t)(c + 1) * KC);
+      LOAD_A(a_nxt, rbeg + (int64_t)(c + 1) * KC);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const float* brow = cur + (s * 4 + g) * LD + r;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        float b = brow[nt * 16];
+#pragma unroll
+        for (int j = 0; j < MT; ++j) acc[j][nt] = mfma16(a_cur[s][j], b, acc[j][nt]);
+      }
+    }
+    if (more) {
+      STORE_Q(nxt);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) a_cur[s] = a_nxt[s];
+    }
+    __syncthreads();
+  }
+#undef LOAD_Q
+#undef STORE_Q
+#undef LOAD_A
+
+  float* Zo = Zpart + (int64_t)blockIdx.y * split_stride;
+#pragma unroll
+  for (int j = 0; j < MT; ++j)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      int zr = cw + MT * (4 * g + v) + j;
+      if (zr < n) {
+        float* zp = Zo + (int64_t)zr * ldz + r;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) zp[nt * 16] = acc[j][nt][v];
+      }
+    }
+}
+
+// out[row][col] = (accumulate ? out : 0) + sum_s part[s][row][col], summed in split order.
+template <typename T>
+__global__ void k_reduce_splits(const T* __restrict__ part, int nsplit, int64_t split_stride,
+                                int64_t rows, int ncols, int64_t ldi, T* __restrict__ out,
+                                int64_t ldo, int accumulate) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * ncols) return;
+  int64_t row = idx / ncols;
+  int col = (int)(idx - row * ncols);
+  const T* p = part + row * ldi + col;
+  T s = accumulate ? out[row * ldo + col] : T(0);
+  for (int i = 0; i < nsplit; ++i) s += p[(int64_t)i * split_stride];
+  out[row * ldo + col] = s;
+}
+
+__global__ void k_pad_panel(const float* __restrict__ src, int64_t rows, int l, float* __restrict__ dst,
+                            int Lp) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * Lp) return;
+  int64_t row = idx / Lp;
+  int col = (int)(idx - row * Lp);
+  dst[idx] = col < l ? src[row * l + col] : 0.f;
+}
+
+__global__ void k_unpad_panel(const float* __restrict__ src, int64_t rows, int Lp, int l,
+                              float* __restrict__ dst, int accumulate) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * l) return;
+  int64_t row = idx / l;
+  int col = (int)(idx - row * l);
+  float v = src[row * Lp + col];
+  dst[idx] = accumulate ? dst[idx] + v : v;
+}
+
+// dst[c][row] = src[row][c], c < l; 32x32 tiles through LDS.
+__global__ void k_transpose_panel(const float* __restrict__ src, int64_t rows, int Lp, int l,
+                                  float* __restrict__ dst) {
+  __shared__ float tile[32][33];
+  int64_t r0 = (int64_t)blockIdx.x * 32;
+  int c0 = blockIdx.y * 32;
+  int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 256 threads: ty = 0..7
+  for (int i = ty; i < 32; i += 8) {
+    int64_t row = r0 + i;
+    int col = c0 + tx;
+    tile[i][tx] = (row < rows && col < Lp) ? src[row * Lp + col] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    int col = c0 + i;
+    int64_t row = r0 + tx;
+    if (col < l && row < rows) dst[(int64_t)col * rows + row] = tile[tx][i];
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// Host-side launch logic
+// --------------------------------------------------------------------------------------------
+static int target_workgroups() {
+  static int t = [] {
+    const char* e = getenv("BRSVD_TARGET_WGS");
+    int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 1024;
+  }();
+  return t;
+}
+
+struct NGroups {
+  int groups, nt;   // column groups per launch sequence, n-tiles per group
+};
+static NGroups column_groups(int Lp) {
+  int nt_total = Lp / 16;
+  int groups = (nt_total + kMaxNT - 1) / kMaxNT;
+  int nt = (nt_total + groups - 1) / groups;
+  return {groups, nt};
+}
+
+// ---- gemm_an ----
+struct AnCfg {
+  int mt, waves, kc;
+};
+static AnCfg an_cfg(int nt) {
+  if (nt <= 8) return {2, 4, 64};
+  return {2, 4, 32};
+}
+struct AnPlan {
+  int row_tiles, ksplit, chunks_per_split;
+};
+static AnPlan an_plan(int64_t rows, int64_t K, int nt) {
+  AnCfg c = an_cfg(nt);
+  AnPlan p;
+  p.row_tiles = (int)ceil_div(rows, c.waves * c.mt * 16);
+  int nchunks = (int)ceil_div(K, c.kc);
+  int want = (int)ceil_div(target_workgroups(), p.row_tiles);
+  want = want < 1 ? 1 : (want > nchunks ? nchunks : want);
+  p.chunks_per_split = (int)ceil_div(nchunks, want);
+  p.ksplit = (int)ceil_div(nchunks, p.chunks_per_split);
+  return p;
+}
+
+uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp) {
+  NGroups ng = column_groups(Lp);
+  AnPlan p = an_plan(rows, K, ng.nt);
+  return p.ksplit > 1 ? (uint64_t)p.ksplit * rows * Lp * sizeof(float) : 0;
+}
+
+template <int NT, int MT, int WAVES, int KC, bool VEC>
+static int launch_an_inst(const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
+                          float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
+                          hipStream_t stream) {
+  auto kern = k_gemm_an<NT, MT, WAVES, KC, VEC>;
+  constexpr int lds_bytes = 2 * KC * (NT * 16 + 4) * (int)sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      lds_bytes));
+    attr_set = true;
+  }
+  dim3 grid(p.row_tiles, p.ksplit);
+  hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds_bytes, stream, A, lda, rows, K, X, ldx, Y, ldy,
+                     ncols, split_stride, p.chunks_per_split);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+template <int NT>
+static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
+                        float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
+                        hipStream_t stream) {
+  constexpr int KC = NT <= 8 ? 64 : 32;
+  if (vec)
+    return launch_an_inst<NT, 2, 4, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
+  return launch_an_inst<NT, 2, 4, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
+}
+
+#define BRSVD_NT_SWITCH(nt, CALL)                                                      \
+  switch (nt) {                                                                        \
+    case 1: return CALL(1); case 2: return CALL(2); case 3: return CALL(3);            \
+    case 4: return CALL(4); case 5: return CALL(5); case 6: return CALL(6);            \
+    case 7: return CALL(7); case 8: return CALL(8); case 9: return CALL(9);            \
+    case 10: return CALL(10); case 11: return CALL(11); case 12: return CALL(12);      \
+    case 13: return CALL(13); case 14: return CALL(14); case 15: return CALL(15);      \
+    case 16: return CALL(16); case 17: return CALL(17);                                \
+    default: return BRSVD_ERR_ARG;                                                     \
+  }
+
+static int launch_an(int nt, bool vec, const float* A, int64_t lda, int rows, int K, const float* X,
+                     int ldx, float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
+                     hipStream_t stream) {
+#define CALL(N) launch_an_nt<N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream)
+  BRSVD_NT_SWITCH(nt, CALL)
+#undef CALL
+}
+
+static int reduce_f32(const float* part, int nsplit, int64_t split_stride, int64_t rows, int ncols,
+                      int64_t ldi, float* out, int64_t ldo, bool accumulate, hipStream_t stream) {
+  int64_t total = rows * ncols;
+  if (total == 0) return BRSVD_OK;
+  hipLaunchKernelGGL(k_reduce_splits<float>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                     part, nsplit, split_stride, rows, ncols, ldi, out, ldo, accumulate ? 1 : 0);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp, float* Y,
+            int64_t ldy, int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream,
+            const KernelEvents* ev) {
+  if (rows <= 0 || K <= 0 || Lp <= 0 || Lp % 16 || ncols <= 0 || ncols > Lp) return BRSVD_ERR_ARG;
+  if (rows > INT32_MAX || K > INT32_MAX) return BRSVD_ERR_ARG;
+  NGroups ng = column_groups(Lp);
+  AnPlan p = an_plan(rows, K, ng.nt);
+  const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && K >= 4 && (K % 4 == 0);
+  if (p.ksplit > 1 && scratch_bytes < (uint64_t)p.ksplit * rows * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
+  for (int gi = 0; gi < ng.groups; ++gi) {
+    int c0 = gi * ng.nt * 16;
+    int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
+    if (nt <= 0) break;
+    int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group
+    if (p.ksplit == 1) {
+      if (nc <= 0) continue;
+      BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, 0, p, stream));
+    } else {
+      float* part = (float*)scratch;
+      BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, part + c0, Lp, nt * 16,
+                          rows * Lp, p, stream));
+    }
+  }
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
+  if (p.ksplit > 1)
+    BRSVD_TRY(reduce_f32((const float*)scratch, p.ksplit, rows * Lp, rows, ncols, Lp, Y, ldy, false, stream));
+  return BRSVD_OK;
+}
+
+// ---- gemm_at ----
+struct AtPlan {
+  int mt, col_tiles, nblocks, sub, rows_per_sub, nsplit;
+};
+static int at_mt(int nt) { return nt <= 8 ? 4 : 2; }
+constexpr int kAtWaves = 4;
+constexpr int kAtKC = 32;
+
+static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
+  AtPlan p;
+  p.mt = at_mt(nt);
+  p.col_tiles = (int)ceil_div(n, kAtWaves * p.mt * 16);
+  if (block_rows <= 0 || block_rows > rows) block_rows = rows;
+  p.nblocks = (int)ceil_div(rows, block_rows);
+  int want = (int)ceil_div(target_workgroups(), (int64_t)p.col_tiles * p.nblocks);
+  int max_sub = (int)ceil_div(block_rows, kAtKC);
+  want = want < 1 ? 1 : (want > max_sub ? max_sub : want);
+  int64_t rps = ceil_div(block_rows, want);
+  rps = ceil_div(rps, kAtKC) * kAtKC;
+  p.rows_per_sub = (int)rps;
+  p.sub = (int)ceil_div(block_rows, rps);
+  p.nsplit = p.nblocks * p.sub;
+  return p;
+}
+
+uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows) {
+  NGroups ng = column_groups(Lp);
+  AtPlan p = at_plan(rows, n, ng.nt, block_rows);
+  return (uint64_t)p.nsplit * n * Lp * sizeof(float);
+}
+
+template <int NT, int MT, bool VEC>
+static int launch_at_inst(const float* A, int64_t lda, int64_t rows, int n, const float* Q, int ldq,
+                          float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
+                          hipStream_t stream) {
+  auto kern = k_gemm_at<NT, MT, kAtWaves, kAtKC, VEC>;
+  constexpr int LD = NT * 16 + ((16 - (NT * 16) % 64) + 64) % 64;
+  constexpr int lds_bytes = 2 * kAtKC * LD * (int)sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      lds_bytes));
+    attr_set = true;
+  }
+  dim3 grid(p.col_tiles, p.nsplit);
+  hipLaunchKernelGGL(kern, grid, dim3(kAtWaves * 64), lds_bytes, stream, A, lda, rows, n, Q, ldq, Zp, ldz,
+                     split_stride, block_rows, p.sub, p.rows_per_sub);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+template <int NT>
+static int launch_at_nt(bool vec, const float* A, int64_t lda, int64_t rows, int n, const float* Q, int ldq,
+                        float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
+                        hipStream_t stream) {
+  constexpr int MT = NT <= 8 ? 4 : 2;
+  if (vec)
+    return launch_at_inst<NT, MT, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
+  return launch_at_inst<NT, MT, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
+}
+
+static int launch_at(int nt, bool vec, const float* A, int64_t lda, int64_t rows, int n, const float* Q,
+                     int ldq, float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
+                     hipStream_t stream) {
+#define CALL(N) launch_at_nt<N>(vec, A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream)
+  BRSVD_NT_SWITCH(nt, CALL)
+#undef CALL
+}
+
+int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp, float* Z,
+            bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream,
+            const KernelEvents* ev) {
+  if (rows <= 0 || n <= 0 || Lp <= 0 || Lp % 16) return BRSVD_ERR_ARG;
+  if (n > INT32_MAX) return BRSVD_ERR_ARG;
+  if (block_rows <= 0 || block_rows > rows) block_rows = rows;
+  NGroups ng = column_groups(Lp);
+  AtPlan p = at_plan(rows, n, ng.nt, block_rows);
+  if (p.nsplit > 65535) return BRSVD_ERR_ARG;
+  if (scratch_bytes < (uint64_t)p.nsplit * n * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
+  const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && (n % 4 == 0) && n >= 4;
+  float* part = (float*)scratch;
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
+  for (int gi = 0; gi < ng.groups; ++gi) {
+    int c0 = gi * ng.nt * 16;
+    int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
+    if (nt <= 0) break;
+    BRSVD_TRY(launch_at(nt, vec, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
+  }
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
+  return reduce_f32(part, p.nsplit, n * Lp, n, Lp, Lp, Z, Lp, accumulate, stream);
+}
+
+int pad_panel(const float* src, int64_t rows, int l, float* dst, int Lp, hipStream_t stream) {
+  int64_t total = rows * Lp;
+  hipLaunchKernelGGL(k_pad_panel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, l, dst, Lp);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int unpad_panel(const float* src, int64_t rows, int Lp, int l, float* dst, bool accumulate, hipStream_t stream) {
+  int64_t total = rows * l;
+  hipLaunchKernelGGL(k_unpad_panel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, Lp, l,
+                     dst, accumulate ? 1 : 0);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, hipStream_t stream) {
+  dim3 grid((unsigned)ceil_div(rows, 32), (unsigned)ceil_div(l, 32));
+  hipLaunchKernelGGL(k_transpose_panel, grid, dim3(256), 0, stream, src, rows, Lp, l, dst);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+}  // namespace brsvd

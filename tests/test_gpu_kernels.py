@@ -1,0 +1,117 @@
+"""Kernel-level parity on the GPU, through the C ABI, against the fp64 oracle steps."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1706_07191_amd as B
+from oracle import brsvd_oracle as O
+from oracle import loops
+from paper_1706_07191_amd import synth
+from tests.gpu_util import EPS32, need_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _bound(absA, absX, K):
+    # fp32 accumulation of K products: error <= c * sqrt(K) * eps * sum |a||x| (random-walk model, c = 8)
+    return 8.0 * np.sqrt(K) * EPS32 * (absA @ absX) + 1e-30
+
+
+GEMM_SHAPES = [  # rows, n, l
+    (1000, 1000, 30),     # C1-like, ragged rows (1000 = 7*128 + 104)
+    (77, 1003, 20),       # unaligned n -> scalar load path, fewer rows than a tile
+    (513, 2048, 110),     # C2 width, 7 column tiles
+    (300, 1024, 272),     # C3 width, 17 column tiles
+    (260, 520, 300),      # two column groups
+    (64, 8, 1),           # degenerate widths
+    (40, 36, 36),         # l == n
+]
+
+
+@pytest.mark.parametrize("rows,n,l", GEMM_SHAPES)
+def test_gemm_an_matches_oracle(rows, n, l):
+    dev = need_gpu()
+    print(f"[case] gemm_an rows={rows} n={n} l={l}", flush=True)
+    A = synth.gaussian(rows, n, 101).numpy()
+    X = synth.gaussian(n, l, 102).numpy()
+    Y = B.brsvd_gemm_an(torch.from_numpy(A).to(dev), torch.from_numpy(X).to(dev))
+    torch.cuda.synchronize()
+    ref = O.a_times(A, X.astype(np.float64), b=128)
+    d = np.abs(Y.double().cpu().numpy() - ref)
+    assert np.all(d <= _bound(np.abs(A).astype(np.float64), np.abs(X).astype(np.float64), n))
+
+
+@pytest.mark.parametrize("rows,n,l", GEMM_SHAPES)
+def test_gemm_at_matches_oracle(rows, n, l):
+    dev = need_gpu()
+    print(f"[case] gemm_at rows={rows} n={n} l={l}", flush=True)
+    A = synth.gaussian(rows, n, 103).numpy()
+    Q = synth.gaussian(rows, l, 104).numpy()
+    Z = B.brsvd_gemm_at(torch.from_numpy(A).to(dev), torch.from_numpy(Q).to(dev))
+    torch.cuda.synchronize()
+    ref = O.at_times(A, Q.astype(np.float64), b=100)
+    d = np.abs(Z.double().cpu().numpy() - ref)
+    assert np.all(d <= _bound(np.abs(A.T).astype(np.float64), np.abs(Q).astype(np.float64), rows))
+    # accumulate flag: Z += A^T Q
+    Z2 = B.brsvd_gemm_at(torch.from_numpy(A).to(dev), torch.from_numpy(Q).to(dev), Z=Z.clone(), accumulate=True)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(Z2.double().cpu().numpy() - 2 * ref) <=
+                  2 * _bound(np.abs(A.T).astype(np.float64), np.abs(Q).astype(np.float64), rows))
+
+
+def test_gemm_with_row_stride():
+    """A given as a view with lda > n (a column slab of a wider matrix)."""
+    dev = need_gpu()
+    full = synth.gaussian(300, 1200, 105)
+    A = full[:, 100:900]
+    X = synth.gaussian(800, 30, 106)
+    Ad = full.to(dev)[:, 100:900]
+    Y = B.brsvd_gemm_an(Ad, X.to(dev))
+    ref = O.a_times(A.numpy(), X.numpy().astype(np.float64), b=0)
+    assert np.max(np.abs(Y.double().cpu().numpy() - ref)) < 1e-3
+    Q = synth.gaussian(300, 30, 107)
+    Z = B.brsvd_gemm_at(Ad, Q.to(dev))
+    refz = O.at_times(A.numpy(), Q.numpy().astype(np.float64), b=0)
+    assert np.max(np.abs(Z.double().cpu().numpy() - refz)) < 1e-3
+
+
+@pytest.mark.parametrize("rows,l,cond", [(3000, 30, 1e2), (1000, 110, 1e4), (5000, 272, 1e3), (50, 50, 10.0),
+                                          (700, 1, 1.0)])
+def test_orth_cholqr2(rows, l, cond):
+    dev = need_gpu()
+    print(f"[case] orth rows={rows} l={l} cond={cond}", flush=True)
+    s = torch.logspace(0, -np.log10(cond), l, dtype=torch.float64) if l > 1 else torch.ones(1, dtype=torch.float64)
+    mix, _ = torch.linalg.qr(synth.gaussian(l, l, 32, dtype=torch.float64))     # orthogonal: cond(P) = cond
+    P = (synth.exact_spectrum_matrix(rows, l, s, seed=31) @ mix).float()
+    Pd = P.to(dev).contiguous()
+    Qd, R, fb = B.brsvd_orth(Pd, method=B.BRSVD_ORTH_CHOLQR2, want_R=True)
+    Q = Qd.double().cpu().numpy()
+    R = R.cpu().numpy()
+    assert not fb
+    assert O.orth_defect(Q) < 5e-6
+    # same range as P and P = Q R with R upper triangular
+    P64 = P.double().numpy()
+    assert np.linalg.norm(Q @ R - P64) <= 1e-5 * np.linalg.norm(P64)
+    assert np.allclose(R, np.triu(R))
+    Qo = O.orth_householder(P64)
+    # range(Q) = range(P) up to the fp32 rounding of P R^-1, which scales with cond(P)
+    assert np.linalg.norm(Qo @ (Qo.T @ Q) - Q, 2) < 20 * EPS32 * cond
+
+
+@pytest.mark.parametrize("l", [1, 2, 7, 30, 111, 272])
+def test_small_svd_jacobi(l):
+    dev = need_gpu()
+    print(f"[case] small_svd l={l}", flush=True)
+    rng = np.random.default_rng(40 + l)
+    R = np.triu(rng.standard_normal((l, l))) * (0.97 ** np.arange(l))[None, :]
+    S, Ur, Vr, sweeps = B.brsvd_small_svd(torch.from_numpy(R).to(dev))
+    S, Ur, Vr = S.cpu().numpy(), Ur.cpu().numpy(), Vr.cpu().numpy()
+    s_ref = np.linalg.svd(R, compute_uv=False)
+    assert np.max(np.abs(S - s_ref)) < 1e-12 * s_ref[0]      # LAPACK's small values are only absolutely accurate
+    assert np.linalg.norm((Ur * S) @ Vr.T - R) < 1e-11 * np.linalg.norm(R)
+    assert np.linalg.norm(Ur.T @ Ur - np.eye(l)) < 1e-10
+    assert np.linalg.norm(Vr.T @ Vr - np.eye(l)) < 1e-10
+    assert 1 <= sweeps <= 20 or l == 1
+    if l <= 30:   # the loop-level twin agrees too
+        _, s2, _ = loops.jacobi_svd(R)
+        assert np.max(np.abs(S - s2) / s2) < 1e-8            # both Jacobi codes are relatively accurate
