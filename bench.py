@@ -112,6 +112,7 @@ def main() -> int:
                  "arith_intensity_flop_per_byte": ai})
 
     breakdown = {key: acc[key] / args.steps * 1e3 for key in acc if key.endswith("seconds")}
+    breakdown["jacobi_sweeps"] = acc["jacobi_sweeps"]
 
     cpu = None
     parity = None

@@ -301,21 +301,21 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
   BRSVD_TRY(pass_an(h, A, lda, Xn, Ym));
   {
     Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, ow, nullptr, &res, cs));
+    BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, q == 0, ow, nullptr, &res, cs));
     if (res != Ym) std::swap(Ym, Tm);
   }
   for (int it = 0; it < q; ++it) {
     BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
     {
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, false, ow, nullptr, &res, cs));
       if (res != Xn) std::swap(Xn, Tn);
     }
     BRSVD_TRY(pass_an(h, A, lda, Xn, Tm));
     std::swap(Ym, Tm);
     {
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, it == q - 1, ow, nullptr, &res, cs));
       if (res != Ym) std::swap(Ym, Tm);
     }
   }
@@ -324,7 +324,7 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
   double* Rtot = h->at<double>(h->lay.Rtot);
   {
     Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, ow, Rtot, &res, cs));
+    BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, true, ow, Rtot, &res, cs));
     if (res != Xn) std::swap(Xn, Tn);
   }
   SvdWork sw;
@@ -607,7 +607,7 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int
       float* res = nullptr;
       if ((status = pad_panel(P, rows, l, P0, Lp, s)) != BRSVD_OK) break;
       if (hipMemsetAsync(w.flags, 0, 256, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
-      if ((status = orth_panel(P0, P1, rows, l, Lp, m_now, w, Rtot, &res, s)) != BRSVD_OK) break;
+      if ((status = orth_panel(P0, P1, rows, l, Lp, m_now, true, w, Rtot, &res, s)) != BRSVD_OK) break;
       int flag = 0;
       if (hipMemcpyAsync(&flag, w.flags, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
           hipStreamSynchronize(s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }

@@ -80,8 +80,9 @@ uint64_t tsqr_work_bytes(int64_t rows, int Lp);
 // rows x Lp buffer; *result is set to whichever of P / tmp holds the orthonormal panel.
 // Rtot (stride Lp, fp64, may be null) receives the triangular factor with P_in = Q * Rtot.
 // Asynchronous: a CholeskyQR breakdown is only reported through w.flags[0] on the device.
-int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, OrthWork& w,
-               double* Rtot, float** result, hipStream_t stream);
+// final_basis = false: the panel only seeds the next power half step (one CholeskyQR sweep).
+int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bool final_basis,
+               OrthWork& w, double* Rtot, float** result, hipStream_t stream);
 
 // ---- small SVD (small_svd.hip) -------------------------------------------------------------
 struct SvdWork {

@@ -6,6 +6,8 @@
 // flag; the caller then switches to the Householder-based TSQR route (tsqr.hip).
 // The paper orthonormalises with a TSQR-based CAQR; range(P) -- all the method needs -- is the
 // same for any orthonormalisation.
+#include <algorithm>
+
 #include "common.h"
 
 namespace brsvd {
@@ -16,6 +18,7 @@ __global__ void k_reduce_splits_t(const T* __restrict__ part, int nsplit, int64_
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= count) return;
   T s = T(0);
+#pragma unroll 8
   for (int i = 0; i < nsplit; ++i) s += part[(int64_t)i * split_stride + idx];
   out[idx] = s;
 }
@@ -90,51 +93,286 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
 }
 
 // ---- Cholesky factor and its inverse ---------------------------------------------------------
-// One workgroup of 1024 threads.  On entry the upper triangle of G (Lp x Lp, stride Lp) holds
-// P^T P; on exit it holds R with G = R^T R.  X (Lp x Lp fp64 scratch) receives R^-1, which is
-// also written as the zero-padded fp32 right operand of the apply GEMM.  A pivot <= tol * its
-// original diagonal entry sets flag[0] = 1 + column index and ends the kernel.
+// One workgroup of 1024 threads; blocked right-looking factorisation G = R^T R with 16 x 16
+// blocks, then R^-1 by recursive doubling (invert the diagonal blocks, then merge neighbouring
+// blocks: inv([R11 R12; 0 R22]) = [X11, -X11 R12 X22; 0, X22]).  Everything is fp64.  For
+// l <= kCholLdsMaxL the matrix lives in LDS for the whole kernel; above that it stays in global
+// memory (L2) and only the current 16-row panel is mirrored in LDS.
+// A pivot <= tol * its original diagonal entry sets flag[0] = 1 + column and ends the kernel.
+constexpr int kNB = 16;
+constexpr int kCholLdsMaxL = 136;
+
+__device__ __forceinline__ double shfl_d(double v, int src) { return __shfl(v, src, 64); }
+
+// Wave-level Cholesky of the nb x nb diagonal block at (kb, kb): lane c (mod 16) keeps column c in
+// registers, pivots and row entries travel by shuffles.  Writes R_kk back and into Rkk (16 x 17).
+__device__ bool chol_diag_wave(double* M, int ld, int kb, int nb, const double* d0, double tol,
+                               double* Rkk, int lane) {
+  const int c = lane & 15;
+  double col[kNB];
+#pragma unroll
+  for (int i = 0; i < kNB; ++i)
+    col[i] = (i < nb && c < nb) ? (i <= c ? M[(int64_t)(kb + i) * ld + kb + c] : 0.0) : (i == c ? 1.0 : 0.0);
+  bool ok = true;
+#pragma unroll
+  for (int j = 0; j < kNB; ++j) {
+    const double d = shfl_d(col[j], j);
+    if (j < nb && !(d > tol * d0[kb + j])) ok = false;
+    const double inv = 1.0 / sqrt(d);
+    const double rj = (c >= j) ? col[j] * inv : 0.0;
+    col[j] = rj;
+#pragma unroll
+    for (int r = j + 1; r < kNB; ++r) {
+      const double rjr = shfl_d(rj, r);
+      if (c >= r) col[r] -= rjr * rj;
+    }
+  }
+  if (lane < kNB) {
+#pragma unroll
+    for (int i = 0; i < kNB; ++i) {
+      Rkk[i * 17 + c] = col[i];
+      if (i <= c && c < nb) M[(int64_t)(kb + i) * ld + kb + c] = col[i];
+    }
+  }
+  return ok;
+}
+
+// In-place inverse of the nb x nb upper-triangular diagonal block at (kb, kb), one wave.
+__device__ void inv_diag_wave(double* M, int ld, int kb, int nb, int lane) {
+  const int c = lane & 15;
+  double rc[kNB], x[kNB];
+#pragma unroll
+  for (int i = 0; i < kNB; ++i) {
+    rc[i] = (i < nb && c < nb) ? (i <= c ? M[(int64_t)(kb + i) * ld + kb + c] : 0.0) : (i == c ? 1.0 : 0.0);
+    x[i] = 0.0;
+  }
+  // x = column c of the inverse: x[c] = 1/r[c][c]; x[i] = -(sum_{t=i+1..c} r[i][t] x[t]) / r[i][i]
+#pragma unroll
+  for (int i = kNB - 1; i >= 0; --i) {
+    double s = 0.0;
+#pragma unroll
+    for (int t = i + 1; t < kNB; ++t) {
+      const double rit = shfl_d(rc[i], t);      // r[i][t] lives in lane t
+      if (t <= c) s = fma(rit, x[t], s);
+    }
+    const double rii = shfl_d(rc[i], i);
+    if (i == c) x[i] = 1.0 / rii;
+    else if (i < c) x[i] = -s / rii;
+  }
+  if (lane < kNB && c < nb) {
+#pragma unroll
+    for (int i = 0; i < kNB; ++i)
+      if (i <= c) M[(int64_t)(kb + i) * ld + kb + c] = x[i];
+  }
+}
+
+template <bool IN_LDS>
 __global__ void __launch_bounds__(1024)
-k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ X,
+k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
            float* __restrict__ Rinv32, int* __restrict__ flag, double tol) {
-  __shared__ double d0[kMaxL];
-  const int tid = threadIdx.x;
-  const int ty = tid >> 5, tx = tid & 31;
+  extern __shared__ double smem[];
+  __shared__ int bad;
+  double* Rkk = smem;                 // 16 x 17
+  double* d0 = smem + 16 * 17;        // kMaxL
+  double* rest = d0 + kMaxL;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < Lp * Lp; i += 1024) Rinv32[i] = 0.f;
-  if (flag[0] != 0) return;   // an earlier panel already broke down: results are void anyway
-  for (int i = tid; i < l; i += 1024) d0[i] = G[(int64_t)i * Lp + i];
-  for (int j = 0; j < l; ++j) {
+  if (flag[0] != 0) return;           // an earlier panel already broke down: results are void anyway
+  double* M;
+  int ld;
+  double* pan;                        // current 16-row panel R[kb:kb+nb, :] (row stride ldp)
+  int ldp;
+  if (IN_LDS) {
+    M = rest; ld = l | 1;
+    for (int idx = tid; idx < l * l; idx += 1024) {
+      int i = idx / l, c = idx - i * l;
+      M[i * ld + c] = c >= i ? G[(int64_t)i * Lp + c] : 0.0;
+    }
+    pan = nullptr; ldp = ld;
+  } else {
+    M = G; ld = Lp;
+    pan = rest; ldp = kMaxL;
+  }
+  if (tid == 0) bad = 0;
+  __syncthreads();
+  for (int i = tid; i < l; i += 1024) d0[i] = M[(int64_t)i * ld + i];
+  __syncthreads();
+
+  // ---- factorisation ----
+  for (int kb = 0; kb < l; kb += kNB) {
+    const int nb = min(kNB, l - kb);
+    if (wave == 0) {
+      bool ok = chol_diag_wave(M, ld, kb, nb, d0, tol, Rkk, lane);
+      if (!ok && lane == 0) bad = kb + 1;
+    }
     __syncthreads();
-    const double d = G[(int64_t)j * Lp + j];
-    if (!(d > tol * d0[j])) {
-      if (tid == 0) flag[0] = j + 1;
+    if (bad) {
+      if (tid == 0) flag[0] = bad;
       return;
     }
-    const double inv = 1.0 / sqrt(d);
-    __syncthreads();
-    for (int c = j + tid; c < l; c += 1024) G[(int64_t)j * Lp + c] *= inv;   // G[j][j] <- sqrt(d)
-    __syncthreads();
-    for (int rr = j + 1 + ty; rr < l; rr += 32) {
-      const double f = G[(int64_t)j * Lp + rr];
-      for (int c = rr + tx; c < l; c += 32) G[(int64_t)rr * Lp + c] -= f * G[(int64_t)j * Lp + c];
+    const int t0 = kb + nb;           // first trailing column
+    const int T = l - t0;
+    // row panel: R[kb:kb+nb, c] = R_kk^-T G[kb:kb+nb, c], one column per thread
+    for (int c = t0 + tid; c < l; c += 1024) {
+      double x[kNB];
+#pragma unroll
+      for (int i = 0; i < kNB; ++i) {
+        if (i < nb) {
+          double sacc = M[(int64_t)(kb + i) * ld + c];
+#pragma unroll
+          for (int t = 0; t < kNB; ++t)
+            if (t < i) sacc = fma(-Rkk[t * 17 + i], x[t], sacc);
+          x[i] = sacc / Rkk[i * 17 + i];
+          M[(int64_t)(kb + i) * ld + c] = x[i];
+          if (!IN_LDS) pan[i * ldp + c] = x[i];
+        }
+      }
     }
-  }
-  __syncthreads();
-  // R^-1 by back substitution, one column per thread: R X = I.
-  for (int jj = tid; jj < l; jj += 1024) {
-    X[(int64_t)jj * Lp + jj] = 1.0 / G[(int64_t)jj * Lp + jj];
-    for (int i = jj - 1; i >= 0; --i) {
-      double s = 0.0;
-      for (int k = i + 1; k <= jj; ++k) s = fma(G[(int64_t)i * Lp + k], X[(int64_t)k * Lp + jj], s);
-      X[(int64_t)i * Lp + jj] = -s / G[(int64_t)i * Lp + i];
+    __syncthreads();
+    // trailing update with 4 x 4 register tiles: G[r][c] -= sum_t R[kb+t][r] R[kb+t][c], r <= c
+    const double* P = IN_LDS ? (M + (int64_t)kb * ld) : pan;
+    const int nt = (T + 3) >> 2;
+    for (int idx = tid; idx < nt * nt; idx += 1024) {
+      const int ti = idx / nt, tj = idx - ti * nt;
+      if (tj < ti) continue;
+      const int r0 = t0 + 4 * ti, c0 = t0 + 4 * tj;
+      double acc[4][4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+      for (int t = 0; t < nb; ++t) {
+        double av[4], bv[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          av[a] = (r0 + a < l) ? P[t * ldp + r0 + a] : 0.0;
+          bv[a] = (c0 + a < l) ? P[t * ldp + c0 + a] : 0.0;
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int r = r0 + a, c = c0 + b;
+          if (r < l && c < l && r <= c) M[(int64_t)r * ld + c] -= acc[a][b];
+        }
     }
+    __syncthreads();
   }
-  __syncthreads();
+
+  // ---- publish R ----
   for (int idx = tid; idx < l * l; idx += 1024) {
     int i = idx / l, c = idx - i * l;
-    double rv = c >= i ? G[(int64_t)i * Lp + c] : 0.0;
-    Rout[(int64_t)i * Lp + c] = rv;
-    if (c >= i) Rinv32[(int64_t)i * Lp + c] = (float)X[(int64_t)i * Lp + c];
+    Rout[(int64_t)i * Lp + c] = c >= i ? M[(int64_t)i * ld + c] : 0.0;
+  }
+  __syncthreads();
+
+  // ---- inverse, level 0: diagonal blocks, one wave each ----
+  const int nblk = (l + kNB - 1) / kNB;
+  for (int bi = wave; bi < nblk; bi += 16) inv_diag_wave(M, ld, bi * kNB, min(kNB, l - bi * kNB), lane);
+  __syncthreads();
+  // ---- merge levels: X12 = -X11 (R12 X22).  T = R12 X22 is staged in registers (LDS variant:
+  // at most one 4 x 4 tile per thread per level) or in the global scratch Xtmp, so that the
+  // update can be done in place. ----
+  for (int B = kNB; B < l; B *= 2) {
+    const int npair = (l + 2 * B - 1) / (2 * B);
+    const int tr = B / 4, tc_full = B / 4, per = tr * tc_full;
+    int total = 0;
+    for (int p = 0; p < npair; ++p) {
+      int a = 2 * B * p, w = min(a + 2 * B, l) - (a + B);
+      if (w > 0) total += tr * ((w + 3) / 4);
+    }
+    for (int phase = 0; phase < 2; ++phase) {
+      double keep[4][4];
+      bool have = false;
+      int kr0 = 0, kc0 = 0;
+      for (int idx = tid; idx < total; idx += 1024) {
+        // tile -> (pair, tile row, tile column); only the last pair can be narrower than B
+        const int p = idx / per, rem = idx - p * per;
+        const int a0 = 2 * B * p;
+        const int w = min(a0 + 2 * B, l) - (a0 + B);
+        const int tcw = (p == npair - 1) ? (w + 3) / 4 : tc_full;
+        const int ti = rem / tcw, tj = rem - ti * tcw;
+        const int r0 = a0 + 4 * ti, c0 = a0 + B + 4 * tj;
+        double acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+        if (phase == 0) {
+          // T[i][j] = sum_{t <= j} R12[i][t] X22[t][j]
+          for (int t = a0 + B; t < min(c0 + 4, l); ++t) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              av[a] = M[(int64_t)(r0 + a) * ld + t];
+              bv[a] = (c0 + a < l && t <= c0 + a) ? M[(int64_t)t * ld + c0 + a] : 0.0;
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+              for (int b = 0; b < 4; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+          }
+        } else {
+          // X12[i][j] = -sum_{t >= i} X11[i][t] T[t][j]
+          const double* Tm = IN_LDS ? M : Xtmp;
+          const int ldt = IN_LDS ? ld : Lp;
+          for (int t = r0; t < a0 + B; ++t) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              av[a] = (t >= r0 + a) ? M[(int64_t)(r0 + a) * ld + t] : 0.0;
+              bv[a] = (c0 + a < l) ? Tm[(int64_t)t * ldt + c0 + a] : 0.0;
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+              for (int b = 0; b < 4; ++b) acc[a][b] = fma(-av[a], bv[b], acc[a][b]);
+          }
+        }
+        if (IN_LDS || phase == 1) {
+          // in place: hold the tile until every thread has finished reading (total <= 1024 here
+          // for the LDS variant, so each thread holds at most one tile); phase 1 of the global
+          // variant reads T from Xtmp and X11 from M, and writes the X12 region nobody reads
+          if (IN_LDS) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+              for (int b = 0; b < 4; ++b) keep[a][b] = acc[a][b];
+            have = true; kr0 = r0; kc0 = c0;
+          } else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+              for (int b = 0; b < 4; ++b)
+                if (c0 + b < l) M[(int64_t)(r0 + a) * ld + c0 + b] = acc[a][b];
+          }
+        } else {
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+              if (c0 + b < l) Xtmp[(int64_t)(r0 + a) * Lp + c0 + b] = acc[a][b];
+        }
+      }
+      __syncthreads();
+      if (IN_LDS && have) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (kc0 + b < l) M[(int64_t)(kr0 + a) * ld + kc0 + b] = keep[a][b];
+      }
+      __syncthreads();
+    }
+  }
+  for (int idx = tid; idx < l * l; idx += 1024) {
+    int i = idx / l, c = idx - i * l;
+    if (c >= i) Rinv32[(int64_t)i * Lp + c] = (float)M[(int64_t)i * ld + c];
   }
 }
 
@@ -149,15 +387,17 @@ __global__ void k_triu_mul(const double* __restrict__ R2, const double* __restri
   Rtot[(int64_t)i * Lp + c] = s;
 }
 
+// Row chunks of the Gram kernel: enough workgroups to fill the chip, at least 64 rows each.
 uint64_t orth_gram_chunks(int64_t rows) {
-  int64_t c = ceil_div(rows, 1024);
+  int64_t c = ceil_div(rows, 64);
   if (c > 64) c = 64;
   if (c < 1) c = 1;
   return (uint64_t)c;
 }
 
 static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t stream) {
-  int chunks = (int)orth_gram_chunks(rows);
+  int nbk = (Lp + 63) / 64;
+  int chunks = (int)std::min<int64_t>((int64_t)orth_gram_chunks(rows), ceil_div(1024, nbk * (nbk + 1) / 2));
   if (chunks > w.gram_chunks_max) return BRSVD_ERR_BUDGET;
   int64_t rpc = ceil_div(rows, chunks);
   rpc = ceil_div(rpc, kGramRC) * kGramRC;
@@ -173,36 +413,64 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
   return BRSVD_OK;
 }
 
+static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags, double tol,
+                    hipStream_t stream) {
+  const bool in_lds = l <= kCholLdsMaxL;
+  const int ld = l | 1;
+  const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)l * ld : (size_t)kNB * kMaxL)) * sizeof(double);
+  static bool attr_set = false;
+  if (!attr_set) {
+    const int max_lds = (16 * 17 + kMaxL + kCholLdsMaxL * (kCholLdsMaxL | 1)) * (int)sizeof(double);
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      max_lds));
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (16 * 17 + kMaxL + kNB * kMaxL) * (int)sizeof(double)));
+    attr_set = true;
+  }
+  if (in_lds)
+    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol);
+  else
+    hipLaunchKernelGGL(k_chol_inv<false>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags,
+                       tol);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
 int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot,
                float** result, hipStream_t stream);
 
-static int cholqr2(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot,
-                   float** result, hipStream_t stream) {
+static int cholqr(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
+                  float** result, hipStream_t stream) {
   const double tol = 1e-12;
   float* src = P;
   float* dst = tmp;
-  for (int sweep = 0; sweep < 2; ++sweep) {
+  for (int sweep = 0; sweep < nsweeps; ++sweep) {
     BRSVD_TRY(gram(src, rows, Lp, w, stream));
-    hipLaunchKernelGGL(k_chol_inv, dim3(1), dim3(1024), 0, stream, w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv,
-                       w.flags, tol);
-    BRSVD_HIP_TRY(hipGetLastError());
+    BRSVD_TRY(chol_inv(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream));
     BRSVD_TRY(gemm_an(src, Lp, rows, Lp, w.Rinv, Lp, dst, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
     float* t = src; src = dst; dst = t;
   }
-  *result = src;   // after two swaps: the original P
+  *result = src;
   if (Rtot) {
-    hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream,
-                       w.R[1], w.R[0], l, Lp, Rtot);
-    BRSVD_HIP_TRY(hipGetLastError());
+    if (nsweeps == 2) {
+      hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream,
+                         w.R[1], w.R[0], l, Lp, Rtot);
+      BRSVD_HIP_TRY(hipGetLastError());
+    } else {
+      BRSVD_HIP_TRY(hipMemcpyAsync(Rtot, w.R[0], (size_t)Lp * Lp * sizeof(double), hipMemcpyDeviceToDevice, stream));
+    }
   }
   return BRSVD_OK;
 }
 
-int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, OrthWork& w, double* Rtot,
-               float** result, hipStream_t stream) {
+int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bool final_basis, OrthWork& w,
+               double* Rtot, float** result, hipStream_t stream) {
   if (rows < l) return BRSVD_ERR_ARG;
   if (method == BRSVD_ORTH_TSQR) return tsqr_panel(P, tmp, rows, l, Lp, w, Rtot, result, stream);
-  return cholqr2(P, tmp, rows, l, Lp, w, Rtot, result, stream);
+  // A panel that only seeds the next power half step needs a well-conditioned basis, not one
+  // orthonormal to working precision: one CholeskyQR sweep (fp64 Gram) leaves ||Q^T Q - I|| of
+  // order eps32 * cond(P).  The bases that reach the output (Q behind U, W_B behind V) get two.
+  return cholqr(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream);
 }
 
 }  // namespace brsvd

@@ -2,10 +2,11 @@
 //
 // With B^T = W_B * R (thin QR of the n x l panel), R = Ur * diag(s) * Vr^T gives
 // B = Vr * diag(s) * (W_B Ur)^T, i.e. the small left factor is Vr and V = W_B * Ur.
-// The rows of a working copy of R are rotated in pairs until they are mutually orthogonal:
-// J^T R = diag(s) Vr^T, so s_i is the norm of row i, Vr's column i the normalised row i, and
-// Ur = J the accumulated rotations.  Everything is fp64; one workgroup of 1024 threads, each
-// wave handling the row pairs of a round-robin step assigned to it.
+// The rows of a working copy W of R are rotated in pairs (round-robin schedule) until they are
+// mutually orthogonal: then W = diag(s) Vr^T, so s_i is the norm of row i and Vr's column i the
+// normalised row i; Ur = R Vr diag(1/s) follows from one small product.  Everything is fp64.
+//   l <= kJacobiLdsMaxL : one workgroup of 1024 threads, W resident in LDS for all sweeps.
+//   larger l            : one launch per round-robin step, one wave per row pair, W in L2.
 #include "common.h"
 
 namespace brsvd {
@@ -13,6 +14,7 @@ namespace brsvd {
 constexpr int kSvdThreads = 1024;
 constexpr int kSvdWaves = kSvdThreads / 64;
 constexpr int kMaxSweeps = 40;
+constexpr int kJacobiLdsMaxL = 128;
 
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -20,104 +22,242 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// W: Lp x Lp working rows (stride Lp), JT: rows are the columns of J (stride Lp).
+// Pair pi of round-robin step `step` among L2 (even) players.
+__device__ __forceinline__ void rr_pair(int pi, int step, int L2, int& a, int& b) {
+  const int N = L2 - 1;
+  if (pi == 0) { a = N; b = step; }
+  else {
+    a = step + pi; if (a >= N) a -= N;
+    b = step - pi; if (b < 0) b += N;
+  }
+  if (a > b) { int t = a; a = b; b = t; }
+}
+
+// 1/sqrt(x) and 1/x for positive normal x: hardware seed plus two Newton steps (full fp64).
+__device__ __forceinline__ double rsqrt_nr(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  const double h = 0.5 * x;
+  y = fma(y, fma(-h * y, y, 0.5), y);
+  y = fma(y, fma(-h * y, y, 0.5), y);
+  return y;
+}
+__device__ __forceinline__ double rcp_nr(double x) {
+  double y = __builtin_amdgcn_rcp(x);
+  y = fma(y, fma(-x, y, 1.0), y);
+  y = fma(y, fma(-x, y, 1.0), y);
+  return y;
+}
+
+// Rotation (c, s) that makes two rows with squared norms al, be and inner product ga orthogonal:
+// with zeta = (be - al) / (2 ga), t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1/sqrt(1+t^2),
+// s = c t, written so that it needs one reciprocal and two reciprocal square roots.
+// Returns false (identity) when |ga| <= tol * sqrt(al * be).
+__device__ __forceinline__ bool rotation(double al, double be, double ga, double tol2, double& c, double& s) {
+  c = 1.0; s = 0.0;
+  if (!(ga * ga > tol2 * al * be)) return false;
+  const double tau = be - al, g2 = 2.0 * ga;
+  const double hh = fma(tau, tau, g2 * g2);
+  const double h = hh * rsqrt_nr(hh);
+  const double t = copysign(g2, g2 * tau >= 0.0 ? 1.0 : -1.0) * rcp_nr(fabs(tau) + h);
+  c = rsqrt_nr(fma(t, t, 1.0));
+  s = c * t;
+  return true;
+}
+
+// Sum over the 16 lanes of a DPP row, result in every lane of the row.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, true);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, true);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum(double v) {
+  v += dpp_f64<0x128>(v);   // row_ror:8
+  v += dpp_f64<0x124>(v);   // row_ror:4
+  v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+  return v;
+}
+
+// Singular values (row norms), their descending order, and the final rows, written to global.
+__device__ void publish(const double* W, int ld, int l, int Lp, double* Wg, double* sig, int* order_sh,
+                        int tid, int lane, int wave) {
+  for (int i = wave; i < l; i += kSvdWaves) {
+    double s2 = 0.0;
+    for (int e = lane; e < l; e += 64) { double x = W[(int64_t)i * ld + e]; s2 = fma(x, x, s2); }
+    s2 = wave_sum(s2);
+    if (lane == 0) sig[Lp + i] = sqrt(s2);
+  }
+  for (int i = tid; i < l; i += kSvdThreads) order_sh[i] = 0;
+  __syncthreads();
+  for (int i = tid; i < l; i += kSvdThreads) {
+    const double si = sig[Lp + i];
+    int rank = 0;
+    for (int j = 0; j < l; ++j) {
+      const double sj = sig[Lp + j];
+      rank += (sj > si) || (sj == si && j < i);
+    }
+    order_sh[rank] = i;
+  }
+  __syncthreads();
+  for (int i = tid; i < l; i += kSvdThreads) {
+    sig[i] = sig[Lp + order_sh[i]];
+    sig[2 * Lp + i] = (double)order_sh[i];
+  }
+  if (Wg != W)
+    for (int idx = tid; idx < l * l; idx += kSvdThreads) {
+      int i = idx / l, c = idx - i * l;
+      Wg[(int64_t)i * Lp + c] = W[(int64_t)i * ld + c];
+    }
+}
+
+// LDS-resident Jacobi: 16 waves, each quarter wave (16 lanes) owns one row pair per step, so a
+// step handles up to 64 pairs (l <= 128).  EPL = elements of a row per lane = ceil(l / 16).
+template <int EPL>
 __global__ void __launch_bounds__(kSvdThreads)
-k_jacobi(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ W,
-         double* __restrict__ JT, double* __restrict__ sig, int* __restrict__ info,
-         const int* __restrict__ breakdown_flag, double tol) {
+k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ Wg,
+             double* __restrict__ sig, int* __restrict__ info, const int* __restrict__ breakdown_flag,
+             double tol) {
+  extern __shared__ double W[];
   __shared__ int rotated;
-  __shared__ int order[kMaxL];
+  __shared__ int order_sh[kMaxL];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (breakdown_flag && breakdown_flag[0] != 0) {
     if (tid == 0) { info[0] = 0; info[1] = 0; }
     return;
   }
+  const int ld = l;
   for (int idx = tid; idx < l * l; idx += kSvdThreads) {
     int i = idx / l, c = idx - i * l;
-    W[(int64_t)i * Lp + c] = R[(int64_t)i * ldr + c];
-    JT[(int64_t)i * Lp + c] = (i == c) ? 1.0 : 0.0;
+    W[i * ld + c] = R[(int64_t)i * ldr + c];
   }
-  const int L2 = (l + 1) & ~1;         // even number of players; index l is a phantom when l is odd
+  const int L2 = (l + 1) & ~1;
   const int npairs = L2 / 2;
+  const int pi = wave * 4 + (lane >> 4);
+  const int r16 = lane & 15;
+  const double tol2 = tol * tol;
   int sweeps = 0, converged = (l < 2);
+  __syncthreads();
   while (!converged && sweeps < kMaxSweeps) {
     if (tid == 0) rotated = 0;
     __syncthreads();
+    bool any = false;
     for (int step = 0; step < L2 - 1; ++step) {
-      for (int pi = wave; pi < npairs; pi += kSvdWaves) {
-        int a, b;
-        if (pi == 0) { a = L2 - 1; b = step; }
-        else { a = (step + pi) % (L2 - 1); b = (step - pi + (L2 - 1)) % (L2 - 1); }
-        if (a >= l || b >= l) continue;
-        if (a > b) { int t = a; a = b; b = t; }
-        double* wa = W + (int64_t)a * Lp;
-        double* wb = W + (int64_t)b * Lp;
-        double al = 0.0, be = 0.0, ga = 0.0;
-        for (int e = lane; e < l; e += 64) {
-          double x = wa[e], y = wb[e];
-          al = fma(x, x, al); be = fma(y, y, be); ga = fma(x, y, ga);
-        }
-        al = wave_sum(al); be = wave_sum(be); ga = wave_sum(ga);
-        if (fabs(ga) > tol * sqrt(al * be) && al > 0.0 && be > 0.0) {
-          double zeta = (be - al) / (2.0 * ga);
-          double t = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-          double c = 1.0 / sqrt(1.0 + t * t), s = c * t;
-          double* ja = JT + (int64_t)a * Lp;
-          double* jb = JT + (int64_t)b * Lp;
-          for (int e = lane; e < l; e += 64) {
-            double x = wa[e], y = wb[e];
-            wa[e] = c * x - s * y; wb[e] = s * x + c * y;
-            double u = ja[e], v = jb[e];
-            ja[e] = c * u - s * v; jb[e] = s * u + c * v;
+      int a = 0, b = 0;
+      bool valid = pi < npairs;
+      if (valid) { rr_pair(pi, step, L2, a, b); valid = (b < l); }
+      double x[EPL], y[EPL], al = 0.0, be = 0.0, ga = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const int col = r16 + 16 * e;
+        const bool in = valid && col < l;
+        x[e] = in ? W[a * ld + col] : 0.0;
+        y[e] = in ? W[b * ld + col] : 0.0;
+        al = fma(x[e], x[e], al);
+        be = fma(y[e], y[e], be);
+        ga = fma(x[e], y[e], ga);
+      }
+      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      double c, s;
+      if (rotation(al, be, ga, tol2, c, s) && valid) {
+        any = true;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int col = r16 + 16 * e;
+          if (col < l) {
+            W[a * ld + col] = c * x[e] - s * y[e];
+            W[b * ld + col] = s * x[e] + c * y[e];
           }
-          if (lane == 0) rotated = 1;
         }
       }
       __syncthreads();
     }
+    if (any) rotated = 1;
+    __syncthreads();
     ++sweeps;
     converged = (rotated == 0);
     __syncthreads();
   }
-  // singular values = row norms; rank them (descending, ties by index)
-  for (int i = wave; i < l; i += kSvdWaves) {
-    double s2 = 0.0;
-    for (int e = lane; e < l; e += 64) { double x = W[(int64_t)i * Lp + e]; s2 = fma(x, x, s2); }
-    s2 = wave_sum(s2);
-    if (lane == 0) sig[Lp + i] = sqrt(s2);      // unsorted copy in the second half of sig
-  }
-  __syncthreads();
-  for (int i = tid; i < l; i += kSvdThreads) {
-    double si = sig[Lp + i];
-    int rank = 0;
-    for (int j = 0; j < l; ++j) {
-      double sj = sig[Lp + j];
-      rank += (sj > si) || (sj == si && j < i);
-    }
-    order[rank] = i;
-  }
-  __syncthreads();
-  for (int i = tid; i < l; i += kSvdThreads) sig[i] = sig[Lp + order[i]];
-  // reorder rows in place is awkward; publish the permutation instead (third part of sig, as doubles)
-  for (int i = tid; i < l; i += kSvdThreads) sig[2 * Lp + i] = (double)order[i];
+  publish(W, ld, l, Lp, Wg, sig, order_sh, tid, lane, wave);
   if (tid == 0) { info[0] = sweeps; info[1] = converged; }
 }
 
-// Scatter the sorted factors: XV[kk][i] = W[o_i][kk] / s_i (Vr), XU[kk][i] = JT[o_i][kk] (Ur);
-// fp32 zero-padded Lp x Lp operands for the lifts, and optional dense fp64 l x l copies.
-__global__ void k_svd_outputs(const double* __restrict__ W, const double* __restrict__ JT,
+// ---- large l: one launch per step, one wave per pair, rows in global memory -----------------
+constexpr int kStepEPL = kMaxL / 64;
+
+__global__ void k_jacobi_init(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ W) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= l * l) return;
+  int i = idx / l, c = idx - i * l;
+  W[(int64_t)i * Lp + c] = R[(int64_t)i * ldr + c];
+}
+
+__global__ void __launch_bounds__(256)
+k_jacobi_step(double* __restrict__ W, int l, int Lp, int step, double tol, int* __restrict__ rotated) {
+  const int lane = threadIdx.x & 63;
+  const int pi = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int L2 = (l + 1) & ~1;
+  if (pi >= L2 / 2) return;
+  int a, b;
+  rr_pair(pi, step, L2, a, b);
+  if (b >= l) return;
+  double* wa = W + (int64_t)a * Lp;
+  double* wb = W + (int64_t)b * Lp;
+  double x[kStepEPL], y[kStepEPL], al = 0.0, be = 0.0, ga = 0.0;
+#pragma unroll
+  for (int e = 0; e < kStepEPL; ++e) {
+    const int col = lane + 64 * e;
+    x[e] = col < l ? wa[col] : 0.0;
+    y[e] = col < l ? wb[col] : 0.0;
+    al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
+  }
+  al = wave_sum(al); be = wave_sum(be); ga = wave_sum(ga);
+  double c, s;
+  if (!rotation(al, be, ga, tol * tol, c, s)) return;
+#pragma unroll
+  for (int e = 0; e < kStepEPL; ++e) {
+    const int col = lane + 64 * e;
+    if (col < l) { wa[col] = c * x[e] - s * y[e]; wb[col] = s * x[e] + c * y[e]; }
+  }
+  if (lane == 0) *rotated = 1;
+}
+
+__global__ void k_set_int(int* p, int v) { *p = v; }
+
+__global__ void __launch_bounds__(kSvdThreads)
+k_jacobi_publish(double* __restrict__ W, int l, int Lp, double* __restrict__ sig, int* __restrict__ info,
+                 int sweeps, int converged) {
+  __shared__ int order_sh[kMaxL];
+  const int tid = threadIdx.x;
+  publish(W, Lp, l, Lp, W, sig, order_sh, tid, tid & 63, tid >> 6);
+  if (tid == 0) { info[0] = sweeps; info[1] = converged; }
+}
+
+// Sorted factors.  Vr[t][i] = W[o_i][t] / s_i;  Ur[kk][i] = sum_t R[kk][t] Vr[t][i] / s_i.
+// XV / XU: fp32 zero-padded Lp x Lp right operands of the lifts; Ur / Vr: optional dense fp64.
+__global__ void k_svd_outputs(const double* __restrict__ R, int ldr, const double* __restrict__ W,
                               const double* __restrict__ sig, int l, int Lp, double* __restrict__ S,
                               float* __restrict__ S32, float* __restrict__ XV, float* __restrict__ XU,
-                              double* __restrict__ Ur, double* __restrict__ Vr) {
+                              double* __restrict__ Ur, double* __restrict__ Vr,
+                              const int* __restrict__ breakdown_flag) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= Lp * Lp) return;
+  if (breakdown_flag && breakdown_flag[0] != 0) return;   // nothing was computed
   int kk = idx / Lp, i = idx - kk * Lp;
   float xv = 0.f, xu = 0.f;
   if (kk < l && i < l) {
-    int o = (int)sig[2 * Lp + i];
-    double s = sig[i];
-    double v = s > 0.0 ? W[(int64_t)o * Lp + kk] / s : 0.0;
-    double u = JT[(int64_t)o * Lp + kk];
+    const int o = min(max((int)sig[2 * Lp + i], 0), l - 1);   // stays in range even for NaN input
+    const double s = sig[i];
+    const double* wrow = W + (int64_t)o * Lp;
+    double v = 0.0, u = 0.0;
+    if (s > 0.0) {
+      v = wrow[kk] / s;
+      const double* rrow = R + (int64_t)kk * ldr;
+      double acc = 0.0;
+      for (int t = 0; t < l; ++t) acc = fma(rrow[t], wrow[t], acc);
+      u = acc / (s * s);
+    }
     xv = (float)v; xu = (float)u;
     if (Vr) Vr[(int64_t)kk * l + i] = v;
     if (Ur) Ur[(int64_t)kk * l + i] = u;
@@ -130,14 +270,66 @@ __global__ void k_svd_outputs(const double* __restrict__ W, const double* __rest
   if (XU) XU[idx] = xu;
 }
 
+template <int EPL>
+static int launch_jacobi_lds(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag,
+                             double tol, hipStream_t stream) {
+  auto kern = k_jacobi_lds<EPL>;
+  const size_t lds = (size_t)l * l * sizeof(double);
+  static bool attr_set = false;
+  if (!attr_set) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kJacobiLdsMaxL * kJacobiLdsMaxL * (int)sizeof(double)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(1), dim3(kSvdThreads), lds, stream, R, ldr, l, Lp, w.W, w.sig, w.info,
+                     breakdown_flag, tol);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
 int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag, double* S,
               float* S32, float* XV, float* XU, double* Ur, double* Vr, hipStream_t stream) {
   if (l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
-  hipLaunchKernelGGL(k_jacobi, dim3(1), dim3(kSvdThreads), 0, stream, R, ldr, l, Lp, w.W, w.J, w.sig, w.info,
-                     breakdown_flag, 1e-13);
-  BRSVD_HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(k_svd_outputs, dim3((unsigned)ceil_div((int64_t)Lp * Lp, 256)), dim3(256), 0, stream, w.W,
-                     w.J, w.sig, l, Lp, S, S32, XV, XU, Ur, Vr);
+  const double tol = 1e-13;
+  if (l <= kJacobiLdsMaxL) {
+    if (l <= 32) BRSVD_TRY(launch_jacobi_lds<2>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+    else if (l <= 64) BRSVD_TRY(launch_jacobi_lds<4>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+    else if (l <= 96) BRSVD_TRY(launch_jacobi_lds<6>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+    else if (l <= 112) BRSVD_TRY(launch_jacobi_lds<7>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+    else BRSVD_TRY(launch_jacobi_lds<8>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+  } else {
+    // Host-driven sweeps: the convergence flag is read back once per sweep.
+    int* rotated = w.info + 2;
+    int host_flag = 0;
+    if (breakdown_flag) {
+      BRSVD_HIP_TRY(hipMemcpyAsync(&host_flag, breakdown_flag, sizeof(int), hipMemcpyDeviceToHost, stream));
+      BRSVD_HIP_TRY(hipStreamSynchronize(stream));
+    }
+    int sweeps = 0, converged = 0;
+    if (host_flag == 0) {
+      hipLaunchKernelGGL(k_jacobi_init, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream, R,
+                         ldr, l, Lp, w.W);
+      const int L2 = (l + 1) & ~1;
+      const unsigned blocks = (unsigned)ceil_div(L2 / 2, 4);
+      while (!converged && sweeps < kMaxSweeps) {
+        hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, stream, rotated, 0);
+        for (int step = 0; step < L2 - 1; ++step)
+          hipLaunchKernelGGL(k_jacobi_step, dim3(blocks), dim3(256), 0, stream, w.W, l, Lp, step, tol, rotated);
+        BRSVD_HIP_TRY(hipGetLastError());
+        int rot = 1;
+        BRSVD_HIP_TRY(hipMemcpyAsync(&rot, rotated, sizeof(int), hipMemcpyDeviceToHost, stream));
+        BRSVD_HIP_TRY(hipStreamSynchronize(stream));
+        ++sweeps;
+        converged = (rot == 0);
+      }
+    }
+    if (host_flag == 0)
+      hipLaunchKernelGGL(k_jacobi_publish, dim3(1), dim3(kSvdThreads), 0, stream, w.W, l, Lp, w.sig, w.info,
+                         sweeps, converged);
+    BRSVD_HIP_TRY(hipGetLastError());
+  }
+  hipLaunchKernelGGL(k_svd_outputs, dim3((unsigned)ceil_div((int64_t)Lp * Lp, 256)), dim3(256), 0, stream, R, ldr,
+                     w.W, w.sig, l, Lp, S, S32, XV, XU, Ur, Vr, breakdown_flag);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
