@@ -169,7 +169,7 @@ __device__ void inv_diag_wave(double* M, int ld, int kb, int nb, int lane) {
 template <bool IN_LDS>
 __global__ void __launch_bounds__(1024)
 k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
-           float* __restrict__ Rinv32, int* __restrict__ flag, double tol) {
+           float* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored) {
   extern __shared__ double smem[];
   __shared__ int bad;
   double* Rkk = smem;                 // 16 x 17
@@ -198,8 +198,8 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   for (int i = tid; i < l; i += 1024) d0[i] = M[(int64_t)i * ld + i];
   __syncthreads();
 
-  // ---- factorisation ----
-  for (int kb = 0; kb < l; kb += kNB) {
+  // ---- factorisation (skipped when G already holds an upper-triangular factor) ----
+  for (int kb = factored ? l : 0; kb < l; kb += kNB) {
     const int nb = min(kNB, l - kb);
     if (wave == 0) {
       bool ok = chol_diag_wave(M, ld, kb, nb, d0, tol, Rkk, lane);
@@ -414,7 +414,7 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
 }
 
 static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags, double tol,
-                    hipStream_t stream) {
+                    hipStream_t stream, int factored = 0) {
   const bool in_lds = l <= kCholLdsMaxL;
   const int ld = l | 1;
   const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)l * ld : (size_t)kNB * kMaxL)) * sizeof(double);
@@ -428,18 +428,32 @@ static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float*
     attr_set = true;
   }
   if (in_lds)
-    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol);
+    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol, factored);
   else
     hipLaunchKernelGGL(k_chol_inv<false>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags,
-                       tol);
+                       tol, factored);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
 int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot,
                float** result, hipStream_t stream);
+int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
+                  float** result, hipStream_t stream);
 
-static int cholqr(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
+int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags,
+                      hipStream_t stream) {
+  return chol_inv(G, l, Lp, Rout, Xtmp, Rinv32, flags, 0.0, stream, 1);
+}
+
+int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream) {
+  hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream, R2, R1, l, Lp,
+                     Rtot);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
                   float** result, hipStream_t stream) {
   const double tol = 1e-12;
   float* src = P;
@@ -453,9 +467,7 @@ static int cholqr(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps
   *result = src;
   if (Rtot) {
     if (nsweeps == 2) {
-      hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream,
-                         w.R[1], w.R[0], l, Lp, Rtot);
-      BRSVD_HIP_TRY(hipGetLastError());
+      BRSVD_TRY(triu_mul(w.R[1], w.R[0], l, Lp, Rtot, stream));
     } else {
       BRSVD_HIP_TRY(hipMemcpyAsync(Rtot, w.R[0], (size_t)Lp * Lp * sizeof(double), hipMemcpyDeviceToDevice, stream));
     }
@@ -470,7 +482,7 @@ int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bo
   // A panel that only seeds the next power half step needs a well-conditioned basis, not one
   // orthonormal to working precision: one CholeskyQR sweep (fp64 Gram) leaves ||Q^T Q - I|| of
   // order eps32 * cond(P).  The bases that reach the output (Q behind U, W_B behind V) get two.
-  return cholqr(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream);
+  return cholqr_sweeps(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream);
 }
 
 }  // namespace brsvd

@@ -49,6 +49,16 @@ def test_scaled_configs_in_core(name, m, n, b):
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, b, U, S, Vt, cfg.name)
 
 
+def test_forced_tsqr_matches_oracle():
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C2"].scaled(3000, 2500, 700)
+    A = cfg.make_A()
+    Om = cfg.make_Omega()
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), orth=B.BRSVD_ORTH_TSQR)
+    assert st["orth_fallbacks"] == 0
+    check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 700, U, S, Vt, "C2-tsqr")
+
+
 def test_block_size_independence_and_determinism():
     dev = need_gpu()
     cfg = synth.CONFIGS["C1"]
@@ -92,6 +102,7 @@ def test_exact_rank_input_fp32_error_level():
     Om = synth.gaussian(900, k + p, 78)
     cfg = synth.Config("rank", 1500, 900, k, p, 1, 400, r, lambda i: i, 0.0, 0)
     U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev))
+    assert st["orth_fallbacks"] == 1 and st["passes_over_A"] == 2 * (2 * cfg.q + 2)   # the TSQR rerun
     sg = S.double().cpu().numpy()
     assert np.max(np.abs(sg[:r] - s.numpy()) / s.numpy()) < 1e-5
     assert np.all(sg[r:] < 1e-5 * sg[0])

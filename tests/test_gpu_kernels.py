@@ -98,6 +98,51 @@ def test_orth_cholqr2(rows, l, cond):
     assert np.linalg.norm(Qo @ (Qo.T @ Q) - Q, 2) < 20 * EPS32 * cond
 
 
+@pytest.mark.parametrize("rows,l,cond", [(3000, 30, 1e2), (2500, 110, 1e6), (5000, 272, 1e4), (1024, 16, 10.0),
+                                          (1025, 64, 1e3), (40, 40, 10.0)])
+def test_orth_tsqr(rows, l, cond):
+    """The Householder-tree route, forced: orthonormal, same range, P = Q R with R upper triangular."""
+    dev = need_gpu()
+    print(f"[case] tsqr rows={rows} l={l} cond={cond}", flush=True)
+    s = torch.logspace(0, -np.log10(cond), l, dtype=torch.float64)
+    mix, _ = torch.linalg.qr(synth.gaussian(l, l, 34, dtype=torch.float64))
+    P = (synth.exact_spectrum_matrix(rows, l, s, seed=33) @ mix).float()
+    Qd, R, fb = B.brsvd_orth(P.to(dev).contiguous(), method=B.BRSVD_ORTH_TSQR, want_R=True)
+    Q = Qd.double().cpu().numpy()
+    R = R.cpu().numpy()
+    P64 = P.double().numpy()
+    assert O.orth_defect(Q) < 5e-6
+    assert np.allclose(R, np.triu(R))
+    assert np.linalg.norm(Q @ R - P64) <= 1e-5 * np.linalg.norm(P64)
+    Qo = O.orth_householder(P64)
+    assert np.linalg.norm(Qo @ (Qo.T @ Q) - Q, 2) < 20 * EPS32 * cond
+    # R agrees with LAPACK's Householder factor up to row signs
+    Ro = np.linalg.qr(P64, mode="r")
+    assert np.linalg.norm(np.abs(R) - np.abs(Ro)) <= 1e-4 * np.linalg.norm(Ro)
+
+
+def test_orth_auto_falls_back_on_rank_deficient_panel():
+    """A panel of numerical rank r < l: CholeskyQR breaks down, AUTO takes the TSQR route and still
+    returns an orthonormal basis that contains range(P); CHOLQR2 alone reports the breakdown."""
+    dev = need_gpu()
+    rows, l, r = 2000, 24, 10
+    G1 = synth.gaussian(rows, r, 35, dtype=torch.float64)
+    G2 = synth.gaussian(r, l, 36, dtype=torch.float64)
+    P = (G1 @ G2).float()
+    Qd, _, fb = B.brsvd_orth(P.to(dev).contiguous(), method=B.BRSVD_ORTH_AUTO)
+    assert fb
+    Q = Qd.double().cpu().numpy()
+    assert O.orth_defect(Q) < 5e-6
+    P64 = P.double().numpy()
+    assert np.linalg.norm(Q @ (Q.T @ P64) - P64) <= 1e-5 * np.linalg.norm(P64)
+    with pytest.raises(B.BrsvdError) as ei:
+        B.brsvd_orth(P.to(dev).contiguous(), method=B.BRSVD_ORTH_CHOLQR2)
+    assert ei.value.status == B.BRSVD_ERR_ORTH_BREAKDOWN
+    # an all-zero panel cannot be orthonormalised by any route
+    with pytest.raises(B.BrsvdError):
+        B.brsvd_orth(torch.zeros(100, 8, device=dev), method=B.BRSVD_ORTH_AUTO)
+
+
 @pytest.mark.parametrize("l", [1, 2, 7, 30, 111, 128, 129, 272])
 def test_small_svd_jacobi(l):
     """R is the triangular factor of a matrix with prescribed singular values (cond 1e6, about the
