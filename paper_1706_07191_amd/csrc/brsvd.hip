@@ -11,6 +11,7 @@
 // order of the partial sums of A^T * Q).  Host-resident A: each block is copied into one of two
 // staging buffers on the copy stream while the other is being multiplied on the compute stream.
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -30,7 +31,7 @@ enum Cat { CAT_AN = 0, CAT_AT, CAT_ORTH, CAT_SVD, CAT_LIFT, CAT_COPY, CAT_ELEM, 
 struct Layout {
   // offsets into the arena
   uint64_t Pm[2], Pn[2], gemm_scratch, gram_part, G, R0, R1, Xinv, Rinv, Rtot, XV, XU, svdW, svdJ, sig,
-      S32, flags, tsqr, stage[2], scal, total;
+      S32, flags, tsqr, stage[2], scal, rpcaU, rpcaVt, rpca_part, total;
   uint64_t gemm_scratch_bytes, tsqr_bytes, stage_bytes;
   int gram_chunks;
 };
@@ -109,6 +110,11 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   L.S32 = take((uint64_t)Lp * 4);
   L.flags = take(64);
   L.scal = take(64);
+  if (!host) {   // results of the inner SVDs of the robust-PCA loop, and its reduction scratch
+    L.rpcaU = take((uint64_t)m * l * 4);
+    L.rpcaVt = take((uint64_t)l * n * 4);
+    L.rpca_part = take(rpca_part_doubles(m, n) * 8);
+  }
   L.tsqr_bytes = std::max(tsqr_work_bytes(m, Lp), tsqr_work_bytes(n, Lp));
   L.tsqr = take(L.tsqr_bytes);
   if (host) {
@@ -382,6 +388,25 @@ void fill_stats(brsvd_handle h, brsvd_stats* st, int passes, int fallbacks) {
   st->n_blocks = h->nblocks;
 }
 
+void add_stats(brsvd_stats* acc, const brsvd_stats& s) {
+  acc->total_seconds += s.total_seconds;
+  acc->gemm_an_seconds += s.gemm_an_seconds;
+  acc->gemm_at_seconds += s.gemm_at_seconds;
+  acc->orth_seconds += s.orth_seconds;
+  acc->svd_seconds += s.svd_seconds;
+  acc->lift_seconds += s.lift_seconds;
+  acc->copy_seconds += s.copy_seconds;
+  acc->elementwise_seconds += s.elementwise_seconds;
+  acc->gemm_an_launches += s.gemm_an_launches;
+  acc->gemm_at_launches += s.gemm_at_launches;
+  acc->passes_over_A += s.passes_over_A;
+  acc->bytes_A_streamed += s.bytes_A_streamed;
+  acc->orth_fallbacks += s.orth_fallbacks;
+  acc->jacobi_sweeps = s.jacobi_sweeps;
+  acc->row_block = s.row_block;
+  acc->n_blocks = s.n_blocks;
+}
+
 // Runs one factorisation to completion (synchronises), handling the optimistic CholeskyQR route:
 // the breakdown flag is only inspected at the end, and AUTO then repeats the run with TSQR.
 int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
@@ -517,6 +542,83 @@ int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, f
     fill_stats(h, stats, (2 * h->prm.q + 2) * (1 + fallbacks), fallbacks);
   }
   return status;
+}
+
+int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t iters, float lambda, float mu0,
+                    float rho, double norm2_M, float* L, float* S, float* work, double* residuals,
+                    brsvd_stats* stats) {
+  if (!h || !M || !Omegas || !L || !S || !work || iters < 1) return BRSVD_ERR_ARG;
+  if (h->host_a || !(lambda > 0.f) || !(mu0 > 0.f) || !(rho > 1.f)) return BRSVD_ERR_ARG;
+  const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
+  const int l = h->l;
+  hipStream_t cs = h->compute;
+  float* Y = work;
+  float* X = work + count;
+  float* Uw = h->at<float>(h->lay.rpcaU);
+  float* Vtw = h->at<float>(h->lay.rpcaVt);
+  float* Sw = h->at<float>(h->lay.S32);
+  double* part = h->at<double>(h->lay.rpca_part);
+  double* scal = h->at<double>(h->lay.scal);
+  brsvd_stats acc;
+  std::memset(&acc, 0, sizeof(acc));
+  auto flush_stats = [&](int passes, int fallbacks) {
+    if (!stats) return;
+    (void)hipStreamSynchronize(cs);
+    brsvd_stats one;
+    fill_stats(h, &one, passes, fallbacks);
+    add_stats(&acc, one);
+    reset_timing(h, true);
+  };
+  reset_timing(h, stats != nullptr);
+
+  // ||M||_max, ||M||_F^2 and, if not supplied, ||M||_2 from one randomized SVD
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_norms(M, count, part, scal, cs));
+  }
+  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal, 2 * sizeof(double), hipMemcpyDeviceToHost, cs));
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
+  if (!(normF > 0.0)) return BRSVD_ERR_ARG;
+  const int passes1 = 2 * h->prm.q + 2;
+  if (!(norm2_M > 0.0)) {
+    int fb = 0;
+    {
+      Region total(h, CAT_TOTAL, cs);
+      BRSVD_TRY(run_sync(h, M, n, Omegas, Uw, Sw, Vtw, &fb));
+    }
+    float s0 = 0.f;
+    BRSVD_HIP_TRY(hipMemcpy(&s0, Sw, sizeof(float), hipMemcpyDeviceToHost));
+    norm2_M = s0;
+    flush_stats(passes1 * (1 + fb), fb);
+    if (!(norm2_M > 0.0)) return BRSVD_ERR_ARG;
+  }
+  const double J = std::max(norm2_M, max_abs / (double)lambda);
+  double mu = mu0;
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_init(M, count, (float)(1.0 / J), (float)(1.0 / mu), Y, S, X, cs));
+  }
+  for (int it = 0; it < iters; ++it) {
+    int fb = 0;
+    const double mu_next = mu * (double)rho;
+    {
+      Region total(h, CAT_TOTAL, cs);
+      BRSVD_TRY(run_sync(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
+      {
+        Region r(h, CAT_ELEM, cs);
+        BRSVD_TRY(rpca_update(M, Uw, Sw, Vtw, m, n, l, (float)mu, lambda, (float)mu_next,
+                              it == iters - 1 ? L : nullptr, S, Y, X, part, scal + 2, cs));
+      }
+      BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
+      BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+    }
+    if (residuals) residuals[it] = std::sqrt(h->host_scal[2]) / normF;
+    flush_stats(passes1 * (1 + fb), fb);
+    mu = mu_next;
+  }
+  if (stats) *stats = acc;
+  return BRSVD_OK;
 }
 
 const char* brsvd_status_string(int status) {

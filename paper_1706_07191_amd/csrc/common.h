@@ -99,16 +99,18 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
               hipStream_t stream);
 
 // ---- robust-PCA elementwise kernels (rpca.hip) ---------------------------------------------
-// scal (device doubles): [0] max |M_ij|, [1] ||M||_F^2, [2] residual ||M-L-S||_F^2
-int rpca_norms(const float* M, int64_t count, double* scal, hipStream_t stream);
-// Y0 = M / J, S0 = 0, X0 = M - S0 + Y0/mu0
+// Number of doubles of partial-sum scratch the reductions below need.
+uint64_t rpca_part_doubles(int64_t m, int64_t n);
+// scal[0] = max |M_ij|, scal[1] = ||M||_F^2 (device doubles)
+int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream);
+// Y0 = M * inv_J, S0 = 0, X0 = M - S0 + Y0 * inv_mu
 int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y, float* S, float* X,
               hipStream_t stream);
-// Fused update after the SVD of X_i: L = U diag(shrink(s, 1/mu)) V^T (contraction over l),
-// S = shrink(M - L + Y/mu, lambda/mu), Y += mu (M - L - S), residual += ||M-L-S||_F^2, and the
-// next SVD input X = M - S + Y/(rho*mu).  U is m x l (ld l), Vt is l x n (ld n).
+// Fused update after the SVD of X_i: L = U diag(shrink(sig, 1/mu)) Vt (contraction over l),
+// S = shrink(M - L + Y/mu, lambda/mu), Y += mu (M - L - S), *resid2_out = ||M-L-S||_F^2, and the
+// next SVD input X = M - S + Y/mu_next.  U is m x l (ld l), Vt is l x n (ld n).  Lout may be null.
 int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n,
-                int l, float mu, float lambda, float rho, float* L, float* S, float* Y, float* X,
-                double* resid2, hipStream_t stream);
+                int l, float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X,
+                double* part, double* resid2_out, hipStream_t stream);
 
 }  // namespace brsvd

@@ -1,7 +1,173 @@
-// Robust PCA by inexact ALM (Alg. 3): elementwise kernels and the fixed-iteration loop.
+// Robust PCA by the inexact augmented Lagrange multiplier method (Alg. 3, Eq. (3)):
+// the elementwise kernels around the randomized SVD.  All of them are single sweeps over
+// m x n fp32 arrays (HBM-bound); the rank-l product L = U diag(shrunk sigma) V^T is
+// recomputed inside the fused update instead of being stored and re-read.
+#include <algorithm>
+
 #include "common.h"
 
-extern "C" int brsvd_rpca_ialm(brsvd_handle, const float*, const float*, int32_t, float, float, float, double,
-                               float*, float*, float*, double*, brsvd_stats*) {
-  return BRSVD_ERR_ARG;   // filled in by a later change
+namespace brsvd {
+
+constexpr int kRpcaBlocks = 1024;     // fixed grid of the reductions (deterministic partial sums)
+
+__device__ __forceinline__ double block_sum(double v, double* sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  double s = 0.0;
+  if (threadIdx.x == 0)
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += sh[w];
+  return s;   // valid in thread 0
 }
+
+// part[2*b] = max |M| over the block's slice, part[2*b+1] = sum M^2.
+__global__ void __launch_bounds__(256)
+k_rpca_norms(const float* __restrict__ M, int64_t count, double* __restrict__ part) {
+  __shared__ double sh[4];
+  __shared__ double shm[4];
+  double mx = 0.0, ss = 0.0;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) {
+    const double v = (double)M[i];
+    mx = fmax(mx, fabs(v));
+    ss = fma(v, v, ss);
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, 64));
+  if (lane == 0) shm[wave] = mx;
+  const double s = block_sum(ss, sh);
+  if (threadIdx.x == 0) {
+    part[2 * blockIdx.x] = fmax(fmax(shm[0], shm[1]), fmax(shm[2], shm[3]));
+    part[2 * blockIdx.x + 1] = s;
+  }
+}
+
+// scal[0] = max over blocks of part[2b], scal[1] = sum of part[2b+1] (block order).
+__global__ void k_rpca_norms_final(const double* __restrict__ part, int nblocks, double* __restrict__ scal) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double mx = 0.0, ss = 0.0;
+  for (int b = 0; b < nblocks; ++b) { mx = fmax(mx, part[2 * b]); ss += part[2 * b + 1]; }
+  scal[0] = mx;
+  scal[1] = ss;
+}
+
+// out[slot] = sum of part[0..nblocks) in block order.
+__global__ void k_sum_partials(const double* __restrict__ part, int nblocks, double* __restrict__ out) {
+  __shared__ double sh[4];
+  double s = 0.0;
+  for (int b = threadIdx.x; b < nblocks; b += 256) s += part[b];
+  s = block_sum(s, sh);
+  if (threadIdx.x == 0) *out = s;
+}
+
+// Multiplier initialisation of Alg. 3: Y0 = M / J, S0 = 0, and the first SVD input
+// X0 = M - S0 + Y0 / mu0.
+__global__ void k_rpca_init(const float* __restrict__ M, int64_t count, float inv_J, float inv_mu,
+                            float* __restrict__ Y, float* __restrict__ S, float* __restrict__ X) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  const float mv = M[i];
+  const float y = mv * inv_J;
+  Y[i] = y;
+  S[i] = 0.f;
+  X[i] = fmaf(y, inv_mu, mv);
+}
+
+__device__ __forceinline__ float shrinkf(float x, float eps) {
+  return x > eps ? x - eps : (x < -eps ? x + eps : 0.f);
+}
+
+// One ALM iteration after the SVD of X_i (Alg. 3 lines 4-7 and the input of line 3 of the next
+// iteration).  Workgroup tile: 32 rows x 256 columns, one column per thread.
+//   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here)
+//   S = shrink(M - L + Y/mu, lambda/mu)
+//   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
+//   X_next = M - S + Y / mu_next
+// L is stored only when Lout != nullptr (the last iteration).
+constexpr int kRpcaTR = 32;
+__global__ void __launch_bounds__(256)
+k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const float* __restrict__ sig,
+              const float* __restrict__ Vt, int64_t m, int64_t n, int l, float inv_mu, float mu,
+              float thr_s, float inv_mu_next, float* __restrict__ Lout, float* __restrict__ S,
+              float* __restrict__ Y, float* __restrict__ X, double* __restrict__ part) {
+  extern __shared__ float us[];          // kRpcaTR x l : rows of U scaled by the shrunk sigma
+  __shared__ double sh[4];
+  const int tid = threadIdx.x;
+  const int64_t col = (int64_t)blockIdx.x * 256 + tid;
+  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
+  for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
+    const int i = idx / l, t = idx - i * l;
+    const int64_t row = row0 + i;
+    const float sv = fmaxf(sig[t] - inv_mu, 0.f);      // shrinkage of a non-negative singular value
+    us[idx] = row < m ? U[row * l + t] * sv : 0.f;
+  }
+  __syncthreads();
+  float acc[kRpcaTR];
+#pragma unroll
+  for (int i = 0; i < kRpcaTR; ++i) acc[i] = 0.f;
+  if (col < n) {
+    for (int t = 0; t < l; ++t) {
+      const float v = Vt[(int64_t)t * n + col];
+#pragma unroll
+      for (int i = 0; i < kRpcaTR; ++i) acc[i] = fmaf(us[i * l + t], v, acc[i]);
+    }
+  }
+  double z2 = 0.0;
+  if (col < n) {
+#pragma unroll
+    for (int i = 0; i < kRpcaTR; ++i) {
+      const int64_t row = row0 + i;
+      if (row < m) {
+        const int64_t e = row * n + col;
+        const float mv = M[e], yv = Y[e], lv = acc[i];
+        const float sv = shrinkf(fmaf(yv, inv_mu, mv - lv), thr_s);
+        const float z = mv - lv - sv;
+        const float yn = fmaf(mu, z, yv);
+        S[e] = sv;
+        Y[e] = yn;
+        X[e] = fmaf(yn, inv_mu_next, mv - sv);
+        if (Lout) Lout[e] = lv;
+        z2 = fma((double)z, (double)z, z2);
+      }
+    }
+  }
+  const double s = block_sum(z2, sh);
+  if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
+}
+
+uint64_t rpca_part_doubles(int64_t m, int64_t n) {
+  const int64_t blocks = ceil_div(n, 256) * ceil_div(m, kRpcaTR);
+  return (uint64_t)std::max<int64_t>(blocks, 2 * kRpcaBlocks);
+}
+
+int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream) {
+  hipLaunchKernelGGL(k_rpca_norms, dim3(kRpcaBlocks), dim3(256), 0, stream, M, count, part);
+  hipLaunchKernelGGL(k_rpca_norms_final, dim3(1), dim3(64), 0, stream, part, kRpcaBlocks, scal);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y, float* S, float* X,
+              hipStream_t stream) {
+  hipLaunchKernelGGL(k_rpca_init, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, M, count, inv_J,
+                     inv_mu, Y, S, X);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l,
+                float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X, double* part,
+                double* resid2_out, hipStream_t stream) {
+  dim3 grid((unsigned)ceil_div(n, 256), (unsigned)ceil_div(m, kRpcaTR));
+  if (grid.y > 65535) return BRSVD_ERR_ARG;
+  const size_t lds = (size_t)kRpcaTR * l * sizeof(float);
+  hipLaunchKernelGGL(k_rpca_update, grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, 1.0f / mu, mu,
+                     lambda / mu, 1.0f / mu_next, Lout, S, Y, X, part);
+  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part, (int)(grid.x * grid.y), resid2_out);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+}  // namespace brsvd
