@@ -14,12 +14,26 @@
 //   D: lane holds d[i = 4*g + v][j = r] in component v = 0..3.
 // Because the contraction index may be visited in any order, a lane's float4 of four
 // consecutive k (gemm_an) or four consecutive columns (gemm_at) feeds four MFMAs directly.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+
 #include "common.h"
 
 namespace brsvd {
 
 __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Identity the compiler cannot see through: the result is a new value living in VGPRs.  Used to
+// hand the prefetched block of A over to the MFMA stream, so that (a) the wait for the prefetch
+// sits exactly here and (b) no MFMA operand is mapped onto a register with a load in flight.
+template <typename V>
+__device__ __forceinline__ V opaque(V v) {
+  asm volatile("" : "+v"(v));
+  return v;
 }
 
 constexpr int kMaxNT = 17;   // n-tiles (of 16 columns) one launch keeps in registers
@@ -98,39 +112,52 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
 
   if (nchunks > 0) {
     LOAD_X(kbeg);
-    LOAD_A(a_cur, kbeg);
+    LOAD_A(a_nxt, kbeg);
     STORE_X(buf0);
   }
   __syncthreads();
 
+  // Not unrolled on purpose: the register copy a_cur = a_nxt at the top of an iteration is where the
+  // wait for the prefetched block of A belongs; without it the compiler ends up waiting for the
+  // freshly issued loads of the next chunk in the middle of the MFMA stream.
+#pragma nounroll
   for (int c = 0; c < nchunks; ++c) {
     const float* cur = (c & 1) ? buf1 : buf0;
     float* nxt = (c & 1) ? buf0 : buf1;
     const bool more = (c + 1 < nchunks);
+    // the block of A prefetched during the previous chunk becomes current (this copy is where
+    // the wait for those loads sits), then the next one is requested
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int s = 0; s < KS; ++s) a_cur[mt][s] = opaque(a_nxt[mt][s]);
     if (more) {
       LOAD_X(kbeg + (c + 1) * KC);
       LOAD_A(a_nxt, kbeg + (c + 1) * KC);
     }
+    // 4*KS steps of 4 contraction indices each; the panel values of step t+1 are read from LDS
+    // while the MFMAs of step t run (register double buffer bq).
+    {
+      float bq[2][NT];
+      const float* bbase = cur + (4 * g) * LD + r;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
+      for (int nt = 0; nt < NT; ++nt) bq[0][nt] = bbase[nt * 16];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float* brow = cur + (s * 16 + 4 * g + j) * LD + r;
+      for (int t = 0; t < 4 * KS; ++t) {
+        if (t + 1 < 4 * KS) {
+          const float* brow = bbase + (((t + 1) >> 2) * 16 + ((t + 1) & 3)) * LD;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          float b = brow[nt * 16];
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = mfma16(a_cur[mt][s][j], b, acc[mt][nt]);
+          for (int nt = 0; nt < NT; ++nt) bq[(t + 1) & 1][nt] = brow[nt * 16];
         }
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads of step t+1 ahead of the MFMAs of step t
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[mt][nt] = mfma16(a_cur[mt][t >> 2][t & 3], bq[t & 1][nt], acc[mt][nt]);
       }
     }
-    if (more) {
-      STORE_X(nxt);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) a_cur[mt][s] = a_nxt[mt][s];
-    }
+    if (more) STORE_X(nxt);
     __syncthreads();
   }
 #undef LOAD_X
@@ -234,34 +261,47 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
 
   if (nchunks > 0) {
     LOAD_Q(rbeg);
-    LOAD_A(a_cur, rbeg);
+    LOAD_A(a_nxt, rbeg);
     STORE_Q(buf0);
   }
   __syncthreads();
 
+  // Not unrolled on purpose: the register copy a_cur = a_nxt at the top of an iteration is where the
+  // wait for the prefetched block of A belongs; without it the compiler ends up waiting for the
+  // freshly issued loads of the next chunk in the middle of the MFMA stream.
+#pragma nounroll
   for (int c = 0; c < nchunks; ++c) {
     const float* cur = (c & 1) ? buf1 : buf0;
     float* nxt = (c & 1) ? buf0 : buf1;
     const bool more = (c + 1 < nchunks);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) a_cur[s] = opaque(a_nxt[s]);   // wait for the prefetched rows here
     if (more) {
       LOAD_Q(rbeg + (int64_t)(c + 1) * KC);
       LOAD_A(a_nxt, rbeg + (int64_t)(c + 1) * KC);
     }
+    // KS steps of 4 rows each; the panel values of step s+1 are read from LDS while the MFMAs of
+    // step s run (register double buffer bq).
+    {
+      float bq[2][NT];
+      const float* bbase = cur + g * LD + r;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const float* brow = cur + (s * 4 + g) * LD + r;
+      for (int nt = 0; nt < NT; ++nt) bq[0][nt] = bbase[nt * 16];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        float b = brow[nt * 16];
+      for (int s = 0; s < KS; ++s) {
+        if (s + 1 < KS) {
+          const float* brow = bbase + (s + 1) * 4 * LD;
 #pragma unroll
-        for (int j = 0; j < MT; ++j) acc[j][nt] = mfma16(a_cur[s][j], b, acc[j][nt]);
+          for (int nt = 0; nt < NT; ++nt) bq[(s + 1) & 1][nt] = brow[nt * 16];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads of step s+1 ahead of the MFMAs of step s
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int j = 0; j < MT; ++j) acc[j][nt] = mfma16(a_cur[s][j], bq[s & 1][nt], acc[j][nt]);
       }
     }
-    if (more) {
-      STORE_Q(nxt);
-#pragma unroll
-      for (int s = 0; s < KS; ++s) a_cur[s] = a_nxt[s];
-    }
+    if (more) STORE_Q(nxt);
     __syncthreads();
   }
 #undef LOAD_Q
@@ -339,13 +379,47 @@ __global__ void k_transpose_panel(const float* __restrict__ src, int64_t rows, i
 // --------------------------------------------------------------------------------------------
 // Host-side launch logic
 // --------------------------------------------------------------------------------------------
-static int target_workgroups() {
-  static int t = [] {
-    const char* e = getenv("BRSVD_TARGET_WGS");
-    int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 1024;
-  }();
-  return t;
+// Number of workgroup slots of the chip for a kernel whose workgroups use lds_bytes of LDS and run
+// at most wg_per_cu_regs per CU because of registers (a static estimate: the plan must not depend
+// on a device query, because the workspace is sized on the host before any GPU call).
+static bool verbose() {
+  static const bool v = [] { const char* e = getenv("BRSVD_VERBOSE"); return e && atoi(e) > 0; }();
+  return v;
+}
+constexpr int kNumCUs = 256;
+constexpr int kLdsPerCU = 160 * 1024;
+static int wg_slots(int lds_bytes, int wg_per_cu_regs) {
+  int by_lds = lds_bytes > 0 ? kLdsPerCU / lds_bytes : wg_per_cu_regs;
+  int per_cu = by_lds < wg_per_cu_regs ? by_lds : wg_per_cu_regs;
+  if (per_cu < 1) per_cu = 1;
+  return kNumCUs * per_cu;
+}
+
+// Picks how many ways to split the contraction so that tiles*splits workgroups fill whole rounds
+// of `slots`, without drowning the pass in partial-sum traffic.  out_over_in = bytes of one
+// partial output panel (written and re-read) relative to the bytes of A the launch reads;
+// units = indivisible pieces of the contraction range; traffic_weight in (0, 1] discounts that
+// traffic when the launch is bound by MFMA rather than by HBM.
+static int pick_splits(int64_t tiles, int slots, int64_t units, double out_over_in, double traffic_weight,
+                       const char* env_name) {
+  const char* e = getenv(env_name);
+  if (e && atoi(e) > 0) return (int)std::min<int64_t>(atoi(e), units);
+  int best = 1;
+  double best_score = -1.0;
+  const int smax = (int)std::min<int64_t>(units, 128);
+  for (int sp = 1; sp <= smax; ++sp) {
+    const int64_t per = ceil_div(units, sp);
+    const int64_t eff_sp = ceil_div(units, per);          // splits actually produced
+    if (eff_sp != sp) continue;
+    const double w = (double)tiles * sp;
+    const double rounds = std::ceil(w / slots);
+    // time model in units of one contraction piece: rounds * (pieces per workgroup + fill), against
+    // the ideal tiles*units/slots, plus the partial panels (one write and one read each)
+    double score = ((double)tiles * units / slots) / (rounds * ((double)per + 0.5));
+    score /= (1.0 + traffic_weight * 2.0 * out_over_in * (sp > 1 ? sp : 0));
+    if (score > best_score * 1.002) { best_score = score; best = sp; }
+  }
+  return best;
 }
 
 struct NGroups {
@@ -362,10 +436,13 @@ static NGroups column_groups(int Lp) {
 struct AnCfg {
   int mt, waves, kc;
 };
+// Tile shapes picked from sweeps on MI355X (see the launch templates below, which must agree).
 static AnCfg an_cfg(int nt) {
   if (nt <= 8) return {2, 4, 64};
   return {2, 4, 32};
 }
+// Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
+static double traffic_weight(int nt) { return nt <= 2 ? 1.0 : (nt <= 4 ? 0.6 : 0.3); }
 struct AnPlan {
   int row_tiles, ksplit, chunks_per_split;
 };
@@ -373,9 +450,11 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt) {
   AnCfg c = an_cfg(nt);
   AnPlan p;
   p.row_tiles = (int)ceil_div(rows, c.waves * c.mt * 16);
-  int nchunks = (int)ceil_div(K, c.kc);
-  int want = (int)ceil_div(target_workgroups(), p.row_tiles);
-  want = want < 1 ? 1 : (want > nchunks ? nchunks : want);
+  const int nchunks = (int)ceil_div(K, c.kc);
+  const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * 4;
+  const int wg_regs = nt <= 8 ? 2 : 1;         // waves per SIMD the register file allows, as workgroups per CU
+  const int want = pick_splits(p.row_tiles, wg_slots(lds_bytes, wg_regs), nchunks, (double)(nt * 16) / (double)K,
+                               traffic_weight(nt), "BRSVD_AN_SPLITS");
   p.chunks_per_split = (int)ceil_div(nchunks, want);
   p.ksplit = (int)ceil_div(nchunks, p.chunks_per_split);
   return p;
@@ -410,10 +489,12 @@ template <int NT>
 static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
                         float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
                         hipStream_t stream) {
+  constexpr int MT = 2;
+  constexpr int WAVES = 4;
   constexpr int KC = NT <= 8 ? 64 : 32;
   if (vec)
-    return launch_an_inst<NT, 2, 4, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
-  return launch_an_inst<NT, 2, 4, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
+    return launch_an_inst<NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
+  return launch_an_inst<NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
 }
 
 #define BRSVD_NT_SWITCH(nt, CALL)                                                      \
@@ -454,6 +535,9 @@ int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X
   AnPlan p = an_plan(rows, K, ng.nt);
   const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && K >= 4 && (K % 4 == 0);
   if (p.ksplit > 1 && scratch_bytes < (uint64_t)p.ksplit * rows * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
+  if (verbose())
+    fprintf(stderr, "[brsvd] gemm_an rows=%ld K=%ld Lp=%d: %d row tiles x %d k-splits (%d chunks each), vec=%d\n",
+            (long)rows, (long)K, Lp, p.row_tiles, p.ksplit, p.chunks_per_split, (int)vec);
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
@@ -480,7 +564,7 @@ struct AtPlan {
   int mt, col_tiles, nblocks, sub, rows_per_sub, nsplit;
 };
 static int at_mt(int nt) { return nt <= 8 ? 4 : 2; }
-constexpr int kAtWaves = 4;
+constexpr int kAtWaves = 8;
 constexpr int kAtKC = 32;
 
 static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
@@ -489,9 +573,12 @@ static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
   p.col_tiles = (int)ceil_div(n, kAtWaves * p.mt * 16);
   if (block_rows <= 0 || block_rows > rows) block_rows = rows;
   p.nblocks = (int)ceil_div(rows, block_rows);
-  int want = (int)ceil_div(target_workgroups(), (int64_t)p.col_tiles * p.nblocks);
-  int max_sub = (int)ceil_div(block_rows, kAtKC);
-  want = want < 1 ? 1 : (want > max_sub ? max_sub : want);
+  const int max_sub = (int)ceil_div(block_rows, kAtKC);
+  const int ld = nt * 16 + ((16 - (nt * 16) % 64) + 64) % 64;
+  const int lds_bytes = 2 * kAtKC * ld * 4;
+  // one partial panel (n x Lp) per split, against block_rows x n of A read per block
+  const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, 1), max_sub,
+                               (double)(nt * 16) / (double)block_rows, traffic_weight(nt), "BRSVD_AT_SPLITS");
   int64_t rps = ceil_div(block_rows, want);
   rps = ceil_div(rps, kAtKC) * kAtKC;
   p.rows_per_sub = (int)rps;
@@ -556,6 +643,9 @@ int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q
   if (scratch_bytes < (uint64_t)p.nsplit * n * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
   const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && (n % 4 == 0) && n >= 4;
   float* part = (float*)scratch;
+  if (verbose())
+    fprintf(stderr, "[brsvd] gemm_at rows=%ld n=%ld Lp=%d: %d col tiles x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
+            (long)rows, (long)n, Lp, p.col_tiles, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
