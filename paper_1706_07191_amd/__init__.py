@@ -143,15 +143,17 @@ def brsvd_destroy(handle) -> None:
     _check(lib().brsvd_destroy(handle), "brsvd_destroy")
 
 
-def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = None, want_stats=True):
+def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = None, want_stats=True,
+              pinned=False):
     """A: (m, n) fp32 CUDA tensor (or pinned host tensor for a host-resident handle), row stride
-    lda; Omega: (n, l) fp32 CUDA.  Returns (U, S, Vt, stats) as CUDA tensors m x l, l, l x n."""
+    lda; Omega: (n, l) fp32 CUDA.  pinned=True vouches for a host A that torch did not allocate itself
+    (see PinnedMatrix).  Returns (U, S, Vt, stats) as CUDA tensors m x l, l, l x n."""
     import torch
     m, n = A.shape
     l = Omega.shape[1]
     if A.dtype != torch.float32 or A.stride(1) != 1:
         raise TypeError("A must be fp32 with unit column stride")
-    if not A.is_cuda and not A.is_pinned():
+    if not A.is_cuda and not (pinned or A.is_pinned()):
         raise TypeError("a host-resident A must be pinned")
     lda = lda if lda is not None else A.stride(0)
     dev = Omega.device
@@ -243,3 +245,29 @@ def brsvd_small_svd(R, stream=None):
     _check(lib().brsvd_small_svd(_dev(R, torch.float64, "R"), l, S.data_ptr(), Ur.data_ptr(), Vr.data_ptr(),
                                  C.byref(sw), _stream_ptr(stream)), "brsvd_small_svd")
     return S, Ur, Vr, sw.value
+
+
+class PinnedMatrix:
+    """rows x cols fp32 matrix in pinned host memory obtained with one hipHostMalloc of the exact size
+    (torch's pinned allocator rounds requests up to a power of two, which fails for very large A).
+    `.tensor` is a torch view of the memory; call `.free()` when done."""
+
+    def __init__(self, rows: int, cols: int):
+        import numpy as np
+        import torch
+        self._hip = C.CDLL("libamdhip64.so")
+        self._hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        self._hip.hipHostFree.argtypes = [C.c_void_p]
+        ptr = C.c_void_p()
+        err = self._hip.hipHostMalloc(C.byref(ptr), rows * cols * 4, 0)
+        if err != 0 or not ptr.value:
+            raise MemoryError(f"hipHostMalloc of {rows * cols * 4} bytes failed (hip error {err})")
+        self.ptr = ptr.value
+        buf = (C.c_float * (rows * cols)).from_address(self.ptr)
+        self.tensor = torch.from_numpy(np.ctypeslib.as_array(buf)).view(rows, cols)
+
+    def free(self):
+        if self.ptr:
+            self.tensor = None
+            self._hip.hipHostFree(C.c_void_p(self.ptr))
+            self.ptr = None

@@ -109,3 +109,97 @@ def test_exact_rank_input_fp32_error_level():
     from oracle import brsvd_oracle as O
     err = O.recon_error(A.numpy(), U.double().cpu().numpy(), sg, Vt.double().cpu().numpy())
     assert err < 2e-6
+
+
+# ---- full-size configurations, in the launch configuration bench.py times ---------------------------
+
+def _fp64_properties(A_rows, m, n, U, S, Vt, dev, step=4096):
+    """Checks that hold at any size, evaluated in fp64 on the GPU block by block (checker only):
+    orthogonality of U and V, the triplet identity U^T A = diag(S) V^T, and the rank-l error through
+    ||A - U S V^T||_F^2 = ||A||_F^2 - sum S^2.  A_rows(r0, r1) returns rows of A as a CUDA tensor."""
+    l = S.numel()
+    Ud, Vd, Sd = U.double(), Vt.double(), S.double()
+    eye = torch.eye(l, device=dev, dtype=torch.float64)
+    orthU = torch.linalg.matrix_norm(Ud.T @ Ud - eye, 2).item()
+    orthV = torch.linalg.matrix_norm(Vd @ Vd.T - eye, 2).item()
+    acc = torch.zeros(l, n, device=dev, dtype=torch.float64)
+    nA2 = 0.0
+    for r0 in range(0, m, step):
+        blk = A_rows(r0, min(m, r0 + step)).double()
+        acc += Ud[r0:r0 + step].T @ blk
+        nA2 += float((blk * blk).sum())
+    triplet = torch.linalg.matrix_norm(acc - Sd[:, None] * Vd).item() / float(Sd[0])
+    err_l = float(np.sqrt(max(nA2 - float((Sd ** 2).sum()), 0.0) / nA2))
+    return orthU, orthV, triplet, err_l
+
+
+def test_config2_full_size_against_oracle():
+    """The benchmark workload itself: 20000 x 20000, k=100, p=10, q=2, row block 4096 (oracle: ~3 s)."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C2"]
+    A = cfg.make_A(device=dev)
+    Om = cfg.make_Omega(device=dev)
+    U, S, Vt, st = _run(cfg, A, Om)
+    assert st["n_blocks"] == 5 and st["passes_over_A"] == 6
+    check_against_oracle(A.cpu().numpy(), Om.cpu().numpy(), cfg.k, cfg.p, cfg.q, cfg.row_block, U, S, Vt, "C2-full")
+
+
+def test_config3_full_size_properties():
+    """100000 x 50000 (20 GB), k=256, p=16, q=1, row block 8192.  The full fp64 oracle takes about a
+    minute of CPU time, so by default the result is checked through size-independent properties and through
+    the oracle on a row sample of the first pass; BRSVD_FULL_ORACLE=1 adds the complete comparison."""
+    import os
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C3"]
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * 2 ** 30:
+        pytest.skip("needs 40 GB of free HBM")
+    A = cfg.make_A(device=dev)
+    Om = cfg.make_Omega(device=dev)
+    U, S, Vt, st = _run(cfg, A, Om)
+    assert st["n_blocks"] == 13 and st["passes_over_A"] == 4 and st["orth_fallbacks"] == 0
+    orthU, orthV, triplet, err_l = _fp64_properties(lambda a, b: A[a:b], cfg.m, cfg.n, U, S, Vt, dev)
+    print(f"[C3-full] orthU={orthU:.2e} orthV={orthV:.2e} triplet={triplet:.2e} err_l={err_l:.4e}", flush=True)
+    assert orthU <= 1e-5 and orthV <= 1e-5 and triplet <= 1e-4
+    s = S.double().cpu().numpy()
+    assert np.all(np.diff(s) <= 0) and s[-1] > 0
+    # sampled rows of the sketch pass against the oracle's definition Y[i,:] = A[i,:] Omega
+    rows = torch.tensor([0, 1, 8191, 8192, 50000, 98303, 99999], device=dev)
+    Y = B.brsvd_gemm_an(A, Om)
+    ref = A[rows].double().cpu().numpy() @ Om.double().cpu().numpy()
+    got = Y[rows].double().cpu().numpy()
+    assert np.max(np.abs(got - ref)) <= 1e-4 * np.max(np.abs(ref))
+    if os.environ.get("BRSVD_FULL_ORACLE") == "1":
+        check_against_oracle(A.cpu().numpy(), Om.cpu().numpy(), cfg.k, cfg.p, cfg.q, cfg.row_block, U, S, Vt, "C3-full")
+
+
+def test_config4_streaming_large_block():
+    """The out-of-core recipe at its real column count and row block (16384 x 100000 blocks, 16 GB budget)
+    but 40000 rows (16 GB pinned: three blocks, ragged tail); the GPU machine caps pinned host memory at about
+    64 GB, so the 80 GB matrix itself cannot be allocated there."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C4"].scaled(40000, 100000)
+    pm = B.PinnedMatrix(cfg.m, cfg.n)
+    try:
+        cfg.make_A(device="cpu", out=pm.tensor, gen_device=dev)
+        Om = cfg.make_Omega(device=dev)
+        prm = B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block,
+                            a_location=B.BRSVD_A_HOST_PINNED, device_budget_bytes=cfg.device_budget)
+        assert B.brsvd_workspace_bytes(prm) <= cfg.device_budget
+        h = B.brsvd_create(prm)
+        try:
+            U, S, Vt, st = B.brsvd_run(h, pm.tensor, Om, pinned=True)
+        finally:
+            B.brsvd_destroy(h)
+        assert st["n_blocks"] == 3 and st["gemm_an_launches"] == 6 and st["copy_seconds"] > 0
+        orthU, orthV, triplet, err_l = _fp64_properties(lambda a, b: pm.tensor[a:b].to(dev), cfg.m, cfg.n, U, S, Vt, dev)
+        print(f"[C4-40000] orthU={orthU:.2e} orthV={orthV:.2e} triplet={triplet:.2e} err_l={err_l:.4e} "
+              f"link={st['bytes_A_streamed'] / st['total_seconds'] / 1e9:.1f} GB/s", flush=True)
+        assert orthU <= 1e-5 and orthV <= 1e-5 and triplet <= 1e-4
+        # the same matrix resident in HBM gives the same singular values
+        A_dev = pm.tensor.to(dev)
+        U2, S2, Vt2, _ = _run(cfg, A_dev, Om)
+        rel = ((S2[:cfg.k] - S[:cfg.k]).abs() / S[:cfg.k]).max().item()
+        assert rel < 2e-5
+    finally:
+        pm.free()

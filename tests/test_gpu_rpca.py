@@ -80,3 +80,25 @@ def test_rpca_argument_errors():
             B.brsvd_rpca_ialm(h, D.to(dev), Om.to(dev), 0, 0.05, 1e-3, 1.5)      # iters >= 1
     finally:
         B.brsvd_destroy(h)
+
+
+def test_config5_full_size_recovery():
+    """76800 x 2000, rank-5 background + 5 % corruptions, 30 ALM iterations with k = p = 10, q = 1: the
+    planted decomposition is recovered and the residual falls to the fp32 floor (properties; the fp64
+    oracle of this size takes minutes and is exercised at 1200 x 320 above)."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C5"]
+    D, L0, S0 = synth.make_rpca(cfg, device=dev)
+    Om = synth.rpca_omegas(cfg, cfg.n, 30, device=dev)
+    lam = 1.0 / np.sqrt(max(cfg.m, cfg.n))
+    n2 = float(torch.linalg.matrix_norm(D.double(), 2))
+    h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block))
+    try:
+        L, S, res, st = B.brsvd_rpca_ialm(h, D, Om, 30, lam, 1.25 / n2, 1.5, norm2_M=n2)
+    finally:
+        B.brsvd_destroy(h)
+    assert st["passes_over_A"] == 120 and st["n_blocks"] == 10
+    assert res[-1] < 1e-5 and res[-1] < res[10] < res[0]
+    assert float(torch.linalg.norm(L - L0) / torch.linalg.norm(L0)) < 1e-3
+    assert float(torch.linalg.norm(S - S0) / torch.linalg.norm(S0)) < 1e-3
+    assert float(torch.linalg.norm(D - L - S) / torch.linalg.norm(D)) < 1e-5
