@@ -102,7 +102,26 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
 constexpr int kNB = 16;
 constexpr int kCholLdsMaxL = 136;
 
-__device__ __forceinline__ double shfl_d(double v, int src) { return __shfl(v, src, 64); }
+// Broadcast of lane `src` (a compile-time constant after unrolling): two scalar lane reads.
+__device__ __forceinline__ double shfl_d(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+// 1/sqrt(x) and 1/x: hardware seed plus two Newton steps (full fp64 accuracy for normal x).
+__device__ __forceinline__ double rsqrt_fast(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  const double h = 0.5 * x;
+  y = fma(y, fma(-h * y, y, 0.5), y);
+  y = fma(y, fma(-h * y, y, 0.5), y);
+  return y;
+}
+__device__ __forceinline__ double rcp_fast(double x) {
+  double y = __builtin_amdgcn_rcp(x);
+  y = fma(y, fma(-x, y, 1.0), y);
+  y = fma(y, fma(-x, y, 1.0), y);
+  return y;
+}
 
 // Wave-level Cholesky of the nb x nb diagonal block at (kb, kb): lane c (mod 16) keeps column c in
 // registers, pivots and row entries travel by shuffles.  Writes R_kk back and into Rkk (16 x 17).
@@ -118,7 +137,7 @@ __device__ bool chol_diag_wave(double* M, int ld, int kb, int nb, const double* 
   for (int j = 0; j < kNB; ++j) {
     const double d = shfl_d(col[j], j);
     if (j < nb && !(d > tol * d0[kb + j])) ok = false;
-    const double inv = 1.0 / sqrt(d);
+    const double inv = d > 0.0 ? rsqrt_fast(d) : 0.0;
     const double rj = (c >= j) ? col[j] * inv : 0.0;
     col[j] = rj;
 #pragma unroll
@@ -133,6 +152,10 @@ __device__ bool chol_diag_wave(double* M, int ld, int kb, int nb, const double* 
       Rkk[i * 17 + c] = col[i];
       if (i <= c && c < nb) M[(int64_t)(kb + i) * ld + kb + c] = col[i];
     }
+    double dv = 1.0;
+#pragma unroll
+    for (int i = 0; i < kNB; ++i) dv = (i == c) ? col[i] : dv;
+    Rkk[c * 17 + 16] = rcp_fast(dv);          // 1 / R[c][c] in the spare column, for the panel solve
   }
   return ok;
 }
@@ -155,9 +178,9 @@ __device__ void inv_diag_wave(double* M, int ld, int kb, int nb, int lane) {
       const double rit = shfl_d(rc[i], t);      // r[i][t] lives in lane t
       if (t <= c) s = fma(rit, x[t], s);
     }
-    const double rii = shfl_d(rc[i], i);
-    if (i == c) x[i] = 1.0 / rii;
-    else if (i < c) x[i] = -s / rii;
+    const double inv_rii = rcp_fast(shfl_d(rc[i], i));
+    if (i == c) x[i] = inv_rii;
+    else if (i < c) x[i] = -s * inv_rii;
   }
   if (lane < kNB && c < nb) {
 #pragma unroll
@@ -222,7 +245,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
 #pragma unroll
           for (int t = 0; t < kNB; ++t)
             if (t < i) sacc = fma(-Rkk[t * 17 + i], x[t], sacc);
-          x[i] = sacc / Rkk[i * 17 + i];
+          x[i] = sacc * Rkk[i * 17 + 16];
           M[(int64_t)(kb + i) * ld + c] = x[i];
           if (!IN_LDS) pan[i * ldp + c] = x[i];
         }
