@@ -328,6 +328,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
           for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
         if (phase == 0) {
           // T[i][j] = sum_{t <= j} R12[i][t] X22[t][j]
+#pragma unroll 4
           for (int t = a0 + B; t < min(c0 + 4, l); ++t) {
             double av[4], bv[4];
 #pragma unroll
@@ -344,6 +345,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
           // X12[i][j] = -sum_{t >= i} X11[i][t] T[t][j]
           const double* Tm = IN_LDS ? M : Xtmp;
           const int ldt = IN_LDS ? ld : Lp;
+#pragma unroll 4
           for (int t = r0; t < a0 + B; ++t) {
             double av[4], bv[4];
 #pragma unroll
