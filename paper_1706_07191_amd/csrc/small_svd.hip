@@ -7,6 +7,8 @@
 // normalised row i; Ur = R Vr diag(1/s) follows from one small product.  Everything is fp64.
 //   l <= kJacobiLdsMaxL : one workgroup of 1024 threads, W resident in LDS for all sweeps.
 //   larger l            : one launch per round-robin step, one wave per row pair, W in L2.
+#include <cstdlib>
+
 #include "common.h"
 
 namespace brsvd {
@@ -81,17 +83,18 @@ __device__ __forceinline__ double row16_sum(double v) {
 }
 
 // Singular values (row norms), their descending order, and the final rows, written to global.
+template <int NTHREADS>
 __device__ void publish(const double* W, int ld, int l, int Lp, double* Wg, double* sig, int* order_sh,
                         int tid, int lane, int wave) {
-  for (int i = wave; i < l; i += kSvdWaves) {
+  for (int i = wave; i < l; i += NTHREADS / 64) {
     double s2 = 0.0;
     for (int e = lane; e < l; e += 64) { double x = W[(int64_t)i * ld + e]; s2 = fma(x, x, s2); }
     s2 = wave_sum(s2);
     if (lane == 0) sig[Lp + i] = sqrt(s2);
   }
-  for (int i = tid; i < l; i += kSvdThreads) order_sh[i] = 0;
+  for (int i = tid; i < l; i += NTHREADS) order_sh[i] = 0;
   __syncthreads();
-  for (int i = tid; i < l; i += kSvdThreads) {
+  for (int i = tid; i < l; i += NTHREADS) {
     const double si = sig[Lp + i];
     int rank = 0;
     for (int j = 0; j < l; ++j) {
@@ -101,41 +104,51 @@ __device__ void publish(const double* W, int ld, int l, int Lp, double* Wg, doub
     order_sh[rank] = i;
   }
   __syncthreads();
-  for (int i = tid; i < l; i += kSvdThreads) {
+  for (int i = tid; i < l; i += NTHREADS) {
     sig[i] = sig[Lp + order_sh[i]];
     sig[2 * Lp + i] = (double)order_sh[i];
   }
   if (Wg != W)
-    for (int idx = tid; idx < l * l; idx += kSvdThreads) {
+    for (int idx = tid; idx < l * l; idx += NTHREADS) {
       int i = idx / l, c = idx - i * l;
       Wg[(int64_t)i * Lp + c] = W[(int64_t)i * ld + c];
     }
 }
 
-// LDS-resident Jacobi: 16 waves, each quarter wave (16 lanes) owns one row pair per step, so a
-// step handles up to 64 pairs (l <= 128).  EPL = elements of a row per lane = ceil(l / 16).
-template <int EPL>
-__global__ void __launch_bounds__(kSvdThreads)
+// Sum over groups of 8 lanes (half a DPP row), result in every lane of the group.
+__device__ __forceinline__ double row8_sum(double v) {
+  v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_f64<0x141>(v);   // row_half_mirror
+  return v;
+}
+
+// LDS-resident Jacobi: each group of LPP lanes (16 or 8) owns one row pair per round-robin step, so a
+// wave handles 64/LPP pairs with one instruction stream and 64 pairs (l <= 128) take 1024 or 512
+// threads.  EPL = elements of a row per lane = ceil(l / LPP).
+template <int EPL, int LPP>
+__global__ void __launch_bounds__(64 * LPP)
 k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ Wg,
              double* __restrict__ sig, int* __restrict__ info, const int* __restrict__ breakdown_flag,
              double tol) {
   extern __shared__ double W[];
   __shared__ int rotated;
   __shared__ int order_sh[kMaxL];
+  constexpr int NT = 64 * LPP;   // 64 row pairs per step
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (breakdown_flag && breakdown_flag[0] != 0) {
     if (tid == 0) { info[0] = 0; info[1] = 0; }
     return;
   }
   const int ld = l;
-  for (int idx = tid; idx < l * l; idx += kSvdThreads) {
+  for (int idx = tid; idx < l * l; idx += NT) {
     int i = idx / l, c = idx - i * l;
     W[i * ld + c] = R[(int64_t)i * ldr + c];
   }
   const int L2 = (l + 1) & ~1;
   const int npairs = L2 / 2;
-  const int pi = wave * 4 + (lane >> 4);
-  const int r16 = lane & 15;
+  const int pi = tid / LPP;
+  const int rl = tid % LPP;
   const double tol2 = tol * tol;
   int sweeps = 0, converged = (l < 2);
   __syncthreads();
@@ -150,7 +163,7 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
       double x[EPL], y[EPL], al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        const int col = r16 + 16 * e;
+        const int col = rl + LPP * e;
         const bool in = valid && col < l;
         x[e] = in ? W[a * ld + col] : 0.0;
         y[e] = in ? W[b * ld + col] : 0.0;
@@ -158,13 +171,14 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
         be = fma(y[e], y[e], be);
         ga = fma(x[e], y[e], ga);
       }
-      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      if (LPP == 16) { al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga); }
+      else { al = row8_sum(al); be = row8_sum(be); ga = row8_sum(ga); }
       double c, s;
       if (rotation(al, be, ga, tol2, c, s) && valid) {
         any = true;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-          const int col = r16 + 16 * e;
+          const int col = rl + LPP * e;
           if (col < l) {
             W[a * ld + col] = c * x[e] - s * y[e];
             W[b * ld + col] = s * x[e] + c * y[e];
@@ -179,7 +193,7 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
     converged = (rotated == 0);
     __syncthreads();
   }
-  publish(W, ld, l, Lp, Wg, sig, order_sh, tid, lane, wave);
+  publish<NT>(W, ld, l, Lp, Wg, sig, order_sh, tid, lane, wave);
   if (tid == 0) { info[0] = sweeps; info[1] = converged; }
 }
 
@@ -230,7 +244,7 @@ k_jacobi_publish(double* __restrict__ W, int l, int Lp, double* __restrict__ sig
                  int sweeps, int converged) {
   __shared__ int order_sh[kMaxL];
   const int tid = threadIdx.x;
-  publish(W, Lp, l, Lp, W, sig, order_sh, tid, tid & 63, tid >> 6);
+  publish<kSvdThreads>(W, Lp, l, Lp, W, sig, order_sh, tid, tid & 63, tid >> 6);
   if (tid == 0) { info[0] = sweeps; info[1] = converged; }
 }
 
@@ -270,10 +284,10 @@ __global__ void k_svd_outputs(const double* __restrict__ R, int ldr, const doubl
   if (XU) XU[idx] = xu;
 }
 
-template <int EPL>
+template <int EPL, int LPP>
 static int launch_jacobi_lds(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag,
                              double tol, hipStream_t stream) {
-  auto kern = k_jacobi_lds<EPL>;
+  auto kern = k_jacobi_lds<EPL, LPP>;
   const size_t lds = (size_t)l * l * sizeof(double);
   static bool attr_set = false;
   if (!attr_set) {
@@ -281,7 +295,7 @@ static int launch_jacobi_lds(const double* R, int ldr, int l, int Lp, SvdWork& w
                                       kJacobiLdsMaxL * kJacobiLdsMaxL * (int)sizeof(double)));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(1), dim3(kSvdThreads), lds, stream, R, ldr, l, Lp, w.W, w.sig, w.info,
+  hipLaunchKernelGGL(kern, dim3(1), dim3(64 * LPP), lds, stream, R, ldr, l, Lp, w.W, w.sig, w.info,
                      breakdown_flag, tol);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
@@ -292,11 +306,13 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
   if (l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
   const double tol = 1e-13;
   if (l <= kJacobiLdsMaxL) {
-    if (l <= 32) BRSVD_TRY(launch_jacobi_lds<2>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
-    else if (l <= 64) BRSVD_TRY(launch_jacobi_lds<4>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
-    else if (l <= 96) BRSVD_TRY(launch_jacobi_lds<6>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
-    else if (l <= 112) BRSVD_TRY(launch_jacobi_lds<7>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
-    else BRSVD_TRY(launch_jacobi_lds<8>(R, ldr, l, Lp, w, breakdown_flag, tol, stream));
+    // 16 lanes per pair measured faster than 8 (1.12 vs 1.23 ms at l = 110): with 16 waves the
+    // instruction streams hide each other's latency better than 8 longer ones do.
+    if (l <= 32) BRSVD_TRY((launch_jacobi_lds<2, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else if (l <= 64) BRSVD_TRY((launch_jacobi_lds<4, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else if (l <= 96) BRSVD_TRY((launch_jacobi_lds<6, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else if (l <= 112) BRSVD_TRY((launch_jacobi_lds<7, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else BRSVD_TRY((launch_jacobi_lds<8, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
   } else {
     // Host-driven sweeps: the convergence flag is read back once per sweep.
     int* rotated = w.info + 2;
