@@ -36,6 +36,13 @@ enum {
 
 enum { BRSVD_A_DEVICE = 0, BRSVD_A_HOST_PINNED = 1 };
 enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
+/* How often A is read.  SEPARATE: one pass per product, 2q+2 passes, the panel re-orthonormalised
+ * after every half step (the count the paper gives for a straightforward implementation, Sec. 3).
+ * FUSED: while a row block is resident both products of a power step are taken from it,
+ * T_I = A_I X and Z += A_I^T T_I, and the last pass forms Y_I = A_I X together with C^T += A_I^T Y_I,
+ * from which B^T = C^T R^-1 (Y = Q R): q+1 passes -- the paper's "only twice" for q = 1 -- at the
+ * price of one skipped re-orthonormalisation per pass (panels of condition up to (s_1/s_l)^2). */
+enum { BRSVD_PASSES_SEPARATE = 0, BRSVD_PASSES_FUSED = 1 };
 
 /* Problem statement of Alg. 1 / Alg. 2 (inputs A, k, p, q and the partition), plus where A
  * lives and how much device memory may be used (Sec. 4: the block size is chosen from the
@@ -49,7 +56,7 @@ typedef struct {
                                    that fits the budget                                        */
   uint64_t device_budget_bytes; /* cap on all device memory owned by the handle; 0 = no cap    */
   int32_t orth_method;          /* BRSVD_ORTH_*                                                */
-  int32_t reserved;             /* must be 0                                                   */
+  int32_t pass_mode;            /* BRSVD_PASSES_*                                              */
   void* compute_stream;         /* hipStream_t for all kernels; NULL = the null stream         */
   void* copy_stream;            /* hipStream_t for host->device block copies (host-resident A);
                                    NULL = the library creates one (default priority)           */

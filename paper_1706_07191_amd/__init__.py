@@ -26,13 +26,15 @@ BRSVD_A_HOST_PINNED = 1
 BRSVD_ORTH_AUTO = 0
 BRSVD_ORTH_CHOLQR2 = 1
 BRSVD_ORTH_TSQR = 2
+BRSVD_PASSES_SEPARATE = 0
+BRSVD_PASSES_FUSED = 1
 
 
 class brsvd_params(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64),
                 ("k", C.c_int32), ("p", C.c_int32), ("q", C.c_int32), ("a_location", C.c_int32),
                 ("row_block", C.c_int64), ("device_budget_bytes", C.c_uint64),
-                ("orth_method", C.c_int32), ("reserved", C.c_int32),
+                ("orth_method", C.c_int32), ("pass_mode", C.c_int32),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
 
 
@@ -120,9 +122,10 @@ def _dev(t, dtype, name):
 
 
 def make_params(m, n, k, p, q, row_block=0, device_budget_bytes=0, a_location=BRSVD_A_DEVICE,
-                orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None) -> brsvd_params:
+                orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None,
+                pass_mode=BRSVD_PASSES_SEPARATE) -> brsvd_params:
     return brsvd_params(m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
-                        device_budget_bytes=device_budget_bytes, orth_method=orth_method, reserved=0,
+                        device_budget_bytes=device_budget_bytes, orth_method=orth_method, pass_mode=pass_mode,
                         compute_stream=_stream_ptr(compute_stream),
                         copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None)
 

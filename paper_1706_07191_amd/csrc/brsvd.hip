@@ -72,7 +72,8 @@ int validate(const brsvd_params* p) {
   if (p->m > INT32_MAX || p->n > INT32_MAX) return BRSVD_ERR_ARG;
   if (p->a_location != BRSVD_A_DEVICE && p->a_location != BRSVD_A_HOST_PINNED) return BRSVD_ERR_ARG;
   if (p->orth_method < BRSVD_ORTH_AUTO || p->orth_method > BRSVD_ORTH_TSQR) return BRSVD_ERR_ARG;
-  if (p->row_block < 0 || p->reserved != 0) return BRSVD_ERR_ARG;
+  if (p->row_block < 0) return BRSVD_ERR_ARG;
+  if (p->pass_mode != BRSVD_PASSES_SEPARATE && p->pass_mode != BRSVD_PASSES_FUSED) return BRSVD_ERR_ARG;
   return BRSVD_OK;
 }
 
@@ -287,6 +288,33 @@ int pass_at(brsvd_handle h, const float* A, int64_t lda, const float* Q, float* 
   return BRSVD_OK;
 }
 
+// One read of A doing both products of a power step: T_I = A_I * X and Z += A_I^T * T_I while block I
+// is resident (device-resident A: two launches over the whole matrix).
+int pass_fused(brsvd_handle h, const float* A, int64_t lda, const float* X, float* T, float* Z) {
+  const int Lp = h->Lp;
+  const int64_t n = h->prm.n;
+  void* scr = h->arena + h->lay.gemm_scratch;
+  if (!h->host_a) {
+    BRSVD_TRY(pass_an(h, A, lda, X, T));
+    return pass_at(h, A, lda, T, Z);
+  }
+  Streamer st(h, A, lda);
+  for (int i = 0; i < h->nblocks; ++i) {
+    const float* blk;
+    BRSVD_TRY(st.acquire(i, &blk));
+    float* Ti = T + (int64_t)i * h->b * Lp;
+    KernelEvents ke;
+    bool t = kernel_events(h, CAT_AN, &ke);
+    BRSVD_TRY(gemm_an(blk, n, st.rows_of(i), n, X, Lp, Ti, Lp, Lp, scr, h->lay.gemm_scratch_bytes, h->compute,
+                      t ? &ke : nullptr));
+    t = kernel_events(h, CAT_AT, &ke);
+    BRSVD_TRY(gemm_at(blk, n, st.rows_of(i), n, Ti, Lp, Z, i > 0, st.rows_of(i), scr, h->lay.gemm_scratch_bytes,
+                      h->compute, t ? &ke : nullptr));
+    BRSVD_TRY(st.release(i));
+  }
+  return BRSVD_OK;
+}
+
 // The whole factorisation, enqueued asynchronously on the handle's streams.
 int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S,
                   float* Vt, int method) {
@@ -304,29 +332,50 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
   float* res;
 
   BRSVD_TRY(pad_panel(Omega, n, l, Xn, Lp, cs));
-  BRSVD_TRY(pass_an(h, A, lda, Xn, Ym));
-  {
-    Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, q == 0, ow, nullptr, &res, cs));
-    if (res != Ym) std::swap(Ym, Tm);
-  }
-  for (int it = 0; it < q; ++it) {
-    BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
-    {
+  if (h->prm.pass_mode == BRSVD_PASSES_FUSED) {
+    // q passes Z = A^T (A X), X <- orth(Z), then one pass Y = A X, C^T = A^T Y; with Y = Q R the
+    // projection is B^T = A^T Q = C^T R^-1, so R^-1 is applied to both panels.
+    for (int it = 0; it < q; ++it) {
+      BRSVD_TRY(pass_fused(h, A, lda, Xn, Ym, Tn));
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, false, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel(Tn, Xn, n, l, Lp, method, false, ow, nullptr, &res, cs));
       if (res != Xn) std::swap(Xn, Tn);
     }
-    BRSVD_TRY(pass_an(h, A, lda, Xn, Tm));
-    std::swap(Ym, Tm);
+    BRSVD_TRY(pass_fused(h, A, lda, Xn, Ym, Tn));
     {
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, it == q - 1, ow, nullptr, &res, cs));
+      ow.comp = Tn; ow.comp_tmp = Xn; ow.comp_rows = n;
+      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, true, ow, nullptr, &res, cs));
+      if (res != Ym) std::swap(Ym, Tm);
+      Xn = ow.comp; Tn = ow.comp_tmp;     // B^T and a free n x Lp buffer
+      ow.comp = ow.comp_tmp = nullptr; ow.comp_rows = 0;
+    }
+  } else {
+    BRSVD_TRY(pass_an(h, A, lda, Xn, Ym));
+    {
+      Region r(h, CAT_ORTH, cs);
+      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, q == 0, ow, nullptr, &res, cs));
       if (res != Ym) std::swap(Ym, Tm);
     }
+    for (int it = 0; it < q; ++it) {
+      BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+      {
+        Region r(h, CAT_ORTH, cs);
+        BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, false, ow, nullptr, &res, cs));
+        if (res != Xn) std::swap(Xn, Tn);
+      }
+      BRSVD_TRY(pass_an(h, A, lda, Xn, Tm));
+      std::swap(Ym, Tm);
+      {
+        Region r(h, CAT_ORTH, cs);
+        BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, it == q - 1, ow, nullptr, &res, cs));
+        if (res != Ym) std::swap(Ym, Tm);
+      }
+    }
+    // projection B^T = A^T Q
+    BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
   }
-  // projection B^T = A^T Q, its thin QR, the small SVD, the lifts
-  BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+  // thin QR of B^T, the small SVD, the lifts
   double* Rtot = h->at<double>(h->lay.Rtot);
   {
     Region r(h, CAT_ORTH, cs);
@@ -351,6 +400,10 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
     BRSVD_TRY(transpose_panel(Tn, n, Lp, l, Vt, cs));
   }
   return BRSVD_OK;
+}
+
+int passes_per_run(brsvd_handle h) {
+  return h->prm.pass_mode == BRSVD_PASSES_FUSED ? h->prm.q + 1 : 2 * h->prm.q + 2;
 }
 
 void reset_timing(brsvd_handle h, bool on) {
@@ -539,7 +592,7 @@ int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, f
   }
   if (stats) {
     (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, (2 * h->prm.q + 2) * (1 + fallbacks), fallbacks);
+    fill_stats(h, stats, passes_per_run(h) * (1 + fallbacks), fallbacks);
   }
   return status;
 }
@@ -580,7 +633,7 @@ int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t
   BRSVD_HIP_TRY(hipStreamSynchronize(cs));
   const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
   if (!(normF > 0.0)) return BRSVD_ERR_ARG;
-  const int passes1 = 2 * h->prm.q + 2;
+  const int passes1 = passes_per_run(h);
   if (!(norm2_M > 0.0)) {
     int fb = 0;
     {

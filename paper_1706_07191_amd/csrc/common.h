@@ -73,7 +73,14 @@ struct OrthWork {
   uint64_t gemm_scratch_bytes;
   void* tsqr_work;     // TSQR scratch
   uint64_t tsqr_bytes;
+  // Optional companion panel (comp_rows x Lp): every R^-1 applied to the panel being orthonormalised
+  // is applied to it as well (comp <- comp * R^-1, ping-ponging with comp_tmp; the result is in comp).
+  float* comp = nullptr;
+  float* comp_tmp = nullptr;
+  int64_t comp_rows = 0;
 };
+// Applies the current w.Rinv to the companion panel, if any.
+int apply_to_companion(OrthWork& w, int Lp, hipStream_t stream);
 uint64_t orth_gram_chunks(int64_t rows);
 uint64_t tsqr_work_bytes(int64_t rows, int Lp);
 // Orthonormalises the columns of P (rows x Lp padded panel, rows >= l).  tmp is a second

@@ -471,6 +471,14 @@ int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, floa
   return chol_inv(G, l, Lp, Rout, Xtmp, Rinv32, flags, 0.0, stream, 1);
 }
 
+int apply_to_companion(OrthWork& w, int Lp, hipStream_t stream) {
+  if (!w.comp) return BRSVD_OK;
+  BRSVD_TRY(gemm_an(w.comp, Lp, w.comp_rows, Lp, w.Rinv, Lp, w.comp_tmp, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes,
+                    stream));
+  float* t = w.comp; w.comp = w.comp_tmp; w.comp_tmp = t;
+  return BRSVD_OK;
+}
+
 int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream) {
   hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream, R2, R1, l, Lp,
                      Rtot);
@@ -487,6 +495,7 @@ int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps
     BRSVD_TRY(gram(src, rows, Lp, w, stream));
     BRSVD_TRY(chol_inv(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream));
     BRSVD_TRY(gemm_an(src, Lp, rows, Lp, w.Rinv, Lp, dst, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
+    BRSVD_TRY(apply_to_companion(w, Lp, stream));
     float* t = src; src = dst; dst = t;
   }
   *result = src;

@@ -147,6 +147,7 @@ int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, d
   double* Rt = stack[cur ^ 1];    // free now: keeps the TSQR factor for the product R2 * R
   BRSVD_TRY(chol_inv_factored(w.G, l, Lp, Rt, w.Xinv, w.Rinv, w.flags, stream));
   BRSVD_TRY(gemm_an(P, Lp, rows, Lp, w.Rinv, Lp, tmp, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
+  BRSVD_TRY(apply_to_companion(w, Lp, stream));
   float* res = nullptr;
   BRSVD_TRY(cholqr_sweeps(tmp, P, rows, l, Lp, 1, w, nullptr, &res, stream));
   *result = res;

@@ -40,14 +40,14 @@ def test_status_strings():
 def _p(**kw):
     base = dict(m=2000, n=1000, k=20, p=10, q=2, row_block=512)
     base.update(kw)
-    return B.brsvd_params(a_location=kw.pop("a_location", 0), reserved=0, orth_method=0,
+    return B.brsvd_params(a_location=kw.pop("a_location", 0), pass_mode=base.pop("pass_mode", 0), orth_method=0,
                           device_budget_bytes=base.pop("device_budget_bytes", 0),
                           compute_stream=None, copy_stream=None, **{k: v for k, v in base.items()
                                                                     if k not in ("a_location",)})
 
 
 @pytest.mark.parametrize("bad", [dict(m=0), dict(n=-1), dict(k=0), dict(p=-1), dict(q=-1),
-                                 dict(k=600, p=0), dict(m=20, n=1000), dict(row_block=-5)])
+                                 dict(k=600, p=0), dict(m=20, n=1000), dict(row_block=-5), dict(pass_mode=7)])
 def test_invalid_params_rejected(bad):
     out = C.c_uint64(0)
     assert B.lib().brsvd_workspace_bytes(C.byref(_p(**bad)), C.byref(out)) == B.BRSVD_ERR_ARG

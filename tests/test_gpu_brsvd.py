@@ -10,10 +10,11 @@ from tests.gpu_util import check_against_oracle, need_gpu
 pytestmark = pytest.mark.gpu
 
 
-def _run(cfg, A_dev, Om_dev, row_block=None, a_location=B.BRSVD_A_DEVICE, budget=0, orth=B.BRSVD_ORTH_AUTO):
+def _run(cfg, A_dev, Om_dev, row_block=None, a_location=B.BRSVD_A_DEVICE, budget=0, orth=B.BRSVD_ORTH_AUTO,
+         pass_mode=B.BRSVD_PASSES_SEPARATE):
     m, n = cfg.m, cfg.n
     prm = B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block if row_block is None else row_block,
-                        a_location=a_location, device_budget_bytes=budget, orth_method=orth)
+                        a_location=a_location, device_budget_bytes=budget, orth_method=orth, pass_mode=pass_mode)
     h = B.brsvd_create(prm)
     try:
         U, S, Vt, st = B.brsvd_run(h, A_dev, Om_dev)
@@ -57,6 +58,36 @@ def test_forced_tsqr_matches_oracle():
     U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), orth=B.BRSVD_ORTH_TSQR)
     assert st["orth_fallbacks"] == 0
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 700, U, S, Vt, "C2-tsqr")
+
+
+@pytest.mark.parametrize("name,m,n,b,q", [("C2", 3000, 2500, 700, 2), ("C3", 4000, 3000, 1024, 1),
+                                           ("C1", 2000, 1000, 512, 2), ("C1", 1500, 800, 333, 0)])
+def test_fused_passes_match_oracle(name, m, n, b, q):
+    """q+1 reads of A instead of 2q+2: both products of a power step from one resident block, projection
+    recovered as C^T R^-1.  Same range(Y) in exact arithmetic, so the same oracle applies."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS[name].scaled(m, n, b)
+    cfg.q = q
+    A = cfg.make_A()
+    Om = cfg.make_Omega()
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), pass_mode=B.BRSVD_PASSES_FUSED)
+    assert st["passes_over_A"] == q + 1 and st["bytes_A_streamed"] == (q + 1) * 4 * m * n
+    assert st["gemm_an_launches"] == q + 1 and st["gemm_at_launches"] == q + 1
+    check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, q, b, U, S, Vt, f"{cfg.name}-fused-q{q}")
+
+
+def test_fused_passes_host_resident_and_tsqr():
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C4"].scaled(3000, 3500, 900)
+    A = cfg.make_A()
+    Om = cfg.make_Omega()
+    Ap = torch.empty(cfg.m, cfg.n, dtype=torch.float32, pin_memory=True)
+    Ap.copy_(A)
+    U, S, Vt, st = _run(cfg, Ap, Om.to(dev), a_location=B.BRSVD_A_HOST_PINNED, pass_mode=B.BRSVD_PASSES_FUSED)
+    assert st["passes_over_A"] == 2 and st["n_blocks"] == 4 and st["gemm_an_launches"] == 8
+    check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 900, U, S, Vt, "C4-host-fused")
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), orth=B.BRSVD_ORTH_TSQR, pass_mode=B.BRSVD_PASSES_FUSED)
+    check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 900, U, S, Vt, "C4-fused-tsqr")
 
 
 def test_block_size_independence_and_determinism():
