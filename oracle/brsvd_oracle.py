@@ -180,3 +180,49 @@ def rpca_ialm(M, Omegas, k: int, p: int, q: int, iters: int, lam: float, mu0: fl
         res.append(float(np.linalg.norm(Z) / normM))
         mu *= rho
     return L, S, np.array(res)
+
+
+def rpca_ialm_tol(M, Omegas, k: int, p: int, q: int, max_iters: int, tol: float, lam: float, mu0: float,
+                  rho: float, row_block: int = 0):
+    """Alg. 3 with its own stopping rule: after the multiplier update of an iteration the loop is
+    left as soon as ||M - L - S||_F / ||M||_F < tol (mu is not advanced any more); max_iters bounds
+    the loop (Omegas must hold at least that many test matrices).  Same readings as rpca_ialm.
+    Returns L, S, the residual of every iteration run, and the number of iterations run.
+    """
+    M = np.asarray(M, dtype=np.float64)
+    normM = np.linalg.norm(M)
+    J = max(np.linalg.norm(M, 2), np.max(np.abs(M)) / lam)
+    Y = M / J
+    S = np.zeros_like(M)
+    L = np.zeros_like(M)
+    mu = float(mu0)
+    res = []
+    i = 0
+    while i < max_iters:
+        U, s, Vt = brsvd(M - S + Y / mu, Omegas[i], k, p, q, row_block)
+        L = (U * shrink(s, 1.0 / mu)) @ Vt
+        S = shrink(M - L + Y / mu, lam / mu)
+        Z = M - L - S
+        Y = Y + mu * Z
+        res.append(float(np.linalg.norm(Z) / normM))
+        i += 1
+        if res[-1] < tol:
+            break
+        mu = rho * mu
+    return L, S, np.array(res), i
+
+
+def norm2_power(A, x0, iters: int) -> float:
+    """Spectral norm ||A||_2 (needed by the multiplier initialisation of Alg. 3) by the power
+    method on A^T A: x <- x0 / |x0|; repeat iters times { y = A x; est = |y|; x = A^T y / |A^T y| }.
+    Returns the last est (a lower bound of ||A||_2 that increases monotonically)."""
+    A = np.asarray(A, dtype=np.float64)
+    x = np.asarray(x0, dtype=np.float64).reshape(-1)
+    x = x / np.linalg.norm(x)
+    est = 0.0
+    for _ in range(iters):
+        y = A @ x
+        est = float(np.linalg.norm(y))
+        z = A.T @ y
+        x = z / np.linalg.norm(z)
+    return est
