@@ -126,6 +126,25 @@ int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t
                     float lambda, float mu0, float rho, double norm2_M,
                     float* L, float* S, float* work, double* residuals, brsvd_stats* stats);
 
+/* The same iteration with the stopping rule of Alg. 3: the loop is left after the first iteration
+ * whose residual ||M-L-S||_F / ||M||_F is below tol (tol >= 0; the multiplier update of that
+ * iteration is done, mu is not advanced), or after max_iters iterations.  Omegas holds max_iters
+ * test matrices; residuals (HOST, may be NULL) has room for max_iters doubles, of which the first
+ * *iters_done are written; iters_done (HOST, may be NULL) receives the number of iterations run.
+ * brsvd_rpca_ialm is this call with tol = 0. */
+int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int32_t max_iters,
+                        double tol, float lambda, float mu0, float rho, double norm2_M,
+                        float* L, float* S, float* work, double* residuals, int32_t* iters_done,
+                        brsvd_stats* stats);
+
+/* Spectral norm ||A||_2, the scale of the multiplier initialisation of Alg. 3, by the power method
+ * on A^T A: x = x0/|x0|; iters times { y = A x; est = |y|; x = A^T y / |A^T y| }; *norm2_out (HOST)
+ * receives the last est, a lower bound of ||A||_2 that grows with iters.  Two reads of A per
+ * iteration.  A: DEVICE, m x n of the handle (a_location must be BRSVD_A_DEVICE), leading
+ * dimension lda; x0: DEVICE, n floats, not zero.  Synchronises compute_stream. */
+int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* x0, int32_t iters,
+                      double* norm2_out);
+
 /* Frees everything the handle owns (never the caller's buffers).  NULL is allowed. */
 int brsvd_destroy(brsvd_handle h);
 

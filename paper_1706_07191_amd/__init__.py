@@ -52,7 +52,8 @@ class brsvd_stats(C.Structure):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
-EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_destroy",
+EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
+           "brsvd_norm2_power", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_orth", "brsvd_small_svd"]
 
@@ -80,6 +81,9 @@ def lib() -> C.CDLL:
     L.brsvd_run.argtypes = [vp, vp, i64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
     L.brsvd_rpca_ialm.argtypes = [vp, vp, vp, i32, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
                                   C.POINTER(brsvd_stats)]
+    L.brsvd_rpca_ialm_tol.argtypes = [vp, vp, vp, i32, dbl, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
+                                      C.POINTER(i32), C.POINTER(brsvd_stats)]
+    L.brsvd_norm2_power.argtypes = [vp, vp, i64, vp, i32, C.POINTER(dbl)]
     L.brsvd_destroy.argtypes = [vp]
     L.brsvd_status_string.argtypes = [C.c_int]
     L.brsvd_status_string.restype = C.c_char_p
@@ -185,6 +189,33 @@ def brsvd_rpca_ialm(handle, M, Omegas, iters, lam, mu0, rho, norm2_M=0.0, L=None
                                    C.byref(st))
     _check(status, "brsvd_rpca_ialm")
     return L, S, list(res), st.as_dict()
+
+
+def brsvd_rpca_ialm_tol(handle, M, Omegas, max_iters, tol, lam, mu0, rho, norm2_M=0.0, L=None, S=None, work=None):
+    """Returns L, S, the residuals of the iterations run, their number, and the statistics."""
+    import torch
+    m, n = M.shape
+    L = torch.empty_like(M) if L is None else L
+    S = torch.empty_like(M) if S is None else S
+    work = torch.empty(2 * m * n, device=M.device) if work is None else work
+    res = (C.c_double * max_iters)()
+    done = C.c_int32(0)
+    st = brsvd_stats()
+    status = lib().brsvd_rpca_ialm_tol(handle, _dev(M, torch.float32, "M"), _dev(Omegas, torch.float32, "Omegas"),
+                                       max_iters, tol, lam, mu0, rho, norm2_M, _dev(L, torch.float32, "L"),
+                                       _dev(S, torch.float32, "S"), _dev(work, torch.float32, "work"), res,
+                                       C.byref(done), C.byref(st))
+    _check(status, "brsvd_rpca_ialm_tol")
+    return L, S, list(res)[:done.value], done.value, st.as_dict()
+
+
+def brsvd_norm2_power(handle, A, x0, iters, lda=None) -> float:
+    import torch
+    out = C.c_double(0.0)
+    lda = A.stride(0) if lda is None else lda
+    _check(lib().brsvd_norm2_power(handle, A.data_ptr(), lda, _dev(x0, torch.float32, "x0"), iters, C.byref(out)),
+           "brsvd_norm2_power")
+    return out.value
 
 
 def brsvd_gemm_scratch_bytes(rows, n, l) -> int:

@@ -97,11 +97,15 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
     gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp));
     gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b));
   }
+  if (!host) {   // single-vector products of the spectral-norm power method (16-column panels)
+    gs = std::max(gs, gemm_an_scratch_bytes(m, n, kTile));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, b));
+  }
   gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp));
   gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp));
   L.gemm_scratch_bytes = gs;
   L.gemm_scratch = take(gs);
-  L.gram_chunks = (int)std::max(orth_gram_chunks(m), orth_gram_chunks(n));
+  L.gram_chunks = (int)std::max(orth_gram_slots(m, Lp), orth_gram_slots(n, Lp));
   L.gram_part = take((uint64_t)L.gram_chunks * Lp * Lp * 8);
   const uint64_t sq8 = (uint64_t)Lp * Lp * 8, sq4 = (uint64_t)Lp * Lp * 4;
   L.G = take(sq8); L.R0 = take(sq8); L.R1 = take(sq8); L.Xinv = take(sq8); L.Rtot = take(sq8);
@@ -597,11 +601,12 @@ int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, f
   return status;
 }
 
-int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t iters, float lambda, float mu0,
-                    float rho, double norm2_M, float* L, float* S, float* work, double* residuals,
-                    brsvd_stats* stats) {
-  if (!h || !M || !Omegas || !L || !S || !work || iters < 1) return BRSVD_ERR_ARG;
-  if (h->host_a || !(lambda > 0.f) || !(mu0 > 0.f) || !(rho > 1.f)) return BRSVD_ERR_ARG;
+int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int32_t max_iters, double tol,
+                        float lambda, float mu0, float rho, double norm2_M, float* L, float* S, float* work,
+                        double* residuals, int32_t* iters_done, brsvd_stats* stats) {
+  if (iters_done) *iters_done = 0;
+  if (!h || !M || !Omegas || !L || !S || !work || max_iters < 1) return BRSVD_ERR_ARG;
+  if (h->host_a || !(lambda > 0.f) || !(mu0 > 0.f) || !(rho > 1.f) || !(tol >= 0.0)) return BRSVD_ERR_ARG;
   const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
   const int l = h->l;
   hipStream_t cs = h->compute;
@@ -652,25 +657,76 @@ int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t
     Region r(h, CAT_ELEM, cs);
     BRSVD_TRY(rpca_init(M, count, (float)(1.0 / J), (float)(1.0 / mu), Y, S, X, cs));
   }
-  for (int it = 0; it < iters; ++it) {
+  int it = 0;
+  double mu_last = mu;
+  while (it < max_iters) {
     int fb = 0;
     const double mu_next = mu * (double)rho;
+    mu_last = mu;
     {
       Region total(h, CAT_TOTAL, cs);
       BRSVD_TRY(run_sync(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
       {
         Region r(h, CAT_ELEM, cs);
-        BRSVD_TRY(rpca_update(M, Uw, Sw, Vtw, m, n, l, (float)mu, lambda, (float)mu_next,
-                              it == iters - 1 ? L : nullptr, S, Y, X, part, scal + 2, cs));
+        BRSVD_TRY(rpca_update(M, Uw, Sw, Vtw, m, n, l, (float)mu, lambda, (float)mu_next, nullptr, S, Y, X, part,
+                              scal + 2, cs));
       }
       BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
       BRSVD_HIP_TRY(hipStreamSynchronize(cs));
     }
-    if (residuals) residuals[it] = std::sqrt(h->host_scal[2]) / normF;
+    const double res = std::sqrt(h->host_scal[2]) / normF;
+    if (residuals) residuals[it] = res;
     flush_stats(passes1 * (1 + fb), fb);
+    ++it;
+    if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
     mu = mu_next;
   }
+  // L of the last iteration run: its triplets and its mu are still in place
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_lowrank(Uw, Sw, Vtw, m, n, l, (float)mu_last, L, cs));
+  }
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  flush_stats(0, 0);
+  if (iters_done) *iters_done = it;
   if (stats) *stats = acc;
+  return BRSVD_OK;
+}
+
+int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t iters, float lambda, float mu0,
+                    float rho, double norm2_M, float* L, float* S, float* work, double* residuals,
+                    brsvd_stats* stats) {
+  return brsvd_rpca_ialm_tol(h, M, Omegas, iters, 0.0, lambda, mu0, rho, norm2_M, L, S, work, residuals, nullptr,
+                             stats);
+}
+
+int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* x0, int32_t iters,
+                      double* norm2_out) {
+  if (!h || !A || !x0 || !norm2_out || iters < 1 || lda < h->prm.n || h->host_a) return BRSVD_ERR_ARG;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  const int L1 = kTile;                 // the vector travels as column 0 of a 16-column padded panel
+  hipStream_t cs = h->compute;
+  float* xn = h->Pn(0);
+  float* zn = h->Pn(1);
+  float* ym = h->Pm(0);
+  void* scr = h->arena + h->lay.gemm_scratch;
+  const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
+  double* part = h->at<double>(h->lay.rpca_part);
+  double* scal = h->at<double>(h->lay.scal);
+  BRSVD_TRY(pad_panel(x0, n, 1, xn, L1, cs));
+  BRSVD_TRY(rpca_norms(xn, n * L1, part, scal, cs));
+  BRSVD_TRY(scale_rsqrt(xn, n * L1, scal + 1, cs));
+  for (int it = 0; it < iters; ++it) {
+    BRSVD_TRY(gemm_an(A, lda, m, n, xn, L1, ym, L1, L1, scr, scr_bytes, cs));              // y = A x
+    BRSVD_TRY(rpca_norms(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
+    BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, h->b, scr, scr_bytes, cs));         // z = A^T y
+    BRSVD_TRY(rpca_norms(zn, n * L1, part, scal + 4, cs));
+    BRSVD_TRY(scale_rsqrt(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
+    std::swap(xn, zn);
+  }
+  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal + 3, sizeof(double), hipMemcpyDeviceToHost, cs));
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  *norm2_out = std::sqrt(h->host_scal[0]);
   return BRSVD_OK;
 }
 
@@ -734,7 +790,7 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int
   hipStream_t s = (hipStream_t)stream;
   const uint64_t panel = align_up((uint64_t)rows * Lp * 4);
   const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8), sq4 = align_up((uint64_t)Lp * Lp * 4);
-  const int chunks = (int)orth_gram_chunks(rows);
+  const int chunks = (int)orth_gram_slots(rows, Lp);
   const uint64_t gs = align_up(gemm_an_scratch_bytes(rows, Lp, Lp));
   const uint64_t tb = align_up(tsqr_work_bytes(rows, Lp));
   const uint64_t total = 2 * panel + (uint64_t)chunks * sq8 + 5 * sq8 + sq4 + 256 + gs + tb;

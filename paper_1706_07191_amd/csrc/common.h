@@ -62,7 +62,7 @@ int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, h
 
 // ---- orthonormalisation (orth.hip, tsqr.hip) -----------------------------------------------
 struct OrthWork {
-  double* gram_part;   // gram_chunks_max x Lp x Lp partial Gram matrices
+  double* gram_part;   // gram_chunks_max slots of Lp x Lp partial Gram sums (orth_gram_slots)
   int gram_chunks_max;
   double* G;           // Lp x Lp
   double* R[2];        // upper-triangular factors of the two CholeskyQR sweeps (stride Lp)
@@ -81,7 +81,7 @@ struct OrthWork {
 };
 // Applies the current w.Rinv to the companion panel, if any.
 int apply_to_companion(OrthWork& w, int Lp, hipStream_t stream);
-uint64_t orth_gram_chunks(int64_t rows);
+uint64_t orth_gram_slots(int64_t rows, int Lp);   // Lp x Lp fp64 slots of partial Gram sums for such a panel
 uint64_t tsqr_work_bytes(int64_t rows, int Lp);
 // Orthonormalises the columns of P (rows x Lp padded panel, rows >= l).  tmp is a second
 // rows x Lp buffer; *result is set to whichever of P / tmp holds the orthonormal panel.
@@ -119,5 +119,11 @@ int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y
 int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n,
                 int l, float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X,
                 double* part, double* resid2_out, hipStream_t stream);
+
+// Lout = U diag(shrink(sig, 1/mu)) Vt, the low-rank part of the iteration that used (U, sig, Vt, mu).
+int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l, float mu,
+                 float* Lout, hipStream_t stream);
+// P[0..count) *= 1 / sqrt(*s2) (device scalar; a zero scalar zeroes P).
+int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream);
 
 }  // namespace brsvd

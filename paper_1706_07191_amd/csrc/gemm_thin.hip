@@ -337,6 +337,18 @@ __global__ void k_reduce_splits(const T* __restrict__ part, int nsplit, int64_t 
   out[row * ldo + col] = s;
 }
 
+// In-place first level of a long split sum: slot g*fan <- sum of the slots [g*fan, min((g+1)*fan, nsplit))
+// in slot order (blockIdx.y = g).  Each thread only touches its own element of every slot.
+__global__ void k_reduce_groups_inplace(float* __restrict__ part, int nsplit, int fan, int64_t split_stride) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= split_stride) return;
+  const int s0 = blockIdx.y * fan, s1 = min(nsplit, s0 + fan);
+  float* p = part + idx;
+  float s = p[(int64_t)s0 * split_stride];
+  for (int i = s0 + 1; i < s1; ++i) s += p[(int64_t)i * split_stride];
+  p[(int64_t)s0 * split_stride] = s;
+}
+
 __global__ void k_pad_panel(const float* __restrict__ src, int64_t rows, int l, float* __restrict__ dst,
                             int Lp) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -516,10 +528,21 @@ static int launch_an(int nt, bool vec, const float* A, int64_t lda, int rows, in
 #undef CALL
 }
 
-static int reduce_f32(const float* part, int nsplit, int64_t split_stride, int64_t rows, int ncols,
+// Sum of the split partial panels in split order; long sums (more than kReduceFan splits) are taken in
+// two levels, groups of kReduceFan consecutive splits first, so that no thread walks thousands of
+// slots serially.  Either way the association is fixed by the plan, not by timing.
+constexpr int kReduceFan = 16;
+static int reduce_f32(float* part, int nsplit, int64_t split_stride, int64_t rows, int ncols,
                       int64_t ldi, float* out, int64_t ldo, bool accumulate, hipStream_t stream) {
   int64_t total = rows * ncols;
   if (total == 0) return BRSVD_OK;
+  if (nsplit > 2 * kReduceFan) {
+    const int groups = (int)ceil_div(nsplit, kReduceFan);
+    hipLaunchKernelGGL(k_reduce_groups_inplace, dim3((unsigned)ceil_div(split_stride, 256), groups), dim3(256), 0,
+                       stream, part, nsplit, kReduceFan, split_stride);
+    nsplit = groups;
+    split_stride *= kReduceFan;
+  }
   hipLaunchKernelGGL(k_reduce_splits<float>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
                      part, nsplit, split_stride, rows, ncols, ldi, out, ldo, accumulate ? 1 : 0);
   BRSVD_HIP_TRY(hipGetLastError());
@@ -555,29 +578,37 @@ int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X
   }
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
   if (p.ksplit > 1)
-    BRSVD_TRY(reduce_f32((const float*)scratch, p.ksplit, rows * Lp, rows, ncols, Lp, Y, ldy, false, stream));
+    BRSVD_TRY(reduce_f32((float*)scratch, p.ksplit, rows * Lp, rows, ncols, Lp, Y, ldy, false, stream));
   return BRSVD_OK;
 }
 
 // ---- gemm_at ----
 struct AtPlan {
-  int mt, col_tiles, nblocks, sub, rows_per_sub, nsplit;
+  int mt, waves, col_tiles, nblocks, sub, rows_per_sub, nsplit;
 };
 static int at_mt(int nt) { return nt <= 8 ? 4 : 2; }
 constexpr int kAtWaves = 8;
 constexpr int kAtKC = 32;
+// Narrow A (tall-skinny inputs, n of a few hundred at most) with a narrow panel: workgroups of two
+// waves (128 columns), so that no wave multiplies clamped duplicate columns and the row range can be
+// cut into enough workgroups to fill the chip.
+constexpr int kAtNarrowWaves = 2;
+constexpr int kAtNarrowMaxNT = 4;
+constexpr int kAtNarrowMaxN = 256;
+static int at_waves(int64_t n, int nt) { return (nt <= kAtNarrowMaxNT && n <= kAtNarrowMaxN) ? kAtNarrowWaves : kAtWaves; }
 
 static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
   AtPlan p;
   p.mt = at_mt(nt);
-  p.col_tiles = (int)ceil_div(n, kAtWaves * p.mt * 16);
+  p.waves = at_waves(n, nt);
+  p.col_tiles = (int)ceil_div(n, p.waves * p.mt * 16);
   if (block_rows <= 0 || block_rows > rows) block_rows = rows;
   p.nblocks = (int)ceil_div(rows, block_rows);
   const int max_sub = (int)ceil_div(block_rows, kAtKC);
   const int ld = nt * 16 + ((16 - (nt * 16) % 64) + 64) % 64;
   const int lds_bytes = 2 * kAtKC * ld * 4;
   // one partial panel (n x Lp) per split, against block_rows x n of A read per block
-  const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, 1), max_sub,
+  const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, p.waves == kAtWaves ? 1 : 8), max_sub,
                                (double)(nt * 16) / (double)block_rows, traffic_weight(nt), "BRSVD_AT_SPLITS");
   int64_t rps = ceil_div(block_rows, want);
   rps = ceil_div(rps, kAtKC) * kAtKC;
@@ -593,11 +624,11 @@ uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_ro
   return (uint64_t)p.nsplit * n * Lp * sizeof(float);
 }
 
-template <int NT, int MT, bool VEC>
+template <int NT, int MT, int WAVES, bool VEC>
 static int launch_at_inst(const float* A, int64_t lda, int64_t rows, int n, const float* Q, int ldq,
                           float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
                           hipStream_t stream) {
-  auto kern = k_gemm_at<NT, MT, kAtWaves, kAtKC, VEC>;
+  auto kern = k_gemm_at<NT, MT, WAVES, kAtKC, VEC>;
   constexpr int LD = NT * 16 + ((16 - (NT * 16) % 64) + 64) % 64;
   constexpr int lds_bytes = 2 * kAtKC * LD * (int)sizeof(float);
   static bool attr_set = false;
@@ -607,7 +638,7 @@ static int launch_at_inst(const float* A, int64_t lda, int64_t rows, int n, cons
     attr_set = true;
   }
   dim3 grid(p.col_tiles, p.nsplit);
-  hipLaunchKernelGGL(kern, grid, dim3(kAtWaves * 64), lds_bytes, stream, A, lda, rows, n, Q, ldq, Zp, ldz,
+  hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds_bytes, stream, A, lda, rows, n, Q, ldq, Zp, ldz,
                      split_stride, block_rows, p.sub, p.rows_per_sub);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
@@ -618,9 +649,20 @@ static int launch_at_nt(bool vec, const float* A, int64_t lda, int64_t rows, int
                         float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
                         hipStream_t stream) {
   constexpr int MT = NT <= 8 ? 4 : 2;
+  if constexpr (NT <= kAtNarrowMaxNT) {
+    if (p.waves == kAtNarrowWaves) {
+      if (vec)
+        return launch_at_inst<NT, MT, kAtNarrowWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
+                                                            block_rows, p, stream);
+      return launch_at_inst<NT, MT, kAtNarrowWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
+                                                           block_rows, p, stream);
+    }
+  }
   if (vec)
-    return launch_at_inst<NT, MT, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
-  return launch_at_inst<NT, MT, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
+    return launch_at_inst<NT, MT, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                  stream);
+  return launch_at_inst<NT, MT, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                 stream);
 }
 
 static int launch_at(int nt, bool vec, const float* A, int64_t lda, int64_t rows, int n, const float* Q,
@@ -644,8 +686,8 @@ int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q
   const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && (n % 4 == 0) && n >= 4;
   float* part = (float*)scratch;
   if (verbose())
-    fprintf(stderr, "[brsvd] gemm_at rows=%ld n=%ld Lp=%d: %d col tiles x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
-            (long)rows, (long)n, Lp, p.col_tiles, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
+    fprintf(stderr, "[brsvd] gemm_at rows=%ld n=%ld Lp=%d: %d col tiles (%d waves) x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
+            (long)rows, (long)n, Lp, p.col_tiles, p.waves, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;

@@ -12,84 +12,88 @@
 
 namespace brsvd {
 
-template <typename T>
-__global__ void k_reduce_splits_t(const T* __restrict__ part, int nsplit, int64_t split_stride,
-                                  int64_t count, T* __restrict__ out) {
-  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= count) return;
-  T s = T(0);
-#pragma unroll 8
-  for (int i = 0; i < nsplit; ++i) s += part[(int64_t)i * split_stride + idx];
-  out[idx] = s;
+// ---- Gram matrix -----------------------------------------------------------------------------
+// G = P^T P on the fp64 matrix cores (v_mfma_f64_16x16x4_f64; products of fp32 values are exact in
+// fp64).  G is cut into blocks of TB x TB tiles of 16 x 16; grid = (row chunks, pairs bi <= bj of
+// blocks).  For a step of four panel rows, lane (r, g) of a wave holds P[row + g][16*tile + r] for
+// each tile of the two blocks: that value is at once the A operand (entry [i = r][k = g] of the
+// transposed tile) and the B operand ([k = g][j = r]), so the panel goes from global memory straight
+// into the MFMA operands.  The eight waves of a workgroup take the steps of the chunk round-robin and
+// add their accumulators through LDS in wave order; chunks are added by the caller in chunk order.
+// Accumulator layout of the instruction: component v of lane (r, g) is entry [g + 4*v][r].
+constexpr int kGramWaves = 8;
+constexpr int kGramRowStep = 4 * kGramWaves;
+
+__device__ __forceinline__ doublex4 mfma_f64(double a, double b, doublex4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
-// ---- Gram matrix -----------------------------------------------------------------------------
-// grid = (row chunks, pairs (bi <= bj) of 64-column blocks); 256 threads, thread (ty, tx) owns
-// the 4x4 entries G[64*bi + 4*ty + i][64*bj + 4*tx + j] of this chunk's partial sum.
-constexpr int kGramRC = 32;
-
-__global__ void __launch_bounds__(256)
-k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk,
-       double* __restrict__ Gpart) {
-  __shared__ float sI[kGramRC][64];
-  __shared__ float sJ[kGramRC][64];
-  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-  // decode the block pair
-  int nb = (Lp + 63) / 64;
+template <int TB>
+__global__ void __launch_bounds__(kGramWaves * 64)
+k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk, double* __restrict__ Gpart) {
+  __shared__ double red[kGramWaves][256];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, g = lane >> 4;
+  const int NT = Lp / 16, nb = (NT + TB - 1) / TB;
   int bi = 0, rem = blockIdx.y;
   while (rem >= nb - bi) { rem -= nb - bi; ++bi; }
   const int bj = bi + rem;
+  const int ti_n = min(TB, NT - bi * TB), tj_n = min(TB, NT - bj * TB);
+  const bool diag = bi == bj;
   const int64_t rbeg = (int64_t)blockIdx.x * rows_per_chunk;
   const int64_t rend = min(rows, rbeg + rows_per_chunk);
+  const float* pi = P + 16 * (bi * TB) + r;
+  const float* pj = P + 16 * (bj * TB) + r;
 
-  double acc[4][4];
+  doublex4 acc[TB][TB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TB; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    for (int j = 0; j < TB; ++j) acc[i][j] = doublex4{0.0, 0.0, 0.0, 0.0};
 
-  for (int64_t r0 = rbeg; r0 < rend; r0 += kGramRC) {
-    // kGramRC x 64 floats per operand = 512 float4, two per thread
+  float an[TB], bn[TB];
+  auto load = [&](int64_t row0) {
+    const int64_t row = row0 + g;
+    const bool valid = row < rend;
+    const int64_t off = (valid ? row : rbeg) * Lp;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      int idx = tid + t * 256;
-      int rr = idx >> 4, c4 = (idx & 15) * 4;
-      int64_t row = r0 + rr;
-      floatx4 vi = floatx4{0.f, 0.f, 0.f, 0.f}, vj = vi;
-      if (row < rend) {
-        if (bi * 64 + c4 < Lp) vi = *(const floatx4*)(P + row * Lp + bi * 64 + c4);
-        if (bj * 64 + c4 < Lp) vj = *(const floatx4*)(P + row * Lp + bj * 64 + c4);
-      }
-      *(floatx4*)&sI[rr][c4] = vi;
-      *(floatx4*)&sJ[rr][c4] = vj;
+    for (int t = 0; t < TB; ++t) {
+      an[t] = (valid && t < ti_n) ? pi[off + 16 * t] : 0.f;
+      bn[t] = (valid && t < tj_n && !diag) ? pj[off + 16 * t] : 0.f;
     }
-    __syncthreads();
-#pragma unroll 8
-    for (int rr = 0; rr < kGramRC; ++rr) {
-      floatx4 a = *(const floatx4*)&sI[rr][4 * ty];
-      floatx4 b = *(const floatx4*)&sJ[rr][4 * tx];
-      double bd[4] = {(double)b[0], (double)b[1], (double)b[2], (double)b[3]};
+  };
+  int64_t row0 = rbeg + 4 * wave;
+  if (row0 < rend) load(row0);
+  for (; row0 < rend; row0 += kGramRowStep) {
+    double a[TB], b[TB];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        double ad = (double)a[i];
+    for (int t = 0; t < TB; ++t) { a[t] = (double)an[t]; b[t] = diag ? a[t] : (double)bn[t]; }
+    if (row0 + kGramRowStep < rend) load(row0 + kGramRowStep);     // next step's rows, in flight under the MFMAs
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fma(ad, bd[j], acc[i][j]);
-      }
-    }
-    __syncthreads();
+    for (int i = 0; i < TB; ++i)
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        if (i < ti_n && j < tj_n && !(diag && j < i)) acc[i][j] = mfma_f64(a[i], b[j], acc[i][j]);
   }
+
   double* Go = Gpart + (int64_t)blockIdx.x * Lp * Lp;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int gi = bi * 64 + 4 * ty + i;
-    if (gi < Lp) {
+  for (int i = 0; i < TB; ++i)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int gj = bj * 64 + 4 * tx + j;
-        if (gj < Lp) Go[(int64_t)gi * Lp + gj] = acc[i][j];
+    for (int j = 0; j < TB; ++j) {
+      if (!(i < ti_n && j < tj_n && !(diag && j < i))) continue;      // uniform over the workgroup
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][v * 64 + lane] = acc[i][j][v];
+      __syncthreads();
+      if (tid < 256) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kGramWaves; ++w) s += red[w][tid];
+        const int v = tid >> 6, ln = tid & 63;
+        const int gi = 16 * (bi * TB + i) + (ln >> 4) + 4 * v, gj = 16 * (bj * TB + j) + (ln & 15);
+        Go[(int64_t)gi * Lp + gj] = s;
       }
+      __syncthreads();
     }
-  }
 }
 
 // ---- Cholesky factor and its inverse ---------------------------------------------------------
@@ -412,28 +416,63 @@ __global__ void k_triu_mul(const double* __restrict__ R2, const double* __restri
   Rtot[(int64_t)i * Lp + c] = s;
 }
 
-// Row chunks of the Gram kernel: enough workgroups to fill the chip, at least 64 rows each.
-uint64_t orth_gram_chunks(int64_t rows) {
-  int64_t c = ceil_div(rows, 64);
-  if (c > 64) c = 64;
-  if (c < 1) c = 1;
-  return (uint64_t)c;
+// Row chunks of the Gram kernel.  Up to 64 chunks of at least 64 rows fill the chip for panels of
+// ordinary height; very tall panels get one chunk per 1024 rows, bounded by about 2048 workgroups
+// per launch and 64 MB of partial sums.  The partial sums are added in chunk order (in two levels
+// of at most kGramFan terms when there are more than kGramFan chunks), so the result is deterministic.
+constexpr int kGramFan = 64;
+uint64_t orth_gram_chunks(int64_t rows, int Lp) {
+  const int nbk = (Lp + 63) / 64, pairs = nbk * (nbk + 1) / 2;
+  int64_t c = std::min<int64_t>(ceil_div(rows, 64), 64);
+  c = std::min<int64_t>(c, std::max<int64_t>(1, ceil_div(1024, pairs)));
+  const int64_t cap = std::min<int64_t>(std::max(2048 / pairs, 1), (64ll << 20) / ((int64_t)Lp * Lp * 8));
+  const int64_t tall = std::min<int64_t>(rows / 1024, cap);
+  return (uint64_t)std::max<int64_t>(std::max(c, tall), 1);
+}
+// Slots of Lp x Lp doubles the partial sums need (chunks, plus the first-level sums).
+uint64_t orth_gram_slots(int64_t rows, int Lp) {
+  const uint64_t c = orth_gram_chunks(rows, Lp);
+  return c > (uint64_t)kGramFan ? c + ceil_div(c, kGramFan) : c;
+}
+
+// out[g] = sum of the slots [g*fan, min((g+1)*fan, nsplit)) of part, in slot order.
+__global__ void k_reduce_groups(const double* __restrict__ part, int nsplit, int fan, int64_t count,
+                                double* __restrict__ out) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= count) return;
+  const int s0 = blockIdx.y * fan, s1 = min(nsplit, s0 + fan);
+  double s = 0.0;
+#pragma unroll 8
+  for (int i = s0; i < s1; ++i) s += part[(int64_t)i * count + idx];
+  out[(int64_t)blockIdx.y * count + idx] = s;
 }
 
 static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t stream) {
-  int nbk = (Lp + 63) / 64;
-  int chunks = (int)std::min<int64_t>((int64_t)orth_gram_chunks(rows), ceil_div(1024, nbk * (nbk + 1) / 2));
-  if (chunks > w.gram_chunks_max) return BRSVD_ERR_BUDGET;
+  int chunks = (int)orth_gram_chunks(rows, Lp);
+  if ((int64_t)orth_gram_slots(rows, Lp) > w.gram_chunks_max) return BRSVD_ERR_BUDGET;
   int64_t rpc = ceil_div(rows, chunks);
-  rpc = ceil_div(rpc, kGramRC) * kGramRC;
+  rpc = ceil_div(rpc, kGramRowStep) * kGramRowStep;
   chunks = (int)ceil_div(rows, rpc);
-  int nb = (Lp + 63) / 64;
-  dim3 grid(chunks, nb * (nb + 1) / 2);
-  hipLaunchKernelGGL(k_gram, grid, dim3(256), 0, stream, P, rows, Lp, rpc, w.gram_part);
+  const int nt = Lp / 16, nb = (nt + 3) / 4;       // blocks of (up to) four tiles; a single smaller block when nt < 4
+  dim3 grid(chunks, nb * (nb + 1) / 2), block(kGramWaves * 64);
+  switch (nt) {
+    case 1: hipLaunchKernelGGL(k_gram<1>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    case 2: hipLaunchKernelGGL(k_gram<2>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    case 3: hipLaunchKernelGGL(k_gram<3>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    default: hipLaunchKernelGGL(k_gram<4>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+  }
   BRSVD_HIP_TRY(hipGetLastError());
-  int64_t count = (int64_t)Lp * Lp;
-  hipLaunchKernelGGL(k_reduce_splits_t<double>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream,
-                     w.gram_part, chunks, count, count, w.G);
+  const int64_t count = (int64_t)Lp * Lp;
+  const unsigned bx = (unsigned)ceil_div(count, 256);
+  if (chunks > kGramFan) {
+    const int groups = (int)ceil_div(chunks, kGramFan);
+    double* lvl1 = w.gram_part + (int64_t)chunks * count;
+    hipLaunchKernelGGL(k_reduce_groups, dim3(bx, groups), dim3(256), 0, stream, w.gram_part, chunks, kGramFan, count,
+                       lvl1);
+    hipLaunchKernelGGL(k_reduce_groups, dim3(bx, 1), dim3(256), 0, stream, lvl1, groups, groups, count, w.G);
+  } else {
+    hipLaunchKernelGGL(k_reduce_groups, dim3(bx, 1), dim3(256), 0, stream, w.gram_part, chunks, chunks, count, w.G);
+  }
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }

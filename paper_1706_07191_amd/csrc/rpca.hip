@@ -79,24 +79,15 @@ __device__ __forceinline__ float shrinkf(float x, float eps) {
   return x > eps ? x - eps : (x < -eps ? x + eps : 0.f);
 }
 
-// One ALM iteration after the SVD of X_i (Alg. 3 lines 4-7 and the input of line 3 of the next
-// iteration).  Workgroup tile: 32 rows x 256 columns, one column per thread.
-//   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here)
-//   S = shrink(M - L + Y/mu, lambda/mu)
-//   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
-//   X_next = M - S + Y / mu_next
-// L is stored only when Lout != nullptr (the last iteration).
 constexpr int kRpcaTR = 32;
-__global__ void __launch_bounds__(256)
-k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const float* __restrict__ sig,
-              const float* __restrict__ Vt, int64_t m, int64_t n, int l, float inv_mu, float mu,
-              float thr_s, float inv_mu_next, float* __restrict__ Lout, float* __restrict__ S,
-              float* __restrict__ Y, float* __restrict__ X, double* __restrict__ part) {
-  extern __shared__ float us[];          // kRpcaTR x l : rows of U scaled by the shrunk sigma
-  __shared__ double sh[4];
+
+// acc[i] = row (row0 + i) of U diag(shrink(sigma, inv_mu)) V^T at column `col` (zero beyond n);
+// `us` (LDS, kRpcaTR x l) receives the block's rows of U scaled by the shrunk singular values.
+__device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const float* __restrict__ sig,
+                                             const float* __restrict__ Vt, int64_t m, int64_t n, int l,
+                                             float inv_mu, int64_t row0, int64_t col, float* us,
+                                             float (&acc)[kRpcaTR]) {
   const int tid = threadIdx.x;
-  const int64_t col = (int64_t)blockIdx.x * 256 + tid;
-  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
   for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
     const int i = idx / l, t = idx - i * l;
     const int64_t row = row0 + i;
@@ -104,7 +95,6 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
     us[idx] = row < m ? U[row * l + t] * sv : 0.f;
   }
   __syncthreads();
-  float acc[kRpcaTR];
 #pragma unroll
   for (int i = 0; i < kRpcaTR; ++i) acc[i] = 0.f;
   if (col < n) {
@@ -114,6 +104,28 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
       for (int i = 0; i < kRpcaTR; ++i) acc[i] = fmaf(us[i * l + t], v, acc[i]);
     }
   }
+}
+
+// One ALM iteration after the SVD of X_i (the low-rank, sparse, multiplier and residual updates of
+// Alg. 3, and the matrix handed to the SVD of the next iteration).  Workgroup tile: 32 rows x 256
+// columns, one column per thread.
+//   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here)
+//   S = shrink(M - L + Y/mu, lambda/mu)
+//   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
+//   X_next = M - S + Y / mu_next
+// L is stored only when Lout != nullptr.
+__global__ void __launch_bounds__(256)
+k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const float* __restrict__ sig,
+              const float* __restrict__ Vt, int64_t m, int64_t n, int l, float inv_mu, float mu,
+              float thr_s, float inv_mu_next, float* __restrict__ Lout, float* __restrict__ S,
+              float* __restrict__ Y, float* __restrict__ X, double* __restrict__ part) {
+  extern __shared__ float us[];
+  __shared__ double sh[4];
+  const int tid = threadIdx.x;
+  const int64_t col = (int64_t)blockIdx.x * 256 + tid;
+  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
+  float acc[kRpcaTR];
+  lowrank_tile(U, sig, Vt, m, n, l, inv_mu, row0, col, us, acc);
   double z2 = 0.0;
   if (col < n) {
 #pragma unroll
@@ -135,6 +147,31 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
   }
   const double s = block_sum(z2, sh);
   if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
+}
+
+// L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
+// same tile arithmetic as the update kernel, so it is the L that iteration used.
+__global__ void __launch_bounds__(256)
+k_rpca_lowrank(const float* __restrict__ U, const float* __restrict__ sig, const float* __restrict__ Vt,
+               int64_t m, int64_t n, int l, float inv_mu, float* __restrict__ Lout) {
+  extern __shared__ float us[];
+  const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
+  float acc[kRpcaTR];
+  lowrank_tile(U, sig, Vt, m, n, l, inv_mu, row0, col, us, acc);
+  if (col < n) {
+#pragma unroll
+    for (int i = 0; i < kRpcaTR; ++i)
+      if (row0 + i < m) Lout[(row0 + i) * n + col] = acc[i];
+  }
+}
+
+// P *= 1 / sqrt(*s2)  (normalisation of a power-method vector held in a padded panel)
+__global__ void k_scale_rsqrt(float* __restrict__ P, int64_t count, const double* __restrict__ s2) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= count) return;
+  const double v = *s2;
+  P[i] = v > 0.0 ? (float)((double)P[i] / sqrt(v)) : 0.f;
 }
 
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
@@ -166,6 +203,22 @@ int rpca_update(const float* M, const float* U, const float* sig, const float* V
   hipLaunchKernelGGL(k_rpca_update, grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, 1.0f / mu, mu,
                      lambda / mu, 1.0f / mu_next, Lout, S, Y, X, part);
   hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part, (int)(grid.x * grid.y), resid2_out);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l, float mu,
+                 float* Lout, hipStream_t stream) {
+  dim3 grid((unsigned)ceil_div(n, 256), (unsigned)ceil_div(m, kRpcaTR));
+  if (grid.y > 65535) return BRSVD_ERR_ARG;
+  hipLaunchKernelGGL(k_rpca_lowrank, grid, dim3(256), (size_t)kRpcaTR * l * sizeof(float), stream, U, sig, Vt, m,
+                     n, l, 1.0f / mu, Lout);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream) {
+  hipLaunchKernelGGL(k_scale_rsqrt, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, P, count, s2);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }

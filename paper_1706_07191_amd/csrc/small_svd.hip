@@ -14,7 +14,6 @@
 namespace brsvd {
 
 constexpr int kSvdThreads = 1024;
-constexpr int kSvdWaves = kSvdThreads / 64;
 constexpr int kMaxSweeps = 40;
 constexpr int kJacobiLdsMaxL = 128;
 

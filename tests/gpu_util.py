@@ -19,6 +19,15 @@ def need_gpu():
     return torch.device("cuda:0")
 
 
+def note(line: str):
+    """Prints a measurement line and appends it to gpurun_out/parity.log when that folder exists."""
+    print(line, flush=True)
+    log_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(log_dir):
+        with open(os.path.join(log_dir, "parity.log"), "a") as f:
+            f.write(line + "\n")
+
+
 def check_against_oracle(A_host, Om_host, k, p, q, b, U, S, Vt, tag=""):
     """A_host / Om_host: numpy fp32; U, S, Vt: torch CUDA results.  Returns a dict of figures."""
     Uo, so, Vto = O.brsvd(A_host, Om_host, k, p, q, row_block=b)
@@ -34,11 +43,7 @@ def check_against_oracle(A_host, Om_host, k, p, q, b, U, S, Vt, tag=""):
     out["err_gpu_l"] = O.recon_error(A_host, Ug, sg, Vg)
     out["err_oracle_l"] = O.recon_error(A_host, Uo, so, Vto)
     line = f"[parity {tag}] " + " ".join(f"{k_}={v:.3e}" for k_, v in out.items())
-    print(line, flush=True)
-    log_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(log_dir):
-        with open(os.path.join(log_dir, "parity.log"), "a") as f:
-            f.write(line + "\n")
+    note(line)
     assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0), "sigma must be descending and non-negative"
     assert out["sigma_rel"] <= SIGMA_RTOL, out
     assert out["orthU"] <= ORTH_TOL and out["orthV"] <= ORTH_TOL, out
