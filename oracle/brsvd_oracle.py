@@ -23,6 +23,11 @@ Readings of the paper taken here:
   * Omega is an input (one n x l matrix; stacking Alg. 2's per-block draws gives the same);
   * all l = k+p triplets are returned, sigma descending; callers truncate to k.
 
+Also here: brsvd_alg2, the block-LOCAL power iteration exactly as Alg. 2 prints it (a different
+approximation, kept apart from the main path; pins in tests/test_oracle_alg2.py), the robust PCA
+loop of Alg. 3 with a fixed iteration count (rpca_ialm) and with its stopping rule
+(rpca_ialm_tol), and the power method for ||M||_2 (norm2_power).
+
 Pins (tests/test_oracle_*.py): dense SVD special case (Omega = I), exact recovery of a
 rank <= k matrix, block-size / orth-method / Omega-mixing invariances, Pythagoras identity,
 interlacing sigma_i(B) <= sigma_i(A), projector closed form for q = 0, the
@@ -226,3 +231,42 @@ def norm2_power(A, x0, iters: int) -> float:
         z = A.T @ y
         x = z / np.linalg.norm(z)
     return est
+
+
+# --------------------------------------------------------------------------------------
+# The block-local scheme as Alg. 2 prints it (power iteration inside each block).
+# --------------------------------------------------------------------------------------
+
+def brsvd_alg2(A, Omega, k: int, p: int, q: int, row_block: int = 0):
+    """Alg. 2 with its block-LOCAL power iteration, on a row-major A walked in row blocks.
+
+    The paper blocks the columns of its input; a row block A_I (b x n) of a row-major matrix is a
+    column block of the transposed input, so Alg. 2 is applied to A^T (its "m" is our n):
+        Y (n x l) = sum over blocks I of (A_I^T A_I)^q A_I^T Omega_I      (first sweep; Omega_I = the
+                                                                           block's rows of Omega, m x l;
+                                                                           factors applied right to left, Eq. (4))
+        Q = orth(Y)                                                       (n x l)
+        B(:, I) = Q^T A_I^T  for every block                              (second sweep; B is l x m)
+        B = Ut Sigma Vp^T,  Up = Q Ut                                     (SVD of B and the lift)
+    so A^T ~ Up Sigma Vp^T, i.e. A ~ Vp Sigma Up^T.  Returns (U, s, Vt) = (Vp, Sigma, Up^T) for A,
+    all l = k + p triplets.  No orthonormalisation happens inside a block (none is printed).
+    This is a different approximation from Alg. 1 unless q = 0 or there is a single block.
+    """
+    m, n = A.shape
+    l = k + p
+    Omega = np.asarray(Omega, dtype=np.float64)
+    assert Omega.shape == (m, l)
+    Y = np.zeros((n, l))
+    for r0, r1 in row_blocks(m, row_block):
+        AI = np.asarray(A[r0:r1], dtype=np.float64)
+        P = AI.T @ Omega[r0:r1]
+        for _ in range(q):
+            P = AI.T @ (AI @ P)
+        Y += P
+    Q = orth_householder(Y)
+    Bt = np.empty((m, l))
+    for r0, r1 in row_blocks(m, row_block):
+        Bt[r0:r1] = np.asarray(A[r0:r1], dtype=np.float64) @ Q
+    Ut, s, Vpt = np.linalg.svd(Bt.T, full_matrices=False)
+    Up = Q @ Ut
+    return Vpt.T, s, Up.T
