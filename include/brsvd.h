@@ -107,6 +107,30 @@ int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out);
 int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega,
               float* U, float* S, float* Vt, brsvd_stats* stats);
 
+/* The block-local scheme exactly as Alg. 2 prints it: the power iteration is run inside each block
+ * while the block is resident, Y += (A_J A_J^T)^q A_J Omega_j (Sec. 3, Eq. (4) for the order of the
+ * products), Omega_j is drawn on the device while the block is being copied (Sec. 3 "Sampling and
+ * power iteration"), then Q = orth(Y), a second sweep forms B, and svd(B) is lifted.  A is read
+ * twice whatever q is.  The paper cuts its input into column blocks; the row blocks of the row-major
+ * A of this library are the column blocks of A^T, so the scheme is applied to A^T and the triplets
+ * are swapped back: the sketch is Y (n x l) = sum_I (A_I^T A_I)^q A_I^T Omega_I with Omega m x l,
+ * and B^T = A Q.  Unless q = 0 or there is one block this is a different (weaker) approximation from
+ * brsvd_run's global power iteration, and without re-orthonormalisation inside a block its fp32
+ * result loses the directions with (s_i / s_1)^(2q+1) below about 1e-7.
+ *   seed   selects Omega = Philox4x32-10 + Box-Muller Gaussian matrix (see brsvd_philox_normal);
+ *   Omega  DEVICE, m x l dense, or NULL; when given it is used instead of the generator.
+ * pass_mode of the handle is ignored.  Other arguments, outputs and errors as for brsvd_run. */
+int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega,
+                   float* U, float* S, float* Vt, brsvd_stats* stats);
+
+/* Rows [row0, row0 + rows) of the Gaussian matrix Omega(seed) with `cols` columns that
+ * brsvd_run_alg2 draws, written dense to out (DEVICE, rows x cols).  Element e = row*cols + col is
+ * output (e & 3) of Philox4x32-10 at counter (e >> 2) with key (seed low word, seed high word),
+ * mapped to N(0,1) by Box-Muller on 23-bit uniforms ((x >> 9) + 0.5) * 2^-23: outputs 0, 1 give
+ * radius*cos, radius*sin of one pair, outputs 2, 3 the second pair.  Asynchronous on `stream`. */
+int brsvd_philox_normal(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, float* out,
+                        void* stream);
+
 /* Robust PCA by the inexact augmented Lagrange multiplier method, Alg. 3 / Eq. (3), with a
  * FIXED number of iterations; each iteration calls the randomized SVD above on
  * M - S_i + Y_i/mu_i, shrinks the singular values by 1/mu_i and the residual entries by

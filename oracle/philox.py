@@ -8,7 +8,8 @@ definition on its own, so that both sides can draw the same Omega from a seed.
 Definition of the matrix Omega(seed; rows x cols), row-major, element e = row * cols + col:
     counter = (e >> 2) as a 128-bit little-endian number in four 32-bit words, key = (seed low word,
     seed high word); x0..x3 = Philox4x32-10(counter, key);
-    u(x) = ((x >> 8) + 0.5) * 2^-24                       (24-bit uniform in (0, 1), exact in fp32)
+    u(x) = ((x >> 9) + 0.5) * 2^-23                       (23-bit uniform in (0, 1); with the half added it
+                                                           still fits the 24-bit significand of fp32)
     z0 = sqrt(-2 ln u(x0)) cos(2 pi u(x1)),  z1 = sqrt(-2 ln u(x0)) sin(2 pi u(x1)),
     z2, z3 likewise from (x2, x3);  Omega[e] = z_(e & 3).
 """
@@ -42,8 +43,8 @@ def philox4x32_10(counter: np.ndarray, key) -> np.ndarray:
     return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
 
 
-def _uniform24(x: np.ndarray) -> np.ndarray:
-    return ((x >> np.uint32(8)).astype(np.float64) + 0.5) * 2.0 ** -24
+def _uniform23(x: np.ndarray) -> np.ndarray:
+    return ((x >> np.uint32(9)).astype(np.float64) + 0.5) * 2.0 ** -23
 
 
 def philox_normal(seed: int, rows: int, cols: int, row0: int = 0) -> np.ndarray:
@@ -56,10 +57,10 @@ def philox_normal(seed: int, rows: int, cols: int, row0: int = 0) -> np.ndarray:
     ctr[:, 0] = idx & _MASK
     ctr[:, 1] = idx >> _S32
     x = philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))
-    r01 = np.sqrt(-2.0 * np.log(_uniform24(x[:, 0])))
-    t01 = 2.0 * np.pi * _uniform24(x[:, 1])
-    r23 = np.sqrt(-2.0 * np.log(_uniform24(x[:, 2])))
-    t23 = 2.0 * np.pi * _uniform24(x[:, 3])
+    r01 = np.sqrt(-2.0 * np.log(_uniform23(x[:, 0])))
+    t01 = 2.0 * np.pi * _uniform23(x[:, 1])
+    r23 = np.sqrt(-2.0 * np.log(_uniform23(x[:, 2])))
+    t23 = 2.0 * np.pi * _uniform23(x[:, 3])
     z = np.stack([r01 * np.cos(t01), r01 * np.sin(t01), r23 * np.cos(t23), r23 * np.sin(t23)], axis=1).reshape(-1)
     off = e0 - 4 * c_first
     return z[off:off + rows * cols].reshape(rows, cols)

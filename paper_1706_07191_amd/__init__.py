@@ -53,7 +53,7 @@ class brsvd_stats(C.Structure):
 
 
 EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
-           "brsvd_norm2_power", "brsvd_destroy",
+           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_orth", "brsvd_small_svd"]
 
@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
     L.brsvd_rpca_ialm_tol.argtypes = [vp, vp, vp, i32, dbl, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
                                       C.POINTER(i32), C.POINTER(brsvd_stats)]
     L.brsvd_norm2_power.argtypes = [vp, vp, i64, vp, i32, C.POINTER(dbl)]
+    L.brsvd_run_alg2.argtypes = [vp, vp, i64, u64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
+    L.brsvd_philox_normal.argtypes = [u64, i64, i64, i32, vp, vp]
     L.brsvd_destroy.argtypes = [vp]
     L.brsvd_status_string.argtypes = [C.c_int]
     L.brsvd_status_string.restype = C.c_char_p
@@ -173,6 +175,38 @@ def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = No
                              _dev(Vt, torch.float32, "Vt"), C.byref(st) if want_stats else None)
     _check(status, "brsvd_run")
     return U, S, Vt, (st.as_dict() if want_stats else None)
+
+
+def brsvd_run_alg2(handle, A, l, seed=0, Omega=None, lda: Optional[int] = None, want_stats=True, pinned=False,
+                   device=None):
+    """Block-local scheme of Alg. 2.  A as for brsvd_run; Omega (m, l) fp32 CUDA or None (then the library
+    draws it from `seed`).  Returns (U, S, Vt, stats)."""
+    import torch
+    m, n = A.shape
+    if A.dtype != torch.float32 or A.stride(1) != 1:
+        raise TypeError("A must be fp32 with unit column stride")
+    if not A.is_cuda and not (pinned or A.is_pinned()):
+        raise TypeError("a host-resident A must be pinned")
+    lda = lda if lda is not None else A.stride(0)
+    dev = device or (Omega.device if Omega is not None else (A.device if A.is_cuda else torch.device("cuda:0")))
+    U = torch.empty(m, l, device=dev)
+    S = torch.empty(l, device=dev)
+    Vt = torch.empty(l, n, device=dev)
+    st = brsvd_stats()
+    status = lib().brsvd_run_alg2(handle, A.data_ptr(), lda, int(seed),
+                                  _dev(Omega, torch.float32, "Omega") if Omega is not None else None,
+                                  U.data_ptr(), S.data_ptr(), Vt.data_ptr(), C.byref(st) if want_stats else None)
+    _check(status, "brsvd_run_alg2")
+    return U, S, Vt, (st.as_dict() if want_stats else None)
+
+
+def brsvd_philox_normal(seed, rows, cols, row0=0, device="cuda:0", stream=None):
+    """Rows [row0, row0 + rows) of the Gaussian matrix brsvd_run_alg2 draws from `seed`."""
+    import torch
+    out = torch.empty(rows, cols, device=device)
+    _check(lib().brsvd_philox_normal(int(seed), row0, rows, cols, out.data_ptr(), _stream_ptr(stream)),
+           "brsvd_philox_normal")
+    return out
 
 
 def brsvd_rpca_ialm(handle, M, Omegas, iters, lam, mu0, rho, norm2_M=0.0, L=None, S=None, work=None):

@@ -406,6 +406,89 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
   return BRSVD_OK;
 }
 
+// The block-local scheme as Alg. 2 prints it, for a row-major A walked in row blocks (= column blocks of
+// A^T, so the roles of m and n are those of the transposed problem):
+//   first sweep    Y (n x l) += (A_I^T A_I)^q A_I^T Omega_I per resident block, factors applied right to
+//                  left (Eq. (4)); Omega_I is drawn on the device while the block is being copied
+//   Q = orth(Y)
+//   second sweep   C_I = A_I Q  (C = B^T, m x l)
+//   C = W_C R, R = Ur diag(s) Vr^T   =>   A ~ (W_C Ur) diag(s) (Q Vr)^T
+// Two reads of A whatever q is.  Omega (m x l, device) overrides the generator when not null.
+int enqueue_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega, float* U,
+                 float* S, float* Vt, int method) {
+  const int l = h->l, Lp = h->Lp, q = h->prm.q;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  hipStream_t cs = h->compute;
+  OrthWork ow = orth_work(h);
+  void* scr = h->arena + h->lay.gemm_scratch;
+  const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
+  float* Yn = h->Pn(0);
+  float* Pn1 = h->Pn(1);
+  float* OmI = h->Pm(0);     // b x Lp windows of the two m x Lp panels
+  float* TI = h->Pm(1);
+  float* res;
+
+  Streamer st(h, A, lda);
+  for (int i = 0; i < h->nblocks; ++i) {
+    const int64_t rows = st.rows_of(i), r0 = (int64_t)i * h->b;
+    if (Omega) BRSVD_TRY(pad_panel(Omega + r0 * l, rows, l, OmI, Lp, cs));
+    else BRSVD_TRY(philox_normal(seed, r0, rows, l, OmI, Lp, cs));
+    const float* blk = A + r0 * lda;
+    int64_t ldb = lda;
+    if (h->host_a) { BRSVD_TRY(st.acquire(i, &blk)); ldb = n; }
+    auto at = [&](const float* Qp, float* Z, bool accumulate) {
+      KernelEvents ke;
+      bool t = kernel_events(h, CAT_AT, &ke);
+      return gemm_at(blk, ldb, rows, n, Qp, Lp, Z, accumulate, rows, scr, scr_bytes, cs, t ? &ke : nullptr);
+    };
+    if (q == 0) {
+      BRSVD_TRY(at(OmI, Yn, i > 0));
+    } else {
+      BRSVD_TRY(at(OmI, Pn1, false));
+      for (int t = 0; t < q; ++t) {
+        KernelEvents ke;
+        bool tm = kernel_events(h, CAT_AN, &ke);
+        BRSVD_TRY(gemm_an(blk, ldb, rows, n, Pn1, Lp, TI, Lp, Lp, scr, scr_bytes, cs, tm ? &ke : nullptr));
+        const bool last = t == q - 1;
+        BRSVD_TRY(at(TI, last ? Yn : Pn1, last && i > 0));
+      }
+    }
+    if (h->host_a) BRSVD_TRY(st.release(i));
+  }
+  {
+    Region r(h, CAT_ORTH, cs);
+    BRSVD_TRY(orth_panel(Yn, Pn1, n, l, Lp, method, true, ow, nullptr, &res, cs));
+    if (res != Yn) std::swap(Yn, Pn1);
+  }
+  float* Cm = h->Pm(0);
+  float* Tm = h->Pm(1);
+  BRSVD_TRY(pass_an(h, A, lda, Yn, Cm));                 // second sweep: C = A Q
+  double* Rtot = h->at<double>(h->lay.Rtot);
+  {
+    Region r(h, CAT_ORTH, cs);
+    BRSVD_TRY(orth_panel(Cm, Tm, m, l, Lp, method, true, ow, Rtot, &res, cs));
+    if (res != Cm) std::swap(Cm, Tm);
+  }
+  SvdWork sw;
+  sw.W = h->at<double>(h->lay.svdW);
+  sw.J = h->at<double>(h->lay.svdJ);
+  sw.sig = h->at<double>(h->lay.sig);
+  sw.info = h->at<int>(h->lay.flags) + 4;
+  float* XV = h->at<float>(h->lay.XV);
+  float* XU = h->at<float>(h->lay.XU);
+  {
+    Region r(h, CAT_SVD, cs);
+    BRSVD_TRY(small_svd(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
+  }
+  {
+    Region r(h, CAT_LIFT, cs);
+    BRSVD_TRY(gemm_an(Cm, Lp, m, Lp, XU, Lp, U, l, l, scr, scr_bytes, cs));            // U = W_C * Ur
+    BRSVD_TRY(gemm_an(Yn, Lp, n, Lp, XV, Lp, Pn1, Lp, Lp, scr, scr_bytes, cs));        // V = Q * Vr
+    BRSVD_TRY(transpose_panel(Pn1, n, Lp, l, Vt, cs));
+  }
+  return BRSVD_OK;
+}
+
 int passes_per_run(brsvd_handle h) {
   return h->prm.pass_mode == BRSVD_PASSES_FUSED ? h->prm.q + 1 : 2 * h->prm.q + 2;
 }
@@ -466,13 +549,17 @@ void add_stats(brsvd_stats* acc, const brsvd_stats& s) {
 
 // Runs one factorisation to completion (synchronises), handling the optimistic CholeskyQR route:
 // the breakdown flag is only inspected at the end, and AUTO then repeats the run with TSQR.
-int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
-             int* fallbacks) {
+template <typename Enqueue>
+int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
   int method = h->prm.orth_method;
   int* dflags = h->at<int>(h->lay.flags);
   for (int attempt = 0; attempt < 2; ++attempt) {
     BRSVD_HIP_TRY(hipMemsetAsync(dflags, 0, 64, h->compute));
-    BRSVD_TRY(enqueue_brsvd(h, A, lda, Omega, U, S, Vt, method));
+    if (h->host_a) {
+      // the staging buffers start out free
+      for (int i = 0; i < 2; ++i) BRSVD_HIP_TRY(hipEventRecord(h->drained[i], h->compute));
+    }
+    BRSVD_TRY(enqueue(method));
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags, dflags, sizeof(int), hipMemcpyDeviceToHost, h->compute));
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags + 1, dflags + 4, 2 * sizeof(int), hipMemcpyDeviceToHost,
                                  h->compute));
@@ -487,6 +574,11 @@ int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, fl
     if (fallbacks) ++*fallbacks;
   }
   return BRSVD_ERR_ORTH_BREAKDOWN;
+}
+
+int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
+             int* fallbacks) {
+  return run_sync_with(h, fallbacks, [&](int method) { return enqueue_brsvd(h, A, lda, Omega, U, S, Vt, method); });
 }
 
 }  // namespace
@@ -586,10 +678,6 @@ int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, f
   if (lda < h->prm.n) return BRSVD_ERR_ARG;
   reset_timing(h, stats != nullptr);
   int fallbacks = 0, status;
-  if (h->host_a) {
-    // the staging buffers start out free
-    for (int i = 0; i < 2; ++i) BRSVD_HIP_TRY(hipEventRecord(h->drained[i], h->compute));
-  }
   {
     Region total(h, CAT_TOTAL, h->compute);
     status = run_sync(h, A, lda, Omega, U, S, Vt, &fallbacks);
@@ -599,6 +687,29 @@ int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, f
     fill_stats(h, stats, passes_per_run(h) * (1 + fallbacks), fallbacks);
   }
   return status;
+}
+
+int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega, float* U,
+                   float* S, float* Vt, brsvd_stats* stats) {
+  if (!h || !A || !U || !S || !Vt) return BRSVD_ERR_ARG;
+  if (lda < h->prm.n) return BRSVD_ERR_ARG;
+  reset_timing(h, stats != nullptr);
+  int fallbacks = 0, status;
+  {
+    Region total(h, CAT_TOTAL, h->compute);
+    status = run_sync_with(h, &fallbacks,
+                           [&](int method) { return enqueue_alg2(h, A, lda, seed, Omega, U, S, Vt, method); });
+  }
+  if (stats) {
+    (void)hipStreamSynchronize(h->compute);
+    fill_stats(h, stats, 2 * (1 + fallbacks), fallbacks);
+  }
+  return status;
+}
+
+int brsvd_philox_normal(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, float* out, void* stream) {
+  if (!out || rows < 1 || cols < 1 || row0 < 0) return BRSVD_ERR_ARG;
+  return philox_normal(seed, row0, rows, cols, out, cols, (hipStream_t)stream);
 }
 
 int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int32_t max_iters, double tol,

@@ -126,4 +126,9 @@ int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, i
 // P[0..count) *= 1 / sqrt(*s2) (device scalar; a zero scalar zeroes P).
 int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream);
 
+// ---- device-side Gaussian generator (philox.hip) -------------------------------------------
+// Rows [row0, row0 + rows) of the m x l matrix Omega(seed) (Philox4x32-10 + Box-Muller, element
+// e = row*l + col from output e&3 of counter e>>2) into out (rows x ld, columns l..ld-1 zeroed).
+int philox_normal(uint64_t seed, int64_t row0, int64_t rows, int l, float* out, int ld, hipStream_t stream);
+
 }  // namespace brsvd
