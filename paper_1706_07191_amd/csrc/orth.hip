@@ -2,8 +2,9 @@
 //
 // Main route: CholeskyQR applied twice.  G = P^T P is accumulated in fp64 (products of fp32
 // values are exact in fp64), factored G = R^T R in fp64, and P <- P * R^-1 is one more thin
-// GEMM on the MFMA path.  A pivot that falls below a relative threshold raises the breakdown
-// flag; the caller then switches to the Householder-based TSQR route (tsqr.hip).
+// GEMM on the MFMA path.  Pivots that fall below a relative threshold are clamped in every sweep
+// but the last one of an output basis; there such a pivot raises the breakdown flag and the caller
+// switches to the Householder-based TSQR route (tsqr.hip).
 // The paper orthonormalises with a TSQR-based CAQR; range(P) -- all the method needs -- is the
 // same for any orthonormalisation.
 #include <algorithm>
@@ -102,7 +103,8 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
 // blocks: inv([R11 R12; 0 R22]) = [X11, -X11 R12 X22; 0, X22]).  Everything is fp64.  For
 // l <= kCholLdsMaxL the matrix lives in LDS for the whole kernel; above that it stays in global
 // memory (L2) and only the current 16-row panel is mirrored in LDS.
-// A pivot <= tol * its original diagonal entry sets flag[0] = 1 + column and ends the kernel.
+// A pivot <= tol * its original diagonal entry is clamped to that value (lenient) or sets
+// flag[0] = 1 + column and ends the kernel.
 constexpr int kNB = 16;
 constexpr int kCholLdsMaxL = 136;
 
@@ -139,10 +141,16 @@ __device__ bool chol_diag_wave(double* M, int ld, int kb, int nb, const double* 
   bool ok = true;
 #pragma unroll
   for (int j = 0; j < kNB; ++j) {
-    const double d = shfl_d(col[j], j);
-    if (j < nb && !(d > tol * d0[kb + j])) ok = false;
+    double d = shfl_d(col[j], j);
+    if (j < nb) {
+      // a pivot at or below the threshold is replaced by the threshold (the factor is then that of G
+      // plus a small diagonal bump): R stays finite and P R^-1 cannot blow up; the caller decides
+      // whether such a panel is acceptable
+      const double floor_ = tol * d0[kb + j];
+      if (!(d > floor_)) { ok = false; d = floor_ > 0.0 ? floor_ : 1.0; }   // an all-zero column keeps R_jj = 1
+    }
     const double inv = d > 0.0 ? rsqrt_fast(d) : 0.0;
-    const double rj = (c >= j) ? col[j] * inv : 0.0;
+    const double rj = (c > j) ? col[j] * inv : (c == j ? d * inv : 0.0);
     col[j] = rj;
 #pragma unroll
     for (int r = j + 1; r < kNB; ++r) {
@@ -196,7 +204,7 @@ __device__ void inv_diag_wave(double* M, int ld, int kb, int nb, int lane) {
 template <bool IN_LDS>
 __global__ void __launch_bounds__(1024)
 k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
-           float* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored) {
+           float* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored, int lenient) {
   extern __shared__ double smem[];
   __shared__ int bad;
   double* Rkk = smem;                 // 16 x 17
@@ -230,7 +238,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
     const int nb = min(kNB, l - kb);
     if (wave == 0) {
       bool ok = chol_diag_wave(M, ld, kb, nb, d0, tol, Rkk, lane);
-      if (!ok && lane == 0) bad = kb + 1;
+      if (!ok && !lenient && lane == 0) bad = kb + 1;
     }
     __syncthreads();
     if (bad) {
@@ -477,8 +485,10 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
   return BRSVD_OK;
 }
 
+// lenient != 0: pivots below tol * (original diagonal) are clamped and the factorisation goes on;
+// otherwise such a pivot raises the breakdown flag and ends the kernel.
 static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags, double tol,
-                    hipStream_t stream, int factored = 0) {
+                    hipStream_t stream, int factored = 0, int lenient = 0) {
   const bool in_lds = l <= kCholLdsMaxL;
   const int ld = l | 1;
   const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)l * ld : (size_t)kNB * kMaxL)) * sizeof(double);
@@ -492,10 +502,11 @@ static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float*
     attr_set = true;
   }
   if (in_lds)
-    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol, factored);
+    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol,
+                       factored, lenient);
   else
     hipLaunchKernelGGL(k_chol_inv<false>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags,
-                       tol, factored);
+                       tol, factored, lenient);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
@@ -503,7 +514,7 @@ static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float*
 int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot,
                float** result, hipStream_t stream);
 int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream);
+                  float** result, hipStream_t stream, bool strict_last = true);
 
 int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags,
                       hipStream_t stream) {
@@ -525,14 +536,21 @@ int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hi
   return BRSVD_OK;
 }
 
+// Only the last sweep of a basis that reaches the output must succeed without clamped pivots (its
+// input is then already nearly orthonormal, so a small pivot there means the panel really lost
+// rank to working precision).  Earlier sweeps, and the single sweep of an intermediate panel, clamp:
+// the numerically dependent directions of an exactly rank-deficient panel -- the paper's own test
+// inputs have rank k < l -- come out as damped rounding noise, which the next sweep or the next
+// power step treats like any other direction; P = Q R holds exactly either way.
 int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream) {
+                  float** result, hipStream_t stream, bool strict_last) {
   const double tol = 1e-12;
   float* src = P;
   float* dst = tmp;
   for (int sweep = 0; sweep < nsweeps; ++sweep) {
     BRSVD_TRY(gram(src, rows, Lp, w, stream));
-    BRSVD_TRY(chol_inv(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream));
+    const int lenient = (sweep + 1 < nsweeps || !strict_last) ? 1 : 0;
+    BRSVD_TRY(chol_inv(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream, 0, lenient));
     BRSVD_TRY(gemm_an(src, Lp, rows, Lp, w.Rinv, Lp, dst, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
     BRSVD_TRY(apply_to_companion(w, Lp, stream));
     float* t = src; src = dst; dst = t;
@@ -555,7 +573,7 @@ int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bo
   // A panel that only seeds the next power half step needs a well-conditioned basis, not one
   // orthonormal to working precision: one CholeskyQR sweep (fp64 Gram) leaves ||Q^T Q - I|| of
   // order eps32 * cond(P).  The bases that reach the output (Q behind U, W_B behind V) get two.
-  return cholqr_sweeps(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream);
+  return cholqr_sweeps(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream, final_basis);
 }
 
 }  // namespace brsvd

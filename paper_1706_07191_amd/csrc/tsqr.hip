@@ -116,7 +116,7 @@ uint64_t tsqr_work_bytes(int64_t rows, int Lp) {
 int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags,
                       hipStream_t stream);
 int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream);
+                  float** result, hipStream_t stream, bool strict_last = true);
 int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream);
 
 int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot, float** result,

@@ -1,0 +1,138 @@
+"""Timing sweeps of the HIP path on one MI355X (synthetic Gaussian-product inputs, A resident in HBM).
+
+  python -m paper_1706_07191_amd.sweep gemm   [--shape MxN ...] [--l L ...]
+      the two pass kernels alone, one launch over all of A: ms, Tflop/s and GB/s of the algorithmic
+      bytes 4*m*n + 4*(m+n)*l.  Narrow panels (l <= 32) are the HBM-bound side of the ridge.
+  python -m paper_1706_07191_amd.sweep shapes [--family tall|square] [--gb G ...] [--q Q] [--p P]
+      whole rank-k BRSVDs over growing inputs at the two aspect ratios of the paper's Fig. 2
+      (tall-skinny m:n:k = 1024:32:1, square m:n:k = 256:256:1): seconds, Tflop/s with the flop
+      count of the paper's Table 1 terms written out, 2*m*n*l*(2q+2) for the passes plus
+      2*(m+n)*l^2 per orthonormalisation sweep and lift, and the share of each phase.
+
+Every line of output is one JSON object.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+
+def _time_ms(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def _gaussian_product(m, n, r, dev, seed):
+    import torch
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    A = torch.empty(m, n, device=dev)
+    G2 = torch.randn(r, n, device=dev, generator=g)
+    step = max(1, (1 << 28) // max(n, 1))
+    for r0 in range(0, m, step):
+        r1 = min(m, r0 + step)
+        A[r0:r1] = torch.randn(r1 - r0, r, device=dev, generator=g) @ G2
+    return A
+
+
+def sweep_gemm(args):
+    import torch
+
+    import paper_1706_07191_amd as B
+    dev = torch.device("cuda:0")
+    for shape in args.shape:
+        m, n = (int(x) for x in shape.lower().split("x"))
+        A = torch.randn(m, n, device=dev)
+        for l in args.l:
+            X = torch.randn(n, l, device=dev)
+            Q = torch.randn(m, l, device=dev)
+            Y = torch.empty(m, l, device=dev)
+            Z = torch.zeros(n, l, device=dev)
+            by = 4.0 * m * n + 4.0 * (m + n) * l
+            for name, fn in (("gemm_an", lambda: B.brsvd_gemm_an(A, X, Y)), ("gemm_at", lambda: B.brsvd_gemm_at(A, Q, Z))):
+                ms = _time_ms(fn, args.reps)
+                print(json.dumps({"kernel": name, "m": m, "n": n, "l": l, "ms": round(ms, 4),
+                                  "tflops": round(2.0 * m * n * l / ms / 1e9, 2),
+                                  "algorithmic_GBps": round(by / ms / 1e6, 1),
+                                  "note": "includes the panel pad/unpad and split-sum kernels of the step-level call"}),
+                      flush=True)
+        del A
+
+
+def sweep_shapes(args):
+    import torch
+
+    import paper_1706_07191_amd as B
+    dev = torch.device("cuda:0")
+    fams = {"tall": (1024, 32), "square": (256, 256)}
+    for fam in args.family:
+        rm, rn = fams[fam]
+        for gb in args.gb:
+            # m = rm*k, n = rn*k with 4*m*n = gb * 1e9 bytes
+            k = max(2, int(round((gb * 1e9 / 4.0 / (rm * rn)) ** 0.5)))
+            m, n, p, q = rm * k, rn * k, args.p, args.q
+            l = k + p
+            if l > min(m, n, 512):
+                print(json.dumps({"family": fam, "gb": gb, "skipped": f"l = {l} exceeds min(m, n, 512)"}), flush=True)
+                continue
+            A = _gaussian_product(m, n, k, dev, 1000 + k)
+            Om = torch.randn(n, l, device=dev)
+            h = B.brsvd_create(B.make_params(m, n, k, p, q, row_block=0))
+            try:
+                B.brsvd_run(h, A, Om, want_stats=False)
+                best = None
+                for _ in range(args.reps):
+                    U, S, Vt, st = B.brsvd_run(h, A, Om)
+                    if best is None or st["total_seconds"] < best["total_seconds"]:
+                        best = st
+            finally:
+                B.brsvd_destroy(h)
+            sweeps = (q + 1) + q + 4           # one CholeskyQR sweep per intermediate panel, two per output basis
+            flops = 2.0 * m * n * l * (2 * q + 2) + 2.0 * (m + n) * l * l * (sweeps + 1)
+            t = best["total_seconds"]
+            err = float(torch.linalg.norm(A[:4096] - (U[:4096] * S) @ Vt) / torch.linalg.norm(A[:4096]))
+            print(json.dumps({"family": fam, "m": m, "n": n, "k": k, "p": p, "q": q, "bytes_A_GB": round(4.0 * m * n / 1e9, 3),
+                              "seconds": round(t, 6), "tflops": round(flops / t / 1e12, 2),
+                              "A_GBps": round(best["bytes_A_streamed"] / t / 1e9, 1),
+                              "share": {key[:-8]: round(best[key] / t, 3) for key in
+                                        ("gemm_an_seconds", "gemm_at_seconds", "orth_seconds", "svd_seconds", "lift_seconds")},
+                              "orth_fallbacks": best["orth_fallbacks"], "passes_over_A": best["passes_over_A"],
+                              "rel_error_first_4096_rows": err}), flush=True)
+            del A, Om, U, S, Vt
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    g = sub.add_parser("gemm")
+    g.add_argument("--shape", nargs="+", default=["20000x20000", "100000x50000"])
+    g.add_argument("--l", nargs="+", type=int, default=[8, 16, 32, 64, 110, 272])
+    g.add_argument("--reps", type=int, default=5)
+    s = sub.add_parser("shapes")
+    s.add_argument("--family", nargs="+", default=["tall", "square"], choices=["tall", "square"])
+    s.add_argument("--gb", nargs="+", type=float, default=[0.25, 1, 4, 16])
+    s.add_argument("--p", type=int, default=10)
+    s.add_argument("--q", type=int, default=1)
+    s.add_argument("--reps", type=int, default=3)
+    args = ap.parse_args(argv)
+    import torch
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible", file=sys.stderr)
+        return 2
+    import paper_1706_07191_amd as B
+    B.lib()
+    (sweep_gemm if args.cmd == "gemm" else sweep_shapes)(args)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -121,23 +121,29 @@ def test_orth_tsqr(rows, l, cond):
     assert np.linalg.norm(np.abs(R) - np.abs(Ro)) <= 1e-4 * np.linalg.norm(Ro)
 
 
-def test_orth_auto_falls_back_on_rank_deficient_panel():
-    """A panel of numerical rank r < l: CholeskyQR breaks down, AUTO takes the TSQR route and still
-    returns an orthonormal basis that contains range(P); CHOLQR2 alone reports the breakdown."""
+def test_orth_rank_deficient_panel():
+    """A panel of numerical rank r < l (the sketch of an exactly rank-r matrix, as in the paper's own test
+    inputs): the first CholeskyQR sweep clamps the vanishing pivots, the second one orthonormalises the
+    damped noise columns; every route returns an orthonormal basis that contains range(P), and P = Q R."""
     dev = need_gpu()
     rows, l, r = 2000, 24, 10
     G1 = synth.gaussian(rows, r, 35, dtype=torch.float64)
     G2 = synth.gaussian(r, l, 36, dtype=torch.float64)
     P = (G1 @ G2).float()
-    Qd, _, fb = B.brsvd_orth(P.to(dev).contiguous(), method=B.BRSVD_ORTH_AUTO)
-    assert fb
+    P64 = P.double().numpy()
+    for method in (B.BRSVD_ORTH_AUTO, B.BRSVD_ORTH_CHOLQR2, B.BRSVD_ORTH_TSQR):
+        Qd, Rd, fb = B.brsvd_orth(P.to(dev).contiguous(), method=method, want_R=True)
+        Q = Qd.double().cpu().numpy()
+        assert O.orth_defect(Q) < 5e-6, method
+        assert np.linalg.norm(Q @ (Q.T @ P64) - P64) <= 1e-5 * np.linalg.norm(P64), method
+        assert np.linalg.norm(Q @ Rd.cpu().numpy() - P64) <= 1e-5 * np.linalg.norm(P64), method
+    # an exactly repeated column
+    P2 = synth.gaussian(1500, 12, 37)
+    P2[:, 7] = P2[:, 3]
+    Qd, Rd, fb = B.brsvd_orth(P2.to(dev).contiguous(), method=B.BRSVD_ORTH_AUTO)
     Q = Qd.double().cpu().numpy()
     assert O.orth_defect(Q) < 5e-6
-    P64 = P.double().numpy()
-    assert np.linalg.norm(Q @ (Q.T @ P64) - P64) <= 1e-5 * np.linalg.norm(P64)
-    with pytest.raises(B.BrsvdError) as ei:
-        B.brsvd_orth(P.to(dev).contiguous(), method=B.BRSVD_ORTH_CHOLQR2)
-    assert ei.value.status == B.BRSVD_ERR_ORTH_BREAKDOWN
+    assert np.linalg.norm(Q @ (Q.T @ P2.double().numpy()) - P2.double().numpy()) <= 1e-5 * np.linalg.norm(P2.double().numpy())
     # an all-zero panel cannot be orthonormalised by any route
     with pytest.raises(B.BrsvdError):
         B.brsvd_orth(torch.zeros(100, 8, device=dev), method=B.BRSVD_ORTH_AUTO)
