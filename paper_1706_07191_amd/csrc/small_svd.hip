@@ -6,7 +6,7 @@
 // mutually orthogonal: then W = diag(s) Vr^T, so s_i is the norm of row i and Vr's column i the
 // normalised row i; Ur = R Vr diag(1/s) follows from one small product.  Everything is fp64.
 //   l <= kJacobiLdsMaxL : one workgroup of 1024 threads, W resident in LDS for all sweeps.
-//   larger l            : one launch per round-robin step, one wave per row pair, W in L2.
+//   larger l            : block Jacobi, one launch per round of block pairs, W in L2, block pairs in LDS.
 #include <cstdlib>
 
 #include "common.h"
@@ -196,8 +196,14 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
   if (tid == 0) { info[0] = sweeps; info[1] = converged; }
 }
 
-// ---- large l: one launch per step, one wave per pair, rows in global memory -----------------
-constexpr int kStepEPL = kMaxL / 64;
+// ---- large l: block Jacobi, rows in global memory (L2), blocks of kJB rows ---------------------
+// The rows are cut into blocks of kJB = 16.  One sweep = one "diagonal" launch, in which every
+// workgroup orthogonalises the pairs inside two blocks (round robin within a block), followed by a
+// round robin over block pairs, one launch per round: workgroup p loads blocks (I, J) into LDS and
+// rotates all kJB x kJB cross pairs in kJB steps (step s pairs row i of I with row (i + s) mod kJB of
+// J; the row of I stays in registers, the rows of J travel through LDS), then writes both blocks
+// back.  Every pair of rows is met exactly once per sweep; launches replace grid-wide barriers.
+constexpr int kJB = 16;
 
 __global__ void k_jacobi_init(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ W) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
@@ -206,34 +212,107 @@ __global__ void k_jacobi_init(const double* __restrict__ R, int ldr, int l, int 
   W[(int64_t)i * Lp + c] = R[(int64_t)i * ldr + c];
 }
 
+// outer < 0: diagonal launch (workgroup p owns blocks 2p and 2p+1); otherwise round `outer` of the
+// round robin over nblk2 (even) blocks.  256 threads = 16 row pairs x 16 lanes; EPL = ceil(l / 16).
+template <int EPL>
 __global__ void __launch_bounds__(256)
-k_jacobi_step(double* __restrict__ W, int l, int Lp, int step, double tol, int* __restrict__ rotated) {
-  const int lane = threadIdx.x & 63;
-  const int pi = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int L2 = (l + 1) & ~1;
-  if (pi >= L2 / 2) return;
-  int a, b;
-  rr_pair(pi, step, L2, a, b);
-  if (b >= l) return;
-  double* wa = W + (int64_t)a * Lp;
-  double* wb = W + (int64_t)b * Lp;
-  double x[kStepEPL], y[kStepEPL], al = 0.0, be = 0.0, ga = 0.0;
-#pragma unroll
-  for (int e = 0; e < kStepEPL; ++e) {
-    const int col = lane + 64 * e;
-    x[e] = col < l ? wa[col] : 0.0;
-    y[e] = col < l ? wb[col] : 0.0;
-    al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
+k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, double tol, int* __restrict__ rotated) {
+  extern __shared__ double sh[];               // 2 * kJB rows of l doubles: block I, then block J
+  const int tid = threadIdx.x, pi = tid >> 4, rl = tid & 15;
+  int I, J;
+  if (outer < 0) { I = 2 * blockIdx.x; J = I + 1; }
+  else rr_pair(blockIdx.x, outer, nblk2, I, J);
+  const int rI = I * kJB, rJ = J * kJB;
+  if (rI >= l) return;                                  // uniform over the workgroup
+  const int nI = min(kJB, l - rI), nJ = max(0, min(kJB, l - rJ));
+  if (outer >= 0 && nJ == 0) return;                    // the padding block of an odd block count
+  for (int idx = tid; idx < 2 * kJB * l; idx += 256) {
+    const int rr = idx / l, c = idx - rr * l;
+    const bool live = rr < kJB ? rr < nI : rr - kJB < nJ;
+    const int grow = rr < kJB ? rI + rr : rJ + rr - kJB;
+    sh[idx] = live ? W[(int64_t)grow * Lp + c] : 0.0;
   }
-  al = wave_sum(al); be = wave_sum(be); ga = wave_sum(ga);
-  double c, s;
-  if (!rotation(al, be, ga, tol * tol, c, s)) return;
+  __syncthreads();
+  const double tol2 = tol * tol;
+  bool any = false;
+  if (outer < 0) {
+    const int blk = pi >> 3, q = pi & 7, nrows = blk == 0 ? nI : nJ;
+    for (int step = 0; step < kJB - 1; ++step) {
+      int a, b;
+      rr_pair(q, step, kJB, a, b);
+      const bool valid = b < nrows;                     // a < b
+      double* wa = sh + (blk * kJB + a) * l;
+      double* wb = sh + (blk * kJB + b) * l;
+      double x[EPL], y[EPL], al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
-  for (int e = 0; e < kStepEPL; ++e) {
-    const int col = lane + 64 * e;
-    if (col < l) { wa[col] = c * x[e] - s * y[e]; wb[col] = s * x[e] + c * y[e]; }
+      for (int e = 0; e < EPL; ++e) {
+        const int col = rl + 16 * e;
+        const bool in = valid && col < l;
+        x[e] = in ? wa[col] : 0.0;
+        y[e] = in ? wb[col] : 0.0;
+        al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
+      }
+      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      double c, s;
+      if (rotation(al, be, ga, tol2, c, s) && valid) {
+        any = true;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int col = rl + 16 * e;
+          if (col < l) { wa[col] = c * x[e] - s * y[e]; wb[col] = s * x[e] + c * y[e]; }
+        }
+      }
+      __syncthreads();
+    }
+  } else {
+    double x[EPL];
+    double* wa = sh + pi * l;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const int col = rl + 16 * e;
+      x[e] = (pi < nI && col < l) ? wa[col] : 0.0;
+    }
+    for (int step = 0; step < kJB; ++step) {
+      const int j = (pi + step) & (kJB - 1);
+      const bool valid = pi < nI && j < nJ;
+      double* wb = sh + (kJB + j) * l;
+      double y[EPL], al = 0.0, be = 0.0, ga = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const int col = rl + 16 * e;
+        y[e] = (valid && col < l) ? wb[col] : 0.0;
+        al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
+      }
+      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      double c, s;
+      if (rotation(al, be, ga, tol2, c, s) && valid) {
+        any = true;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int col = rl + 16 * e;
+          const double xn = c * x[e] - s * y[e];
+          if (col < l) wb[col] = s * x[e] + c * y[e];
+          x[e] = xn;
+        }
+      }
+      __syncthreads();
+    }
+    if (pi < nI) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const int col = rl + 16 * e;
+        if (col < l) wa[col] = x[e];
+      }
+    }
   }
-  if (lane == 0) *rotated = 1;
+  __syncthreads();
+  for (int idx = tid; idx < 2 * kJB * l; idx += 256) {
+    const int rr = idx / l, c = idx - rr * l;
+    const bool live = rr < kJB ? rr < nI : rr - kJB < nJ;
+    const int grow = rr < kJB ? rI + rr : rJ + rr - kJB;
+    if (live) W[(int64_t)grow * Lp + c] = sh[idx];
+  }
+  if (any && rl == 0) *rotated = 1;
 }
 
 __global__ void k_set_int(int* p, int v) { *p = v; }
@@ -300,6 +379,28 @@ static int launch_jacobi_lds(const double* R, int ldr, int l, int Lp, SvdWork& w
   return BRSVD_OK;
 }
 
+template <int EPL>
+static int launch_jacobi_block_inst(double* W, int l, int Lp, int nblk2, int outer, double tol, int* rotated,
+                                    hipStream_t stream) {
+  auto kern = k_jacobi_block<EPL>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      2 * kJB * kMaxL * (int)sizeof(double)));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(nblk2 / 2), dim3(256), (size_t)2 * kJB * l * sizeof(double), stream, W, l, Lp, nblk2,
+                     outer, tol, rotated);
+  return BRSVD_OK;
+}
+static int launch_jacobi_block(double* W, int l, int Lp, int nblk2, int outer, double tol, int* rotated,
+                               hipStream_t stream) {
+  if (l <= 192) return launch_jacobi_block_inst<12>(W, l, Lp, nblk2, outer, tol, rotated, stream);
+  if (l <= 272) return launch_jacobi_block_inst<17>(W, l, Lp, nblk2, outer, tol, rotated, stream);
+  if (l <= 384) return launch_jacobi_block_inst<24>(W, l, Lp, nblk2, outer, tol, rotated, stream);
+  return launch_jacobi_block_inst<32>(W, l, Lp, nblk2, outer, tol, rotated, stream);
+}
+
 int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag, double* S,
               float* S32, float* XV, float* XU, double* Ur, double* Vr, hipStream_t stream) {
   if (l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
@@ -324,12 +425,11 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
     if (host_flag == 0) {
       hipLaunchKernelGGL(k_jacobi_init, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream, R,
                          ldr, l, Lp, w.W);
-      const int L2 = (l + 1) & ~1;
-      const unsigned blocks = (unsigned)ceil_div(L2 / 2, 4);
+      const int nblk = (int)ceil_div(l, kJB), nblk2 = (nblk + 1) & ~1;
       while (!converged && sweeps < kMaxSweeps) {
         hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, stream, rotated, 0);
-        for (int step = 0; step < L2 - 1; ++step)
-          hipLaunchKernelGGL(k_jacobi_step, dim3(blocks), dim3(256), 0, stream, w.W, l, Lp, step, tol, rotated);
+        for (int outer = -1; outer < nblk2 - 1; ++outer)
+          BRSVD_TRY(launch_jacobi_block(w.W, l, Lp, nblk2, outer, tol, rotated, stream));
         BRSVD_HIP_TRY(hipGetLastError());
         int rot = 1;
         BRSVD_HIP_TRY(hipMemcpyAsync(&rot, rotated, sizeof(int), hipMemcpyDeviceToHost, stream));

@@ -149,7 +149,7 @@ def test_orth_rank_deficient_panel():
         B.brsvd_orth(torch.zeros(100, 8, device=dev), method=B.BRSVD_ORTH_AUTO)
 
 
-@pytest.mark.parametrize("l", [1, 2, 7, 30, 111, 128, 129, 272])
+@pytest.mark.parametrize("l", [1, 2, 7, 30, 111, 128, 129, 272, 300, 512])
 def test_small_svd_jacobi(l):
     """R is the triangular factor of a matrix with prescribed singular values (cond 1e6, about the
     largest a factor derived from fp32 data can meaningfully have)."""
