@@ -101,12 +101,12 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
 // One workgroup of 1024 threads; blocked right-looking factorisation G = R^T R with 16 x 16
 // blocks, then R^-1 by recursive doubling (invert the diagonal blocks, then merge neighbouring
 // blocks: inv([R11 R12; 0 R22]) = [X11, -X11 R12 X22; 0, X22]).  Everything is fp64.  For
-// l <= kCholLdsMaxL the matrix lives in LDS for the whole kernel; above that it stays in global
+// Lp <= kCholLdsMaxLp the matrix lives in LDS for the whole kernel; above that it stays in global
 // memory (L2) and only the current 16-row panel is mirrored in LDS.
 // A pivot <= tol * its original diagonal entry is clamped to that value (lenient) or sets
 // flag[0] = 1 + column and ends the kernel.
 constexpr int kNB = 16;
-constexpr int kCholLdsMaxL = 136;
+constexpr int kCholLdsMaxLp = 128;    // largest padded size whose (Lp x (Lp+1)) fp64 matrix fits the LDS
 
 // Broadcast of lane `src` (a compile-time constant after unrolling): two scalar lane reads.
 __device__ __forceinline__ double shfl_d(double v, int src) {
@@ -201,6 +201,29 @@ __device__ void inv_diag_wave(double* M, int ld, int kb, int nb, int lane) {
   }
 }
 
+// Trailing update of one 16 x 16 tile on the fp64 matrix cores: M[r0.., c0..] -= P[:, r0..]^T P[:, c0..],
+// P = the 16 freshly solved rows of R (row stride ldp).  Lane (r, g) holds P[4*kk + g][. + r] as A and
+// B operand of step kk; accumulator component v of lane (r, g) is entry [g + 4*v][r].
+__device__ __forceinline__ void trailing_tile(double* M, int64_t ld, const double* P, int ldp, int r0, int c0,
+                                              int lane) {
+  const int r = lane & 15, g = lane >> 4;
+  double* mt = M + (int64_t)(r0 + g) * ld + c0 + r;
+  doublex4 acc;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) acc[v] = mt[(int64_t)4 * v * ld];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const double* prow = P + (4 * kk + g) * ldp;
+    acc = mfma_f64(-prow[r0 + r], prow[c0 + r], acc);
+  }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) mt[(int64_t)4 * v * ld] = acc[v];
+}
+
+// The working matrix is padded to Lp x Lp with an identity block, so that every block is a full
+// 16 x 16 tile.  Schedule of the factorisation: wave 0 factors the diagonal block of step k+1 (after
+// updating that one tile) while the other waves finish the trailing update of step k, which takes
+// the 16-step pivot chain off the critical path of all but the first block.
 template <bool IN_LDS>
 __global__ void __launch_bounds__(1024)
 k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
@@ -215,88 +238,80 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   if (flag[0] != 0) return;           // an earlier panel already broke down: results are void anyway
   double* M;
   int ld;
-  double* pan;                        // current 16-row panel R[kb:kb+nb, :] (row stride ldp)
+  double* pan;                        // current 16-row panel R[kb:kb+16, :] (row stride ldp)
   int ldp;
   if (IN_LDS) {
-    M = rest; ld = l | 1;
-    for (int idx = tid; idx < l * l; idx += 1024) {
-      int i = idx / l, c = idx - i * l;
-      M[i * ld + c] = c >= i ? G[(int64_t)i * Lp + c] : 0.0;
+    M = rest; ld = Lp + 1;
+    for (int idx = tid; idx < Lp * Lp; idx += 1024) {
+      const int i = idx / Lp, c = idx - i * Lp;
+      M[i * ld + c] = (i < l && c < l) ? (c >= i ? G[(int64_t)i * Lp + c] : 0.0) : (i == c ? 1.0 : 0.0);
     }
     pan = nullptr; ldp = ld;
   } else {
     M = G; ld = Lp;
+    for (int idx = tid; idx < Lp * Lp; idx += 1024) {
+      const int i = idx / Lp, c = idx - i * Lp;
+      if (i >= l || c >= l) M[(int64_t)i * ld + c] = i == c ? 1.0 : 0.0;
+    }
     pan = rest; ldp = kMaxL;
   }
   if (tid == 0) bad = 0;
   __syncthreads();
-  for (int i = tid; i < l; i += 1024) d0[i] = M[(int64_t)i * ld + i];
+  for (int i = tid; i < Lp; i += 1024) d0[i] = M[(int64_t)i * ld + i];
   __syncthreads();
 
   // ---- factorisation (skipped when G already holds an upper-triangular factor) ----
-  for (int kb = factored ? l : 0; kb < l; kb += kNB) {
-    const int nb = min(kNB, l - kb);
+  if (!factored) {
     if (wave == 0) {
-      bool ok = chol_diag_wave(M, ld, kb, nb, d0, tol, Rkk, lane);
-      if (!ok && !lenient && lane == 0) bad = kb + 1;
+      const bool ok = chol_diag_wave(M, ld, 0, kNB, d0, tol, Rkk, lane);
+      if (!ok && !lenient && lane == 0) bad = 1;
     }
     __syncthreads();
     if (bad) {
       if (tid == 0) flag[0] = bad;
       return;
     }
-    const int t0 = kb + nb;           // first trailing column
-    const int T = l - t0;
-    // row panel: R[kb:kb+nb, c] = R_kk^-T G[kb:kb+nb, c], one column per thread
-    for (int c = t0 + tid; c < l; c += 1024) {
+  }
+  for (int kb = factored ? Lp : 0; kb < Lp; kb += kNB) {
+    const int t0 = kb + kNB;          // first trailing column
+    // row panel: R[kb:kb+16, c] = R_kk^-T G[kb:kb+16, c], one column per thread
+    for (int c = t0 + tid; c < Lp; c += 1024) {
       double x[kNB];
 #pragma unroll
       for (int i = 0; i < kNB; ++i) {
-        if (i < nb) {
-          double sacc = M[(int64_t)(kb + i) * ld + c];
+        double sacc = M[(int64_t)(kb + i) * ld + c];
 #pragma unroll
-          for (int t = 0; t < kNB; ++t)
-            if (t < i) sacc = fma(-Rkk[t * 17 + i], x[t], sacc);
-          x[i] = sacc * Rkk[i * 17 + 16];
-          M[(int64_t)(kb + i) * ld + c] = x[i];
-          if (!IN_LDS) pan[i * ldp + c] = x[i];
-        }
+        for (int t = 0; t < kNB; ++t)
+          if (t < i) sacc = fma(-Rkk[t * 17 + i], x[t], sacc);
+        x[i] = sacc * Rkk[i * 17 + 16];
+        M[(int64_t)(kb + i) * ld + c] = x[i];
+        if (!IN_LDS) pan[i * ldp + c] = x[i];
       }
     }
     __syncthreads();
-    // trailing update with 4 x 4 register tiles: G[r][c] -= sum_t R[kb+t][r] R[kb+t][c], r <= c
+    // trailing update, upper tiles (ti <= tj) of the (Lp - t0)^2 block; tile 0 = (0, 0) is the next
+    // diagonal block: wave 0 updates it and factors it at once, waves 1..15 share the other tiles
     const double* P = IN_LDS ? (M + (int64_t)kb * ld) : pan;
-    const int nt = (T + 3) >> 2;
-    for (int idx = tid; idx < nt * nt; idx += 1024) {
-      const int ti = idx / nt, tj = idx - ti * nt;
-      if (tj < ti) continue;
-      const int r0 = t0 + 4 * ti, c0 = t0 + 4 * tj;
-      double acc[4][4];
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
-      for (int t = 0; t < nb; ++t) {
-        double av[4], bv[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          av[a] = (r0 + a < l) ? P[t * ldp + r0 + a] : 0.0;
-          bv[a] = (c0 + a < l) ? P[t * ldp + c0 + a] : 0.0;
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
+    const int T16 = (Lp - t0) / kNB;
+    const int ntile = T16 * (T16 + 1) / 2;
+    if (wave == 0) {
+      if (ntile > 0) {
+        trailing_tile(M, ld, P, ldp, t0, t0, lane);
+        const bool ok = chol_diag_wave(M, ld, t0, kNB, d0, tol, Rkk, lane);
+        if (!ok && !lenient && lane == 0) bad = t0 + 1;
       }
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int r = r0 + a, c = c0 + b;
-          if (r < l && c < l && r <= c) M[(int64_t)r * ld + c] -= acc[a][b];
-        }
+    } else {
+      for (int idx = wave; idx < ntile; idx += 15) {
+        int ti = 0, rem = idx;
+        while (rem >= T16 - ti) { rem -= T16 - ti; ++ti; }
+        trailing_tile(M, ld, P, ldp, t0 + kNB * ti, t0 + kNB * (ti + rem), lane);
+      }
     }
     __syncthreads();
+    if (bad) {
+      if (tid == 0) flag[0] = bad;
+      return;
+    }
   }
 
   // ---- publish R ----
@@ -489,12 +504,11 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
 // otherwise such a pivot raises the breakdown flag and ends the kernel.
 static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags, double tol,
                     hipStream_t stream, int factored = 0, int lenient = 0) {
-  const bool in_lds = l <= kCholLdsMaxL;
-  const int ld = l | 1;
-  const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)l * ld : (size_t)kNB * kMaxL)) * sizeof(double);
+  const bool in_lds = Lp <= kCholLdsMaxLp;
+  const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)Lp * (Lp + 1) : (size_t)kNB * kMaxL)) * sizeof(double);
   static bool attr_set = false;
   if (!attr_set) {
-    const int max_lds = (16 * 17 + kMaxL + kCholLdsMaxL * (kCholLdsMaxL | 1)) * (int)sizeof(double);
+    const int max_lds = (16 * 17 + kMaxL + kCholLdsMaxLp * (kCholLdsMaxLp + 1)) * (int)sizeof(double);
     BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       max_lds));
     BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<false>, hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -44,13 +44,23 @@ k_rpca_norms(const float* __restrict__ M, int64_t count, double* __restrict__ pa
   }
 }
 
-// scal[0] = max over blocks of part[2b], scal[1] = sum of part[2b+1] (block order).
-__global__ void k_rpca_norms_final(const double* __restrict__ part, int nblocks, double* __restrict__ scal) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+// scal[0] = max over blocks of part[2b], scal[1] = sum of part[2b+1]: each of the 256 threads adds its
+// blocks b = tid, tid + 256, ... in order, then the threads' sums are added in lane and wave order.
+__global__ void __launch_bounds__(256)
+k_rpca_norms_final(const double* __restrict__ part, int nblocks, double* __restrict__ scal) {
+  __shared__ double sh[4];
+  __shared__ double shm[4];
   double mx = 0.0, ss = 0.0;
-  for (int b = 0; b < nblocks; ++b) { mx = fmax(mx, part[2 * b]); ss += part[2 * b + 1]; }
-  scal[0] = mx;
-  scal[1] = ss;
+  for (int b = threadIdx.x; b < nblocks; b += 256) { mx = fmax(mx, part[2 * b]); ss += part[2 * b + 1]; }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmax(mx, __shfl_xor(mx, off, 64));
+  if (lane == 0) shm[wave] = mx;
+  const double s = block_sum(ss, sh);
+  if (threadIdx.x == 0) {
+    scal[0] = fmax(fmax(shm[0], shm[1]), fmax(shm[2], shm[3]));
+    scal[1] = s;
+  }
 }
 
 // out[slot] = sum of part[0..nblocks) in block order.
@@ -81,12 +91,13 @@ __device__ __forceinline__ float shrinkf(float x, float eps) {
 
 constexpr int kRpcaTR = 32;
 
-// acc[i] = row (row0 + i) of U diag(shrink(sigma, inv_mu)) V^T at column `col` (zero beyond n);
+// acc[i] = row (row0 + rsub + i) of U diag(shrink(sigma, inv_mu)) V^T at column `col` (zero beyond n);
 // `us` (LDS, kRpcaTR x l) receives the block's rows of U scaled by the shrunk singular values.
+template <int RPT>
 __device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const float* __restrict__ sig,
                                              const float* __restrict__ Vt, int64_t m, int64_t n, int l,
-                                             float inv_mu, int64_t row0, int64_t col, float* us,
-                                             float (&acc)[kRpcaTR]) {
+                                             float inv_mu, int64_t row0, int rsub, int64_t col, float* us,
+                                             float (&acc)[RPT]) {
   const int tid = threadIdx.x;
   for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
     const int i = idx / l, t = idx - i * l;
@@ -96,12 +107,12 @@ __device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const 
   }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < kRpcaTR; ++i) acc[i] = 0.f;
+  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
   if (col < n) {
     for (int t = 0; t < l; ++t) {
       const float v = Vt[(int64_t)t * n + col];
 #pragma unroll
-      for (int i = 0; i < kRpcaTR; ++i) acc[i] = fmaf(us[i * l + t], v, acc[i]);
+      for (int i = 0; i < RPT; ++i) acc[i] = fmaf(us[(rsub + i) * l + t], v, acc[i]);
     }
   }
 }
@@ -113,7 +124,10 @@ __device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const 
 //   S = shrink(M - L + Y/mu, lambda/mu)
 //   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
 //   X_next = M - S + Y / mu_next
-// L is stored only when Lout != nullptr.
+// L is stored only when Lout != nullptr.  CW = columns per workgroup (256, 128 or 64: narrow matrices
+// take a narrower tile so that lanes are not wasted beyond column n); the 256 threads are CW columns
+// x 256/CW row slices of kRpcaTR * CW / 256 rows each.
+template <int CW>
 __global__ void __launch_bounds__(256)
 k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const float* __restrict__ sig,
               const float* __restrict__ Vt, int64_t m, int64_t n, int l, float inv_mu, float mu,
@@ -121,16 +135,18 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
               float* __restrict__ Y, float* __restrict__ X, double* __restrict__ part) {
   extern __shared__ float us[];
   __shared__ double sh[4];
+  constexpr int RPT = kRpcaTR * CW / 256;
   const int tid = threadIdx.x;
-  const int64_t col = (int64_t)blockIdx.x * 256 + tid;
+  const int rsub = (tid / CW) * RPT;
+  const int64_t col = (int64_t)blockIdx.x * CW + tid % CW;
   const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  float acc[kRpcaTR];
-  lowrank_tile(U, sig, Vt, m, n, l, inv_mu, row0, col, us, acc);
+  float acc[RPT];
+  lowrank_tile<RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
   double z2 = 0.0;
   if (col < n) {
 #pragma unroll
-    for (int i = 0; i < kRpcaTR; ++i) {
-      const int64_t row = row0 + i;
+    for (int i = 0; i < RPT; ++i) {
+      const int64_t row = row0 + rsub + i;
       if (row < m) {
         const int64_t e = row * n + col;
         const float mv = M[e], yv = Y[e], lv = acc[i];
@@ -151,19 +167,33 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
 
 // L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
 // same tile arithmetic as the update kernel, so it is the L that iteration used.
+template <int CW>
 __global__ void __launch_bounds__(256)
 k_rpca_lowrank(const float* __restrict__ U, const float* __restrict__ sig, const float* __restrict__ Vt,
                int64_t m, int64_t n, int l, float inv_mu, float* __restrict__ Lout) {
   extern __shared__ float us[];
-  const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  constexpr int RPT = kRpcaTR * CW / 256;
+  const int rsub = (threadIdx.x / CW) * RPT;
+  const int64_t col = (int64_t)blockIdx.x * CW + threadIdx.x % CW;
   const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  float acc[kRpcaTR];
-  lowrank_tile(U, sig, Vt, m, n, l, inv_mu, row0, col, us, acc);
+  float acc[RPT];
+  lowrank_tile<RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
   if (col < n) {
 #pragma unroll
-    for (int i = 0; i < kRpcaTR; ++i)
-      if (row0 + i < m) Lout[(row0 + i) * n + col] = acc[i];
+    for (int i = 0; i < RPT; ++i)
+      if (row0 + rsub + i < m) Lout[(row0 + rsub + i) * n + col] = acc[i];
   }
+}
+
+// Column tile: the width among 256, 128, 64 that wastes the fewest lanes beyond column n (ties: wider).
+static int rpca_col_tile(int64_t n) {
+  int best = 256;
+  int64_t waste = ceil_div(n, 256) * 256 - n;
+  for (int cw : {128, 64}) {
+    const int64_t w = ceil_div(n, cw) * cw - n;
+    if (w < waste) { waste = w; best = cw; }
+  }
+  return best;
 }
 
 // P *= 1 / sqrt(*s2)  (normalisation of a power-method vector held in a padded panel)
@@ -175,13 +205,13 @@ __global__ void k_scale_rsqrt(float* __restrict__ P, int64_t count, const double
 }
 
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
-  const int64_t blocks = ceil_div(n, 256) * ceil_div(m, kRpcaTR);
+  const int64_t blocks = ceil_div(n, rpca_col_tile(n)) * ceil_div(m, kRpcaTR);
   return (uint64_t)std::max<int64_t>(blocks, 2 * kRpcaBlocks);
 }
 
 int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream) {
   hipLaunchKernelGGL(k_rpca_norms, dim3(kRpcaBlocks), dim3(256), 0, stream, M, count, part);
-  hipLaunchKernelGGL(k_rpca_norms_final, dim3(1), dim3(64), 0, stream, part, kRpcaBlocks, scal);
+  hipLaunchKernelGGL(k_rpca_norms_final, dim3(1), dim3(256), 0, stream, part, kRpcaBlocks, scal);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
@@ -197,11 +227,17 @@ int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y
 int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l,
                 float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X, double* part,
                 double* resid2_out, hipStream_t stream) {
-  dim3 grid((unsigned)ceil_div(n, 256), (unsigned)ceil_div(m, kRpcaTR));
+  const int cw = rpca_col_tile(n);
+  dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
   const size_t lds = (size_t)kRpcaTR * l * sizeof(float);
-  hipLaunchKernelGGL(k_rpca_update, grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, 1.0f / mu, mu,
-                     lambda / mu, 1.0f / mu_next, Lout, S, Y, X, part);
+#define BRSVD_RPCA_UPDATE(CW)                                                                                    \
+  hipLaunchKernelGGL(k_rpca_update<CW>, grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, 1.0f / mu, mu,     \
+                     lambda / mu, 1.0f / mu_next, Lout, S, Y, X, part)
+  if (cw == 256) BRSVD_RPCA_UPDATE(256);
+  else if (cw == 128) BRSVD_RPCA_UPDATE(128);
+  else BRSVD_RPCA_UPDATE(64);
+#undef BRSVD_RPCA_UPDATE
   hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part, (int)(grid.x * grid.y), resid2_out);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
@@ -209,10 +245,13 @@ int rpca_update(const float* M, const float* U, const float* sig, const float* V
 
 int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l, float mu,
                  float* Lout, hipStream_t stream) {
-  dim3 grid((unsigned)ceil_div(n, 256), (unsigned)ceil_div(m, kRpcaTR));
+  const int cw = rpca_col_tile(n);
+  dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
-  hipLaunchKernelGGL(k_rpca_lowrank, grid, dim3(256), (size_t)kRpcaTR * l * sizeof(float), stream, U, sig, Vt, m,
-                     n, l, 1.0f / mu, Lout);
+  const size_t lds = (size_t)kRpcaTR * l * sizeof(float);
+  if (cw == 256) hipLaunchKernelGGL(k_rpca_lowrank<256>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
+  else if (cw == 128) hipLaunchKernelGGL(k_rpca_lowrank<128>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
+  else hipLaunchKernelGGL(k_rpca_lowrank<64>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }

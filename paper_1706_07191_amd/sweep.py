@@ -9,6 +9,11 @@
       count of the paper's Table 1 terms written out, 2*m*n*l*(2q+2) for the passes plus
       2*(m+n)*l^2 per orthonormalisation sweep and lift, and the share of each phase.
 
+  python -m paper_1706_07191_amd.sweep rpca   [--shape MxN ...] [--iters I] [--tol T]
+      the robust-PCA loop (Alg. 3, k = p = 10, q = 1) on a synthetic rank-5 + 5 % sparse matrix of the
+      given shape (default: configuration 5 and the two shapes of the paper's Table 2): iterations,
+      seconds, per-phase milliseconds per iteration and the GB/s of the pass and elementwise kernels.
+
 Every line of output is one JSON object.
 """
 from __future__ import annotations
@@ -110,6 +115,46 @@ def sweep_shapes(args):
             del A, Om, U, S, Vt
 
 
+def sweep_rpca(args):
+    import numpy as np
+    import torch
+
+    import paper_1706_07191_amd as B
+    from paper_1706_07191_amd import synth
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["C5"]
+    for shape in args.shape:
+        m, n = (int(x) for x in shape.lower().split("x"))
+        D, L0, S0 = synth.make_rpca(cfg, device=dev, m=m, n=n)
+        Om = synth.rpca_omegas(cfg, n, args.iters, device=dev)
+        lam = 1.0 / np.sqrt(max(m, n))
+        h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536)))
+        try:
+            x0 = synth.gaussian(n, 1, cfg.seed + 5, device=dev).reshape(-1).contiguous()
+            n2 = B.brsvd_norm2_power(h, D, x0, 20)
+            L = torch.empty_like(D)
+            S = torch.empty_like(D)
+            work = torch.empty(2 * m * n, device=dev)
+            for _ in range(args.reps):
+                L, S, res, done, st = B.brsvd_rpca_ialm_tol(h, D, Om, args.iters, args.tol, lam, 1.25 / n2, 1.5,
+                                                            norm2_M=n2, L=L, S=S, work=work)
+        finally:
+            B.brsvd_destroy(h)
+        by = 4.0 * m * n
+        an = st["gemm_an_seconds"] / max(st["gemm_an_launches"], 1)
+        at = st["gemm_at_seconds"] / max(st["gemm_at_launches"], 1)
+        print(json.dumps({"m": m, "n": n, "iterations": done, "tol": args.tol, "residual": res[-1],
+                          "seconds": round(st["total_seconds"], 6),
+                          "ms_per_iteration": {key[:-8]: round(st[key] / done * 1e3, 4) for key in
+                                               ("total_seconds", "gemm_an_seconds", "gemm_at_seconds", "orth_seconds",
+                                                "svd_seconds", "lift_seconds", "elementwise_seconds")},
+                          "gemm_an_GBps": round(by / an / 1e9, 1), "gemm_at_GBps": round(by / at / 1e9, 1),
+                          "elementwise_GBps": round(20.0 * m * n / (st["elementwise_seconds"] / done) / 1e9, 1),
+                          "L_vs_planted": float(torch.linalg.norm(L - L0) / torch.linalg.norm(L0)),
+                          "S_vs_planted": float(torch.linalg.norm(S - S0) / torch.linalg.norm(S0))}), flush=True)
+        del D, L0, S0, Om, L, S, work
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -123,6 +168,11 @@ def main(argv=None) -> int:
     s.add_argument("--p", type=int, default=10)
     s.add_argument("--q", type=int, default=1)
     s.add_argument("--reps", type=int, default=3)
+    r = sub.add_parser("rpca")
+    r.add_argument("--shape", nargs="+", default=["76800x2000", "2073600x100", "32256x2383"])
+    r.add_argument("--iters", type=int, default=30)
+    r.add_argument("--tol", type=float, default=1e-7)
+    r.add_argument("--reps", type=int, default=2)
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
@@ -130,7 +180,7 @@ def main(argv=None) -> int:
         return 2
     import paper_1706_07191_amd as B
     B.lib()
-    (sweep_gemm if args.cmd == "gemm" else sweep_shapes)(args)
+    {"gemm": sweep_gemm, "shapes": sweep_shapes, "rpca": sweep_rpca}[args.cmd](args)
     return 0
 
 
