@@ -63,13 +63,17 @@ k_rpca_norms_final(const double* __restrict__ part, int nblocks, double* __restr
   }
 }
 
-// out[slot] = sum of part[0..nblocks) in block order.
-__global__ void k_sum_partials(const double* __restrict__ part, int nblocks, double* __restrict__ out) {
+// out[blockIdx.x] = sum of part[blockIdx.x * per .. min(nblocks, (blockIdx.x + 1) * per)): thread t adds its
+// entries t, t + 256, ... of the slice in order, then the threads' sums are added in lane and wave
+// order.  One launch with per >= nblocks gives the whole sum; long lists take two launches.
+__global__ void __launch_bounds__(256)
+k_sum_partials(const double* __restrict__ part, int nblocks, int per, double* __restrict__ out) {
   __shared__ double sh[4];
+  const int b0 = blockIdx.x * per, b1 = min(nblocks, b0 + per);
   double s = 0.0;
-  for (int b = threadIdx.x; b < nblocks; b += 256) s += part[b];
+  for (int b = b0 + threadIdx.x; b < b1; b += 256) s += part[b];
   s = block_sum(s, sh);
-  if (threadIdx.x == 0) *out = s;
+  if (threadIdx.x == 0) out[blockIdx.x] = s;
 }
 
 // Multiplier initialisation of Alg. 3: Y0 = M / J, S0 = 0, and the first SVD input
@@ -206,7 +210,7 @@ __global__ void k_scale_rsqrt(float* __restrict__ P, int64_t count, const double
 
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
   const int64_t blocks = ceil_div(n, rpca_col_tile(n)) * ceil_div(m, kRpcaTR);
-  return (uint64_t)std::max<int64_t>(blocks, 2 * kRpcaBlocks);
+  return (uint64_t)std::max<int64_t>(blocks + 64, 2 * kRpcaBlocks);   // + the first-level sums of the residual
 }
 
 int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream) {
@@ -238,7 +242,16 @@ int rpca_update(const float* M, const float* U, const float* sig, const float* V
   else if (cw == 128) BRSVD_RPCA_UPDATE(128);
   else BRSVD_RPCA_UPDATE(64);
 #undef BRSVD_RPCA_UPDATE
-  hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part, (int)(grid.x * grid.y), resid2_out);
+  // residual: the per-workgroup partial sums, in two levels when there are many (first-level sums go
+  // behind the partials)
+  const int nparts = (int)(grid.x * grid.y);
+  if (nparts > 8192) {
+    const int groups = 64, per = (int)ceil_div(nparts, groups);
+    hipLaunchKernelGGL(k_sum_partials, dim3(groups), dim3(256), 0, stream, part, nparts, per, part + nparts);
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part + nparts, groups, groups, resid2_out);
+  } else {
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, stream, part, nparts, nparts, resid2_out);
+  }
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
