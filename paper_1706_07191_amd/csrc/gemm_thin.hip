@@ -41,13 +41,26 @@ constexpr int kMaxNT = 17;   // n-tiles (of 16 columns) one launch keeps in regi
 // --------------------------------------------------------------------------------------------
 // gemm_an
 // --------------------------------------------------------------------------------------------
-// Workgroup: WAVES waves, wave w owns rows [row0 + w*MT*16, +MT*16) and all NT*16 columns.
-// blockIdx.x = row tile, blockIdx.y = split of the contraction range [0, K).
+// Workgroup: WAVES waves, wave w owns rows [row0 + w*MT*16, +MT*16) of a row tile and all NT*16 columns.
+// How a launch is cut into workgroups (AnShape): with S resident workgroup slots on the chip,
+//   * the first `whole` row tiles (a multiple of S) get one workgroup each, which runs over the whole
+//     contraction and writes Y directly: full rounds of equal work;
+//   * the `lt` leftover tiles are cut along the contraction so that they fill one more, shorter round
+//     evenly: f main splits per tile (slot s = chunks [s*(C-x)/f, (s+1)*(C-x)/f)) and, for the S - f*lt
+//     slots that would otherwise idle, a tail strip [C-x, C) of every leftover tile, j strips per extra
+//     workgroup, with x chosen so that j strips weigh as much as one main split.
+// Workgroups of one kind walk the contraction in lockstep, so the panel chunks they share stay in L2.
+// The partial panels of a leftover tile (slots 0..f-1, then the tail) are added in that order.
+struct AnShape {
+  int C, whole, lt, f, x, j;
+};
+
 template <int NT, int MT, int WAVES, int KC, bool VEC>
 __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
           const float* __restrict__ X, int ldx,
-          float* __restrict__ Y, int64_t ldy, int ncols, int64_t split_stride, int chunks_per_split) {
+          float* __restrict__ Y, int64_t ldy, int ncols,
+          float* __restrict__ Part, int64_t ldp, int64_t split_stride, AnShape sh) {
   extern __shared__ float lds[];
   constexpr int NTHREADS = WAVES * 64;
   constexpr int LD = NT * 16 + 4;          // +4: the four k-groups of a wave hit distinct banks
@@ -58,10 +71,34 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
-  const int row0 = blockIdx.x * (WAVES * MT * 16) + wave * (MT * 16);
-  const int kbeg = blockIdx.y * chunks_per_split * KC;
-  const int kend = min(K, kbeg + chunks_per_split * KC);
-  const int nchunks = (kend - kbeg + KC - 1) / KC;
+  float* buf0 = lds;
+  float* buf1 = lds + KC * LD;
+
+  int first_tile, nseg = 1, c0, c1, slot = 0;
+  bool partial = true;
+  {
+    const int b = blockIdx.x, C = sh.C;
+    if (b < sh.whole) {
+      first_tile = b; c0 = 0; c1 = C; partial = false;
+    } else if (b < sh.whole + sh.lt * sh.f) {
+      const int idx = b - sh.whole, s = idx % sh.f;
+      first_tile = sh.whole + idx / sh.f;
+      c0 = (int)((int64_t)s * (C - sh.x) / sh.f);
+      c1 = (int)((int64_t)(s + 1) * (C - sh.x) / sh.f);
+      slot = s;
+    } else {
+      const int i = b - sh.whole - sh.lt * sh.f;
+      first_tile = sh.whole + i * sh.j;
+      nseg = min(sh.j, sh.whole + sh.lt - first_tile);
+      c0 = C - sh.x; c1 = C; slot = sh.f;
+    }
+  }
+  const int nchunks = c1 - c0;
+  const int kbeg = c0 * KC;
+  const int kend = min(K, c1 * KC);
+
+  for (int seg = 0; seg < nseg; ++seg) {
+  const int row0 = (first_tile + seg) * (WAVES * MT * 16) + wave * (MT * 16);
 
   const float* ap[MT];
 #pragma unroll
@@ -107,10 +144,7 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
     }                                                                              \
   }
 
-  float* buf0 = lds;
-  float* buf1 = lds + KC * LD;
-
-  if (nchunks > 0) {
+  {
     LOAD_X(kbeg);
     LOAD_A(a_nxt, kbeg);
     STORE_X(buf0);
@@ -164,21 +198,24 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
 #undef STORE_X
 #undef LOAD_A
 
-  float* Yo = Y + (int64_t)blockIdx.y * split_stride;
+  float* Yo = partial ? Part + (int64_t)slot * split_stride : Y;
+  const int64_t ldo = partial ? ldp : ldy;
+  const int nc = partial ? NT * 16 : ncols;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       int row = row0 + mt * 16 + 4 * g + v;
       if (row < rows) {
-        float* yr = Yo + (int64_t)row * ldy;
+        float* yr = Yo + (int64_t)row * ldo;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           int col = nt * 16 + r;
-          if (col < ncols) yr[col] = acc[mt][nt][v];
+          if (col < nc) yr[col] = acc[mt][nt][v];
         }
       }
     }
+  }   // next tail strip of this workgroup
 }
 
 // --------------------------------------------------------------------------------------------
@@ -339,9 +376,10 @@ __global__ void k_reduce_splits(const T* __restrict__ part, int nsplit, int64_t 
 
 // In-place first level of a long split sum: slot g*fan <- sum of the slots [g*fan, min((g+1)*fan, nsplit))
 // in slot order (blockIdx.y = g).  Each thread only touches its own element of every slot.
-__global__ void k_reduce_groups_inplace(float* __restrict__ part, int nsplit, int fan, int64_t split_stride) {
+__global__ void k_reduce_groups_inplace(float* __restrict__ part, int nsplit, int fan, int64_t split_stride,
+                                        int64_t count) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= split_stride) return;
+  if (idx >= count) return;                 // count <= split_stride elements of every slot take part
   const int s0 = blockIdx.y * fan, s1 = min(nsplit, s0 + fan);
   float* p = part + idx;
   float s = p[(int64_t)s0 * split_stride];
@@ -456,32 +494,54 @@ static AnCfg an_cfg(int nt) {
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
 static double traffic_weight(int nt) { return nt <= 2 ? 1.0 : (nt <= 4 ? 0.6 : 0.3); }
 struct AnPlan {
-  int row_tiles, ksplit, chunks_per_split;
+  int row_tiles, tile_rows, nsplit, wgs;      // nsplit = partial panels per leftover tile (0: none)
+  AnShape sh;
 };
+// See AnShape.  Short contractions (the R^-1 applies and lifts: fewer than 16 chunks) and launches
+// with very many tiles keep one whole tile per workgroup.
 static AnPlan an_plan(int64_t rows, int64_t K, int nt) {
   AnCfg c = an_cfg(nt);
   AnPlan p;
-  p.row_tiles = (int)ceil_div(rows, c.waves * c.mt * 16);
-  const int nchunks = (int)ceil_div(K, c.kc);
+  p.tile_rows = c.waves * c.mt * 16;
+  p.row_tiles = (int)ceil_div(rows, p.tile_rows);
+  const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
   const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * 4;
-  const int wg_regs = nt <= 8 ? 2 : 1;         // waves per SIMD the register file allows, as workgroups per CU
-  const int want = pick_splits(p.row_tiles, wg_slots(lds_bytes, wg_regs), nchunks, (double)(nt * 16) / (double)K,
-                               traffic_weight(nt), "BRSVD_AN_SPLITS");
-  p.chunks_per_split = (int)ceil_div(nchunks, want);
-  p.ksplit = (int)ceil_div(nchunks, p.chunks_per_split);
+  const int wg_regs = nt <= 14 ? 2 : 1;        // workgroups per CU that the register file allows
+  const int S = wg_slots(lds_bytes, wg_regs);
+  AnShape sh = {C, T, 0, 1, 0, 0};
+  const char* e = getenv("BRSVD_AN_SPLITS");
+  if (e && atoi(e) > 0) {
+    sh.whole = 0; sh.lt = T; sh.f = (int)std::min<int64_t>(atoi(e), C);
+  } else if (C >= 16 && T < 8 * S) {
+    sh.whole = T / S * S;
+    sh.lt = T - sh.whole;
+    if (sh.lt > 0) {
+      sh.f = std::max(1, std::min(S / sh.lt, C / 8));
+      const int spare = S - sh.f * sh.lt;
+      if (spare > 0) {
+        sh.j = (int)ceil_div(sh.lt, spare);
+        sh.x = C / (1 + sh.f * sh.j);          // j strips weigh one main split: (C - x) / f = j * x
+        if (sh.x < 4) { sh.x = 0; sh.j = 0; }
+      }
+      if (sh.f == 1 && sh.x == 0) { sh.whole = T; sh.lt = 0; }
+    }
+  }
+  p.sh = sh;
+  p.nsplit = sh.lt > 0 ? sh.f + (sh.x > 0 ? 1 : 0) : 0;
+  p.wgs = sh.whole + sh.lt * sh.f + (sh.x > 0 ? (int)ceil_div(sh.lt, sh.j) : 0);
   return p;
 }
 
 uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp) {
   NGroups ng = column_groups(Lp);
   AnPlan p = an_plan(rows, K, ng.nt);
-  return p.ksplit > 1 ? (uint64_t)p.ksplit * rows * Lp * sizeof(float) : 0;
+  return (uint64_t)p.nsplit * rows * Lp * sizeof(float);
 }
 
 template <int NT, int MT, int WAVES, int KC, bool VEC>
 static int launch_an_inst(const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
-                          float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
-                          hipStream_t stream) {
+                          float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
+                          const AnPlan& p, hipStream_t stream) {
   auto kern = k_gemm_an<NT, MT, WAVES, KC, VEC>;
   constexpr int lds_bytes = 2 * KC * (NT * 16 + 4) * (int)sizeof(float);
   static bool attr_set = false;
@@ -490,23 +550,24 @@ static int launch_an_inst(const float* A, int64_t lda, int rows, int K, const fl
                                       lds_bytes));
     attr_set = true;
   }
-  dim3 grid(p.row_tiles, p.ksplit);
-  hipLaunchKernelGGL(kern, grid, dim3(WAVES * 64), lds_bytes, stream, A, lda, rows, K, X, ldx, Y, ldy,
-                     ncols, split_stride, p.chunks_per_split);
+  hipLaunchKernelGGL(kern, dim3(p.wgs), dim3(WAVES * 64), lds_bytes, stream, A, lda, rows, K, X, ldx, Y, ldy,
+                     ncols, part, ldp, split_stride, p.sh);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
 template <int NT>
 static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
-                        float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
-                        hipStream_t stream) {
+                        float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
+                        const AnPlan& p, hipStream_t stream) {
   constexpr int MT = 2;
   constexpr int WAVES = 4;
   constexpr int KC = NT <= 8 ? 64 : 32;
   if (vec)
-    return launch_an_inst<NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
-  return launch_an_inst<NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream);
+    return launch_an_inst<NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
+                                                   stream);
+  return launch_an_inst<NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
+                                                  stream);
 }
 
 #define BRSVD_NT_SWITCH(nt, CALL)                                                      \
@@ -521,9 +582,9 @@ static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, 
   }
 
 static int launch_an(int nt, bool vec, const float* A, int64_t lda, int rows, int K, const float* X,
-                     int ldx, float* Y, int64_t ldy, int ncols, int64_t split_stride, const AnPlan& p,
-                     hipStream_t stream) {
-#define CALL(N) launch_an_nt<N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, split_stride, p, stream)
+                     int ldx, float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
+                     const AnPlan& p, hipStream_t stream) {
+#define CALL(N) launch_an_nt<N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream)
   BRSVD_NT_SWITCH(nt, CALL)
 #undef CALL
 }
@@ -538,8 +599,9 @@ static int reduce_f32(float* part, int nsplit, int64_t split_stride, int64_t row
   if (total == 0) return BRSVD_OK;
   if (nsplit > 2 * kReduceFan) {
     const int groups = (int)ceil_div(nsplit, kReduceFan);
-    hipLaunchKernelGGL(k_reduce_groups_inplace, dim3((unsigned)ceil_div(split_stride, 256), groups), dim3(256), 0,
-                       stream, part, nsplit, kReduceFan, split_stride);
+    const int64_t count = rows * ldi;       // the rows being reduced, all ldi columns of each
+    hipLaunchKernelGGL(k_reduce_groups_inplace, dim3((unsigned)ceil_div(count, 256), groups), dim3(256), 0, stream,
+                       part, nsplit, kReduceFan, split_stride, count);
     nsplit = groups;
     split_stride *= kReduceFan;
   }
@@ -557,28 +619,27 @@ int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X
   NGroups ng = column_groups(Lp);
   AnPlan p = an_plan(rows, K, ng.nt);
   const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && K >= 4 && (K % 4 == 0);
-  if (p.ksplit > 1 && scratch_bytes < (uint64_t)p.ksplit * rows * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
+  if (scratch_bytes < (uint64_t)p.nsplit * rows * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
   if (verbose())
-    fprintf(stderr, "[brsvd] gemm_an rows=%ld K=%ld Lp=%d: %d row tiles x %d k-splits (%d chunks each), vec=%d\n",
-            (long)rows, (long)K, Lp, p.row_tiles, p.ksplit, p.chunks_per_split, (int)vec);
+    fprintf(stderr, "[brsvd] gemm_an rows=%ld K=%ld Lp=%d: %d whole tiles + %d leftover tiles x %d splits + tail of %d chunks "
+            "(%d per workgroup), %d chunks per tile, %d workgroups, vec=%d\n", (long)rows, (long)K, Lp, p.sh.whole, p.sh.lt,
+            p.sh.f, p.sh.x, p.sh.j, p.sh.C, p.wgs, (int)vec);
+  float* part = (float*)scratch;
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
     int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
     if (nt <= 0) break;
-    int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group
-    if (p.ksplit == 1) {
-      if (nc <= 0) continue;
-      BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, 0, p, stream));
-    } else {
-      float* part = (float*)scratch;
-      BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, part + c0, Lp, nt * 16,
-                          rows * Lp, p, stream));
-    }
+    int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group (may be <= 0)
+    BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr, Lp,
+                        rows * Lp, p, stream));
   }
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
-  if (p.ksplit > 1)
-    BRSVD_TRY(reduce_f32((float*)scratch, p.ksplit, rows * Lp, rows, ncols, Lp, Y, ldy, false, stream));
+  if (p.nsplit > 0) {
+    // rows of the leftover tiles: their partial panels, in split order
+    const int64_t r0 = (int64_t)p.sh.whole * p.tile_rows;
+    BRSVD_TRY(reduce_f32(part + r0 * Lp, p.nsplit, rows * Lp, rows - r0, ncols, Lp, Y + r0 * ldy, ldy, false, stream));
+  }
   return BRSVD_OK;
 }
 
