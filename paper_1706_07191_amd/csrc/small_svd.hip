@@ -53,8 +53,14 @@ __device__ __forceinline__ double rcp_nr(double x) {
 // with zeta = (be - al) / (2 ga), t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1/sqrt(1+t^2),
 // s = c t, written so that it needs one reciprocal and two reciprocal square roots.
 // Returns false (identity) when |ga| <= tol * sqrt(al * be).
-__device__ __forceinline__ bool rotation(double al, double be, double ga, double tol2, double& c, double& s) {
+// Sweeps end when a whole sweep met no pair with |cos| above kSettled: all cosines are then of the order
+// l * kSettled^2 after that sweep's rotations (quadratic convergence), below the rotation threshold, so
+// a further sweep that would only confirm it is not run.
+constexpr double kSettled2 = 1e-16;     // (1e-8)^2
+__device__ __forceinline__ bool rotation(double al, double be, double ga, double tol2, double& c, double& s,
+                                         bool& big) {
   c = 1.0; s = 0.0;
+  big = ga * ga > kSettled2 * al * be;
   if (!(ga * ga > tol2 * al * be)) return false;
   const double tau = be - al, g2 = 2.0 * ga;
   const double hh = fma(tau, tau, g2 * g2);
@@ -122,9 +128,17 @@ __device__ __forceinline__ double row8_sum(double v) {
   return v;
 }
 
-// LDS-resident Jacobi: each group of LPP lanes (16 or 8) owns one row pair per round-robin step, so a
-// wave handles 64/LPP pairs with one instruction stream and 64 pairs (l <= 128) take 1024 or 512
-// threads.  EPL = elements of a row per lane = ceil(l / LPP).
+// LDS-resident Jacobi: each group of LPP lanes (16) owns one row pair per step, so a wave handles
+// 64/LPP pairs with one instruction stream and up to 64 pairs (l <= 128) take 1024 threads.
+// EPL = elements of a row per lane = ceil(l / LPP).
+// Pair schedule of a sweep (every pair of rows met exactly once): the index range is halved
+// recursively.  At a level, every segment [base, base + n) is cut into a top half of h = ceil(n/2) rows
+// and a bottom half; in step s top row i meets bottom row (i + s) mod h, so h steps pair every top with
+// every bottom of the segment; the next level does the same inside both halves, all segments side by
+// side (l-1 .. l+1 steps in all).  Within a level a group keeps its top row in registers and only the
+// bottom rows travel through LDS, which halves the LDS traffic of the round-robin schedule.
+constexpr int kJLev = 7;      // levels for l <= 128
+
 template <int EPL, int LPP>
 __global__ void __launch_bounds__(64 * LPP)
 k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __restrict__ Wg,
@@ -133,7 +147,10 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
   extern __shared__ double W[];
   __shared__ int rotated;
   __shared__ int order_sh[kMaxL];
-  constexpr int NT = 64 * LPP;   // 64 row pairs per step
+  __shared__ short tb_top[kJLev][64], tb_bb[kJLev][64], tb_bs[kJLev][64], tb_hi[kJLev][64];
+  __shared__ short seg_base[2][128], seg_size[2][128];
+  __shared__ int lev_steps[kJLev];
+  constexpr int NT = 64 * LPP;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (breakdown_flag && breakdown_flag[0] != 0) {
     if (tid == 0) { info[0] = 0; info[1] = 0; }
@@ -144,8 +161,36 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
     int i = idx / l, c = idx - i * l;
     W[i * ld + c] = R[(int64_t)i * ldr + c];
   }
-  const int L2 = (l + 1) & ~1;
-  const int npairs = L2 / 2;
+  // schedule tables: per level and group, the top row, the bottom half [bb, bb + bs) and (h << 8) | i
+  if (tid == 0) { seg_base[0][0] = 0; seg_size[0][0] = (short)l; }
+  for (int lev = 0; lev < kJLev; ++lev) {
+    const int nseg = 1 << lev, cur = lev & 1;
+    if (tid < 64) tb_top[lev][tid] = -1;
+    __syncthreads();
+    if (tid < nseg) {
+      const int base = seg_base[cur][tid], size = seg_size[cur][tid];
+      const int h = (size + 1) >> 1, nb = size - h;
+      if (size >= 2) {
+        int off = 0;
+        for (int k = 0; k < tid; ++k) { const int sz = seg_size[cur][k]; if (sz >= 2) off += (sz + 1) >> 1; }
+        for (int i = 0; i < h; ++i) {
+          const int gid = off + i;
+          if (gid < 64) {
+            tb_top[lev][gid] = (short)(base + i); tb_bb[lev][gid] = (short)(base + h);
+            tb_bs[lev][gid] = (short)nb; tb_hi[lev][gid] = (short)((h << 8) | i);
+          }
+        }
+      }
+      seg_base[cur ^ 1][2 * tid] = (short)base; seg_size[cur ^ 1][2 * tid] = (short)h;
+      seg_base[cur ^ 1][2 * tid + 1] = (short)(base + h); seg_size[cur ^ 1][2 * tid + 1] = (short)nb;
+    }
+    if (tid == 0) {
+      int mx = 0;
+      for (int k = 0; k < nseg; ++k) { const int sz = seg_size[cur][k]; if (sz >= 2) mx = max(mx, (sz + 1) >> 1); }
+      lev_steps[lev] = mx;
+    }
+    __syncthreads();
+  }
   const int pi = tid / LPP;
   const int rl = tid % LPP;
   const double tol2 = tol * tol;
@@ -155,33 +200,54 @@ k_jacobi_lds(const double* __restrict__ R, int ldr, int l, int Lp, double* __res
     if (tid == 0) rotated = 0;
     __syncthreads();
     bool any = false;
-    for (int step = 0; step < L2 - 1; ++step) {
-      int a = 0, b = 0;
-      bool valid = pi < npairs;
-      if (valid) { rr_pair(pi, step, L2, a, b); valid = (b < l); }
-      double x[EPL], y[EPL], al = 0.0, be = 0.0, ga = 0.0;
+    for (int lev = 0; lev < kJLev; ++lev) {
+      const int steps = lev_steps[lev];
+      if (steps == 0) continue;                        // uniform over the workgroup
+      const int top = tb_top[lev][pi], bb = tb_bb[lev][pi], bs = tb_bs[lev][pi];
+      const int h = tb_hi[lev][pi] >> 8, i0 = tb_hi[lev][pi] & 255;
+      double x[EPL];
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
         const int col = rl + LPP * e;
-        const bool in = valid && col < l;
-        x[e] = in ? W[a * ld + col] : 0.0;
-        y[e] = in ? W[b * ld + col] : 0.0;
-        al = fma(x[e], x[e], al);
-        be = fma(y[e], y[e], be);
-        ga = fma(x[e], y[e], ga);
+        x[e] = (top >= 0 && col < l) ? W[top * ld + col] : 0.0;
       }
-      if (LPP == 16) { al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga); }
-      else { al = row8_sum(al); be = row8_sum(be); ga = row8_sum(ga); }
-      double c, s;
-      if (rotation(al, be, ga, tol2, c, s) && valid) {
-        any = true;
+      for (int step = 0; step < steps; ++step) {
+        int j = i0 + step;
+        if (j >= h) j -= h;
+        const bool valid = top >= 0 && step < h && j < bs;
+        const double* wb = W + (bb + j) * ld;
+        double y[EPL], al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
           const int col = rl + LPP * e;
-          if (col < l) {
-            W[a * ld + col] = c * x[e] - s * y[e];
-            W[b * ld + col] = s * x[e] + c * y[e];
+          y[e] = (valid && col < l) ? wb[col] : 0.0;
+          al = fma(x[e], x[e], al);
+          be = fma(y[e], y[e], be);
+          ga = fma(x[e], y[e], ga);
+        }
+        if (LPP == 16) { al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga); }
+        else { al = row8_sum(al); be = row8_sum(be); ga = row8_sum(ga); }
+        double c, s;
+        bool big;
+        const bool rot = rotation(al, be, ga, tol2, c, s, big) && valid;
+        any |= big && valid;
+        if (rot) {
+          double* wbw = W + (bb + j) * ld;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) {
+            const int col = rl + LPP * e;
+            const double xn = c * x[e] - s * y[e];
+            if (col < l) wbw[col] = s * x[e] + c * y[e];
+            x[e] = xn;
           }
+        }
+        __syncthreads();
+      }
+      if (top >= 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const int col = rl + LPP * e;
+          if (col < l) W[top * ld + col] = x[e];
         }
       }
       __syncthreads();
@@ -254,8 +320,10 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       }
       al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
       double c, s;
-      if (rotation(al, be, ga, tol2, c, s) && valid) {
-        any = true;
+      bool big;
+      const bool rot = rotation(al, be, ga, tol2, c, s, big) && valid;
+      any |= big && valid;
+      if (rot) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
           const int col = rl + 16 * e;
@@ -285,8 +353,10 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       }
       al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
       double c, s;
-      if (rotation(al, be, ga, tol2, c, s) && valid) {
-        any = true;
+      bool big;
+      const bool rot = rotation(al, be, ga, tol2, c, s, big) && valid;
+      any |= big && valid;
+      if (rot) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
           const int col = rl + 16 * e;
