@@ -50,6 +50,20 @@ def test_scaled_configs_in_core(name, m, n, b):
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, b, U, S, Vt, cfg.name)
 
 
+def test_largest_sketch_width():
+    """l = k + p = 512, the largest width the library accepts, on a matrix barely larger than l."""
+    dev = need_gpu()
+    m, n, k, p, q, b = 1400, 900, 480, 32, 1, 512
+    sig = torch.exp(-torch.arange(600, dtype=torch.float64) / 150.0)
+    A = synth.lowrank_plus_noise(m, n, sig, 1e-5, 4242)
+    Om = synth.gaussian(n, k + p, 4243)
+    cfg = synth.Config("wide", m, n, k, p, q, b, 600, lambda i: i, 1e-5, 4242)
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev))
+    check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, "l512")
+    with pytest.raises(B.BrsvdError):
+        B.brsvd_create(B.make_params(m, n, 500, 13, q))        # l = 513
+
+
 def test_forced_tsqr_matches_oracle():
     dev = need_gpu()
     cfg = synth.CONFIGS["C2"].scaled(3000, 2500, 700)

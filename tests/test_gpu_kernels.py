@@ -25,6 +25,8 @@ GEMM_SHAPES = [  # rows, n, l
     (260, 520, 300),      # two column groups
     (64, 8, 1),           # degenerate widths
     (40, 36, 36),         # l == n
+    (700, 1536, 512),     # the largest sketch width
+    (9000, 2100, 64),     # more row tiles than one round of workgroups: whole tiles plus a cut leftover round
 ]
 
 
@@ -76,7 +78,7 @@ def test_gemm_with_row_stride():
 
 
 @pytest.mark.parametrize("rows,l,cond", [(3000, 30, 1e2), (1000, 110, 1e4), (5000, 272, 1e3), (50, 50, 10.0),
-                                          (700, 1, 1.0)])
+                                          (700, 1, 1.0), (3000, 512, 1e3), (2000, 130, 1e3)])
 def test_orth_cholqr2(rows, l, cond):
     dev = need_gpu()
     print(f"[case] orth rows={rows} l={l} cond={cond}", flush=True)
@@ -99,7 +101,7 @@ def test_orth_cholqr2(rows, l, cond):
 
 
 @pytest.mark.parametrize("rows,l,cond", [(3000, 30, 1e2), (2500, 110, 1e6), (5000, 272, 1e4), (1024, 16, 10.0),
-                                          (1025, 64, 1e3), (40, 40, 10.0)])
+                                          (1025, 64, 1e3), (40, 40, 10.0), (2100, 512, 1e3)])
 def test_orth_tsqr(rows, l, cond):
     """The Householder-tree route, forced: orthonormal, same range, P = Q R with R upper triangular."""
     dev = need_gpu()
