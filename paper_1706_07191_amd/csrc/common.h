@@ -38,27 +38,35 @@ struct KernelEvents {
 };
 
 // Y (rows x ncols, ldy) = A (rows x K, lda) * X (K x Lp padded panel, ldx = Lp).
-// scratch holds split-K partial sums when the launch is split along K.
-uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp);
+// scratch holds partial sums when the launch is split along K.  fp32 and fp64 (esz = element size).
+uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp, int esz = 4);
 int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp,
             float* Y, int64_t ldy, int ncols, void* scratch, uint64_t scratch_bytes,
+            hipStream_t stream, const KernelEvents* ev = nullptr);
+int gemm_an(const double* A, int64_t lda, int64_t rows, int64_t K, const double* X, int Lp,
+            double* Y, int64_t ldy, int ncols, void* scratch, uint64_t scratch_bytes,
             hipStream_t stream, const KernelEvents* ev = nullptr);
 
 // Z (n x Lp padded panel) (+)= A^T * Q; A is rows x n (lda), Q is rows x Lp.  The row range is
 // cut at multiples of block_rows (the row blocks of the method) and each block into equal
 // sub-ranges; partial panels are summed in row order, so the result does not depend on timing.
-uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows);
+uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows, int esz = 4);
 int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp,
             float* Z, bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes,
+            hipStream_t stream, const KernelEvents* ev = nullptr);
+int gemm_at(const double* A, int64_t lda, int64_t rows, int64_t n, const double* Q, int Lp,
+            double* Z, bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes,
             hipStream_t stream, const KernelEvents* ev = nullptr);
 
 // dst (rows x Lp, zero padded) <- src (rows x l dense)
 int pad_panel(const float* src, int64_t rows, int l, float* dst, int Lp, hipStream_t stream);
+int pad_panel(const double* src, int64_t rows, int l, double* dst, int Lp, hipStream_t stream);
 // dst (rows x l dense) (+)= src (rows x Lp) restricted to the first l columns
-int unpad_panel(const float* src, int64_t rows, int Lp, int l, float* dst, bool accumulate,
-                hipStream_t stream);
+int unpad_panel(const float* src, int64_t rows, int Lp, int l, float* dst, bool accumulate, hipStream_t stream);
+int unpad_panel(const double* src, int64_t rows, int Lp, int l, double* dst, bool accumulate, hipStream_t stream);
 // dst (l x rows, ld = rows) <- transpose of src (rows x Lp) restricted to the first l columns
 int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, hipStream_t stream);
+int transpose_panel(const double* src, int64_t rows, int Lp, int l, double* dst, hipStream_t stream);
 
 // ---- orthonormalisation (orth.hip, tsqr.hip) -----------------------------------------------
 struct OrthWork {

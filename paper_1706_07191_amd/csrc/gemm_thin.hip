@@ -26,6 +26,29 @@ namespace brsvd {
 __device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
+__device__ __forceinline__ doublex4 mfma16(double a, double b, doublex4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// Per element type: vector of four elements (MFMA accumulator, and four consecutive k of A), the
+// 16-byte unit the panel is staged with, and where accumulator component v of lane (r, g) sits in the
+// 16 x 16 tile: row 4*g + v for v_mfma_f32_16x16x4_f32, row g + 4*v for v_mfma_f64_16x16x4_f64
+// (column r for both).  The fp64 kernels are the same code at half the tile widths.
+template <typename T> struct El;
+template <> struct El<float> {
+  typedef floatx4 v4;
+  typedef floatx4 u16;
+  static constexpr int kPerU16 = 4;
+  static constexpr int kBankMod = 64;      // row strides are padded against 64 banks of 4 bytes
+  __device__ static __forceinline__ int acc_row(int g, int v) { return 4 * g + v; }
+};
+template <> struct El<double> {
+  typedef doublex4 v4;
+  typedef double u16 __attribute__((ext_vector_type(2)));
+  static constexpr int kPerU16 = 2;
+  static constexpr int kBankMod = 32;
+  __device__ static __forceinline__ int acc_row(int g, int v) { return g + 4 * v; }
+};
 
 // Identity the compiler cannot see through: the result is a new value living in VGPRs.  Used to
 // hand the prefetched block of A over to the MFMA stream, so that (a) the wait for the prefetch
@@ -55,24 +78,28 @@ struct AnShape {
   int C, whole, lt, f, x, j;
 };
 
-template <int NT, int MT, int WAVES, int KC, bool VEC>
+template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
 __global__ void __launch_bounds__(WAVES * 64)
-k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
-          const float* __restrict__ X, int ldx,
-          float* __restrict__ Y, int64_t ldy, int ncols,
-          float* __restrict__ Part, int64_t ldp, int64_t split_stride, AnShape sh) {
-  extern __shared__ float lds[];
+k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
+          const T* __restrict__ X, int ldx,
+          T* __restrict__ Y, int64_t ldy, int ncols,
+          T* __restrict__ Part, int64_t ldp, int64_t split_stride, AnShape sh) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  T* lds = reinterpret_cast<T*>(lds_raw);
+  typedef typename El<T>::v4 vec4;
+  typedef typename El<T>::u16 unit16;
+  constexpr int EPU = El<T>::kPerU16;
   constexpr int NTHREADS = WAVES * 64;
   constexpr int LD = NT * 16 + 4;          // +4: the four k-groups of a wave hit distinct banks
   constexpr int KS = KC / 16;              // 16-wide k steps per chunk
-  constexpr int ROWF4 = NT * 4;
+  constexpr int ROWF4 = NT * 16 / EPU;     // 16-byte units per panel row
   constexpr int F4 = KC * ROWF4;
   constexpr int XPT = (F4 + NTHREADS - 1) / NTHREADS;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
-  float* buf0 = lds;
-  float* buf1 = lds + KC * LD;
+  T* buf0 = lds;
+  T* buf1 = lds + KC * LD;
 
   int first_tile, nseg = 1, c0, c1, slot = 0;
   bool partial = true;
@@ -100,36 +127,36 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
   for (int seg = 0; seg < nseg; ++seg) {
   const int row0 = (first_tile + seg) * (WAVES * MT * 16) + wave * (MT * 16);
 
-  const float* ap[MT];
+  const T* ap[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     int row = min(row0 + mt * 16 + r, rows - 1);
     ap[mt] = A + (int64_t)row * lda;
   }
 
-  floatx4 acc[MT][NT];
+  vec4 acc[MT][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = vec4{T(0), T(0), T(0), T(0)};
 
-  floatx4 xr[XPT];
-  floatx4 a_cur[MT][KS], a_nxt[MT][KS];
+  unit16 xr[XPT];
+  vec4 a_cur[MT][KS], a_nxt[MT][KS];
 
 #define LOAD_X(kbase)                                                              \
   _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
     int idx = tid + i * NTHREADS;                                                  \
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
     int k = (kbase) + kr;                                                          \
-    floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};                                       \
-    if (idx < F4 && k < kend) v = *(const floatx4*)(X + (int64_t)k * ldx + c4 * 4); \
+    unit16 v = unit16{};                                                           \
+    if (idx < F4 && k < kend) v = *(const unit16*)(X + (int64_t)k * ldx + c4 * EPU); \
     xr[i] = v;                                                                     \
   }
 #define STORE_X(buf)                                                               \
   _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
     int idx = tid + i * NTHREADS;                                                  \
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
-    if (idx < F4) *(floatx4*)((buf) + kr * LD + c4 * 4) = xr[i];                   \
+    if (idx < F4) *(unit16*)((buf) + kr * LD + c4 * EPU) = xr[i];                  \
   }
 #define LOAD_A(dst, kbase)                                                         \
   _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                \
@@ -137,7 +164,7 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
     int k = (kbase) + s * 16 + 4 * g;                                              \
     if (VEC) {                                                                     \
       k = min(k, K - 4);                                                           \
-      dst[mt][s] = *(const floatx4*)(ap[mt] + k);                                  \
+      dst[mt][s] = *(const vec4*)(ap[mt] + k);                                  \
     } else {                                                                       \
       _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
         dst[mt][s][j] = ap[mt][min(k + j, K - 1)];                                 \
@@ -156,8 +183,8 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
   // freshly issued loads of the next chunk in the middle of the MFMA stream.
 #pragma nounroll
   for (int c = 0; c < nchunks; ++c) {
-    const float* cur = (c & 1) ? buf1 : buf0;
-    float* nxt = (c & 1) ? buf0 : buf1;
+    const T* cur = (c & 1) ? buf1 : buf0;
+    T* nxt = (c & 1) ? buf0 : buf1;
     const bool more = (c + 1 < nchunks);
     // the block of A prefetched during the previous chunk becomes current (this copy is where
     // the wait for those loads sits), then the next one is requested
@@ -172,14 +199,14 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
     // 4*KS steps of 4 contraction indices each; the panel values of step t+1 are read from LDS
     // while the MFMAs of step t run (register double buffer bq).
     {
-      float bq[2][NT];
-      const float* bbase = cur + (4 * g) * LD + r;
+      T bq[2][NT];
+      const T* bbase = cur + (4 * g) * LD + r;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) bq[0][nt] = bbase[nt * 16];
 #pragma unroll
       for (int t = 0; t < 4 * KS; ++t) {
         if (t + 1 < 4 * KS) {
-          const float* brow = bbase + (((t + 1) >> 2) * 16 + ((t + 1) & 3)) * LD;
+          const T* brow = bbase + (((t + 1) >> 2) * 16 + ((t + 1) & 3)) * LD;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) bq[(t + 1) & 1][nt] = brow[nt * 16];
         }
@@ -198,16 +225,16 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
 #undef STORE_X
 #undef LOAD_A
 
-  float* Yo = partial ? Part + (int64_t)slot * split_stride : Y;
+  T* Yo = partial ? Part + (int64_t)slot * split_stride : Y;
   const int64_t ldo = partial ? ldp : ldy;
   const int nc = partial ? NT * 16 : ncols;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      int row = row0 + mt * 16 + 4 * g + v;
+      int row = row0 + mt * 16 + El<T>::acc_row(g, v);
       if (row < rows) {
-        float* yr = Yo + (int64_t)row * ldo;
+        T* yr = Yo + (int64_t)row * ldo;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           int col = nt * 16 + r;
@@ -225,20 +252,25 @@ k_gemm_an(const float* __restrict__ A, int64_t lda, int rows, int K,
 // panel columns; blockIdx.x = column tile, blockIdx.y = (row block, sub-range) of the contraction.
 // A lane loads MT consecutive columns of one row; component j of that load is the A operand of
 // m-tile j, which therefore holds the interleaved columns {cw + MT*i + j : i = 0..15}.
-template <int NT, int MT, int WAVES, int KC, bool VEC>
+template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
 __global__ void __launch_bounds__(WAVES * 64)
-k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
-          const float* __restrict__ Q, int ldq,
-          float* __restrict__ Zpart, int ldz, int64_t split_stride,
+k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
+          const T* __restrict__ Q, int ldq,
+          T* __restrict__ Zpart, int ldz, int64_t split_stride,
           int64_t block_rows, int sub, int rows_per_sub) {
-  extern __shared__ float lds[];
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  T* lds = reinterpret_cast<T*>(lds_raw);
+  typedef typename El<T>::v4 vec4;
+  typedef typename El<T>::u16 unit16;
+  constexpr int EPU = El<T>::kPerU16;
+  constexpr int BM = El<T>::kBankMod;
   constexpr int NTHREADS = WAVES * 64;
-  constexpr int LD = NT * 16 + ((16 - (NT * 16) % 64) + 64) % 64;   // LD % 64 == 16
+  constexpr int LD = NT * 16 + ((16 - (NT * 16) % BM) + BM) % BM;   // row stride = 16 elements mod the bank period
   constexpr int KS = KC / 4;               // 4-row k steps per chunk
-  constexpr int ROWF4 = NT * 4;
+  constexpr int ROWF4 = NT * 16 / EPU;     // 16-byte units per panel row
   constexpr int F4 = KC * ROWF4;
   constexpr int XPT = (F4 + NTHREADS - 1) / NTHREADS;
-  typedef float vecT __attribute__((ext_vector_type(MT)));
+  typedef T vecT __attribute__((ext_vector_type(MT)));
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
@@ -258,13 +290,13 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
     for (int j = 0; j < MT; ++j) col[j] = min(cw + MT * r + j, n - 1);
   }
 
-  floatx4 acc[MT][NT];
+  vec4 acc[MT][NT];
 #pragma unroll
   for (int j = 0; j < MT; ++j)
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) acc[j][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NT; ++nt) acc[j][nt] = vec4{T(0), T(0), T(0), T(0)};
 
-  floatx4 xr[XPT];
+  unit16 xr[XPT];
   vecT a_cur[KS], a_nxt[KS];
 
 #define LOAD_Q(rbase)                                                              \
@@ -272,20 +304,20 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
     int idx = tid + i * NTHREADS;                                                  \
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
     int64_t row = (rbase) + kr;                                                    \
-    floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};                                       \
-    if (idx < F4 && row < rend) v = *(const floatx4*)(Q + row * ldq + c4 * 4);     \
+    unit16 v = unit16{};                                                           \
+    if (idx < F4 && row < rend) v = *(const unit16*)(Q + row * ldq + c4 * EPU);    \
     xr[i] = v;                                                                     \
   }
 #define STORE_Q(buf)                                                               \
   _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
     int idx = tid + i * NTHREADS;                                                  \
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
-    if (idx < F4) *(floatx4*)((buf) + kr * LD + c4 * 4) = xr[i];                   \
+    if (idx < F4) *(unit16*)((buf) + kr * LD + c4 * EPU) = xr[i];                  \
   }
 #define LOAD_A(dst, rbase)                                                         \
   _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                 \
     int64_t row = min((rbase) + s * 4 + g, rows_total - 1);                        \
-    const float* p = A + row * lda;                                                \
+    const T* p = A + row * lda;                                                \
     if (VEC) {                                                                     \
       dst[s] = *(const vecT*)(p + col[0]);                                         \
     } else {                                                                       \
@@ -293,8 +325,8 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
     }                                                                              \
   }
 
-  float* buf0 = lds;
-  float* buf1 = lds + KC * LD;
+  T* buf0 = lds;
+  T* buf1 = lds + KC * LD;
 
   if (nchunks > 0) {
     LOAD_Q(rbeg);
@@ -308,8 +340,8 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
   // freshly issued loads of the next chunk in the middle of the MFMA stream.
 #pragma nounroll
   for (int c = 0; c < nchunks; ++c) {
-    const float* cur = (c & 1) ? buf1 : buf0;
-    float* nxt = (c & 1) ? buf0 : buf1;
+    const T* cur = (c & 1) ? buf1 : buf0;
+    T* nxt = (c & 1) ? buf0 : buf1;
     const bool more = (c + 1 < nchunks);
 #pragma unroll
     for (int s = 0; s < KS; ++s) a_cur[s] = opaque(a_nxt[s]);   // wait for the prefetched rows here
@@ -320,14 +352,14 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
     // KS steps of 4 rows each; the panel values of step s+1 are read from LDS while the MFMAs of
     // step s run (register double buffer bq).
     {
-      float bq[2][NT];
-      const float* bbase = cur + g * LD + r;
+      T bq[2][NT];
+      const T* bbase = cur + g * LD + r;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) bq[0][nt] = bbase[nt * 16];
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         if (s + 1 < KS) {
-          const float* brow = bbase + (s + 1) * 4 * LD;
+          const T* brow = bbase + (s + 1) * 4 * LD;
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) bq[(s + 1) & 1][nt] = brow[nt * 16];
         }
@@ -345,14 +377,14 @@ k_gemm_at(const float* __restrict__ A, int64_t lda, int64_t rows_total, int n,
 #undef STORE_Q
 #undef LOAD_A
 
-  float* Zo = Zpart + (int64_t)blockIdx.y * split_stride;
+  T* Zo = Zpart + (int64_t)blockIdx.y * split_stride;
 #pragma unroll
   for (int j = 0; j < MT; ++j)
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-      int zr = cw + MT * (4 * g + v) + j;
+      int zr = cw + MT * El<T>::acc_row(g, v) + j;
       if (zr < n) {
-        float* zp = Zo + (int64_t)zr * ldz + r;
+        T* zp = Zo + (int64_t)zr * ldz + r;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) zp[nt * 16] = acc[j][nt][v];
       }
@@ -376,47 +408,49 @@ __global__ void k_reduce_splits(const T* __restrict__ part, int nsplit, int64_t 
 
 // In-place first level of a long split sum: slot g*fan <- sum of the slots [g*fan, min((g+1)*fan, nsplit))
 // in slot order (blockIdx.y = g).  Each thread only touches its own element of every slot.
-__global__ void k_reduce_groups_inplace(float* __restrict__ part, int nsplit, int fan, int64_t split_stride,
+template <typename T>
+__global__ void k_reduce_groups_inplace(T* __restrict__ part, int nsplit, int fan, int64_t split_stride,
                                         int64_t count) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= count) return;                 // count <= split_stride elements of every slot take part
   const int s0 = blockIdx.y * fan, s1 = min(nsplit, s0 + fan);
-  float* p = part + idx;
-  float s = p[(int64_t)s0 * split_stride];
+  T* p = part + idx;
+  T s = p[(int64_t)s0 * split_stride];
   for (int i = s0 + 1; i < s1; ++i) s += p[(int64_t)i * split_stride];
   p[(int64_t)s0 * split_stride] = s;
 }
 
-__global__ void k_pad_panel(const float* __restrict__ src, int64_t rows, int l, float* __restrict__ dst,
-                            int Lp) {
+template <typename T>
+__global__ void k_pad_panel(const T* __restrict__ src, int64_t rows, int l, T* __restrict__ dst, int Lp) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= rows * Lp) return;
   int64_t row = idx / Lp;
   int col = (int)(idx - row * Lp);
-  dst[idx] = col < l ? src[row * l + col] : 0.f;
+  dst[idx] = col < l ? src[row * l + col] : T(0);
 }
 
-__global__ void k_unpad_panel(const float* __restrict__ src, int64_t rows, int Lp, int l,
-                              float* __restrict__ dst, int accumulate) {
+template <typename T>
+__global__ void k_unpad_panel(const T* __restrict__ src, int64_t rows, int Lp, int l, T* __restrict__ dst,
+                              int accumulate) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= rows * l) return;
   int64_t row = idx / l;
   int col = (int)(idx - row * l);
-  float v = src[row * Lp + col];
+  T v = src[row * Lp + col];
   dst[idx] = accumulate ? dst[idx] + v : v;
 }
 
 // dst[c][row] = src[row][c], c < l; 32x32 tiles through LDS.
-__global__ void k_transpose_panel(const float* __restrict__ src, int64_t rows, int Lp, int l,
-                                  float* __restrict__ dst) {
-  __shared__ float tile[32][33];
+template <typename T>
+__global__ void k_transpose_panel(const T* __restrict__ src, int64_t rows, int Lp, int l, T* __restrict__ dst) {
+  __shared__ T tile[32][33];
   int64_t r0 = (int64_t)blockIdx.x * 32;
   int c0 = blockIdx.y * 32;
   int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 256 threads: ty = 0..7
   for (int i = ty; i < 32; i += 8) {
     int64_t row = r0 + i;
     int col = c0 + tx;
-    tile[i][tx] = (row < rows && col < Lp) ? src[row * Lp + col] : 0.f;
+    tile[i][tx] = (row < rows && col < Lp) ? src[row * Lp + col] : T(0);
   }
   __syncthreads();
   for (int i = ty; i < 32; i += 8) {
@@ -475,9 +509,11 @@ static int pick_splits(int64_t tiles, int slots, int64_t units, double out_over_
 struct NGroups {
   int groups, nt;   // column groups per launch sequence, n-tiles per group
 };
-static NGroups column_groups(int Lp) {
+// esz = element size: fp64 accumulators take twice the registers, so a launch keeps 8 n-tiles at most.
+static int max_nt(int esz) { return esz == 8 ? 8 : kMaxNT; }
+static NGroups column_groups(int Lp, int esz) {
   int nt_total = Lp / 16;
-  int groups = (nt_total + kMaxNT - 1) / kMaxNT;
+  int groups = (nt_total + max_nt(esz) - 1) / max_nt(esz);
   int nt = (nt_total + groups - 1) / groups;
   return {groups, nt};
 }
@@ -487,7 +523,8 @@ struct AnCfg {
   int mt, waves, kc;
 };
 // Tile shapes picked from sweeps on MI355X (see the launch templates below, which must agree).
-static AnCfg an_cfg(int nt) {
+static AnCfg an_cfg(int nt, int esz) {
+  if (esz == 8) return {2, 4, 32};
   if (nt <= 8) return {2, 4, 64};
   return {2, 4, 32};
 }
@@ -499,14 +536,14 @@ struct AnPlan {
 };
 // See AnShape.  Short contractions (the R^-1 applies and lifts: fewer than 16 chunks) and launches
 // with very many tiles keep one whole tile per workgroup.
-static AnPlan an_plan(int64_t rows, int64_t K, int nt) {
-  AnCfg c = an_cfg(nt);
+static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
+  AnCfg c = an_cfg(nt, esz);
   AnPlan p;
   p.tile_rows = c.waves * c.mt * 16;
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
-  const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * 4;
-  const int wg_regs = nt <= 14 ? 2 : 1;        // workgroups per CU that the register file allows
+  const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * esz;
+  const int wg_regs = esz == 8 ? (nt <= 4 ? 2 : 1) : (nt <= 14 ? 2 : 1);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
   const char* e = getenv("BRSVD_AN_SPLITS");
@@ -532,18 +569,18 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt) {
   return p;
 }
 
-uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp) {
-  NGroups ng = column_groups(Lp);
-  AnPlan p = an_plan(rows, K, ng.nt);
-  return (uint64_t)p.nsplit * rows * Lp * sizeof(float);
+uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp, int esz) {
+  NGroups ng = column_groups(Lp, esz);
+  AnPlan p = an_plan(rows, K, ng.nt, esz);
+  return (uint64_t)p.nsplit * rows * Lp * esz;
 }
 
-template <int NT, int MT, int WAVES, int KC, bool VEC>
-static int launch_an_inst(const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
-                          float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
-                          const AnPlan& p, hipStream_t stream) {
-  auto kern = k_gemm_an<NT, MT, WAVES, KC, VEC>;
-  constexpr int lds_bytes = 2 * KC * (NT * 16 + 4) * (int)sizeof(float);
+template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
+static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y, int64_t ldy,
+                          int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                          hipStream_t stream) {
+  auto kern = k_gemm_an<T, NT, MT, WAVES, KC, VEC>;
+  constexpr int lds_bytes = 2 * KC * (NT * 16 + 4) * (int)sizeof(T);
   static bool attr_set = false;
   if (!attr_set) {
     BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -556,18 +593,22 @@ static int launch_an_inst(const float* A, int64_t lda, int rows, int K, const fl
   return BRSVD_OK;
 }
 
-template <int NT>
-static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, const float* X, int ldx,
-                        float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
-                        const AnPlan& p, hipStream_t stream) {
-  constexpr int MT = 2;
-  constexpr int WAVES = 4;
-  constexpr int KC = NT <= 8 ? 64 : 32;
-  if (vec)
-    return launch_an_inst<NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
-                                                   stream);
-  return launch_an_inst<NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
-                                                  stream);
+template <typename T, int NT>
+static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
+                        int64_t ldy, int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                        hipStream_t stream) {
+  if constexpr (sizeof(T) == 8 && NT > 8) {
+    return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
+  } else {
+    constexpr int MT = 2;
+    constexpr int WAVES = 4;
+    constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
+    if (vec)
+      return launch_an_inst<T, NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
+                                                        split_stride, p, stream);
+    return launch_an_inst<T, NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
+                                                       split_stride, p, stream);
+  }
 }
 
 #define BRSVD_NT_SWITCH(nt, CALL)                                                      \
@@ -581,10 +622,11 @@ static int launch_an_nt(bool vec, const float* A, int64_t lda, int rows, int K, 
     default: return BRSVD_ERR_ARG;                                                     \
   }
 
-static int launch_an(int nt, bool vec, const float* A, int64_t lda, int rows, int K, const float* X,
-                     int ldx, float* Y, int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride,
-                     const AnPlan& p, hipStream_t stream) {
-#define CALL(N) launch_an_nt<N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream)
+template <typename T>
+static int launch_an(int nt, bool vec, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
+                     int64_t ldy, int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                     hipStream_t stream) {
+#define CALL(N) launch_an_nt<T, N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream)
   BRSVD_NT_SWITCH(nt, CALL)
 #undef CALL
 }
@@ -593,61 +635,79 @@ static int launch_an(int nt, bool vec, const float* A, int64_t lda, int rows, in
 // two levels, groups of kReduceFan consecutive splits first, so that no thread walks thousands of
 // slots serially.  Either way the association is fixed by the plan, not by timing.
 constexpr int kReduceFan = 16;
-static int reduce_f32(float* part, int nsplit, int64_t split_stride, int64_t rows, int ncols,
-                      int64_t ldi, float* out, int64_t ldo, bool accumulate, hipStream_t stream) {
+template <typename T>
+static int reduce_splits(T* part, int nsplit, int64_t split_stride, int64_t rows, int ncols, int64_t ldi, T* out,
+                         int64_t ldo, bool accumulate, hipStream_t stream) {
   int64_t total = rows * ncols;
   if (total == 0) return BRSVD_OK;
   if (nsplit > 2 * kReduceFan) {
     const int groups = (int)ceil_div(nsplit, kReduceFan);
     const int64_t count = rows * ldi;       // the rows being reduced, all ldi columns of each
-    hipLaunchKernelGGL(k_reduce_groups_inplace, dim3((unsigned)ceil_div(count, 256), groups), dim3(256), 0, stream,
+    hipLaunchKernelGGL(k_reduce_groups_inplace<T>, dim3((unsigned)ceil_div(count, 256), groups), dim3(256), 0, stream,
                        part, nsplit, kReduceFan, split_stride, count);
     nsplit = groups;
     split_stride *= kReduceFan;
   }
-  hipLaunchKernelGGL(k_reduce_splits<float>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+  hipLaunchKernelGGL(k_reduce_splits<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
                      part, nsplit, split_stride, rows, ncols, ldi, out, ldo, accumulate ? 1 : 0);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
-int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp, float* Y,
-            int64_t ldy, int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream,
-            const KernelEvents* ev) {
+// Vector loads of four consecutive elements of A need rows aligned to four elements and a length
+// that is a multiple of four (the vector path clamps a lane's group to the last aligned one).
+template <typename T>
+static bool vec_ok(const T* A, int64_t lda, int64_t len) {
+  return (lda % 4 == 0) && (((uintptr_t)A) % (4 * sizeof(T)) == 0) && len >= 4 && (len % 4 == 0);
+}
+
+template <typename T>
+static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* X, int Lp, T* Y, int64_t ldy,
+                     int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
   if (rows <= 0 || K <= 0 || Lp <= 0 || Lp % 16 || ncols <= 0 || ncols > Lp) return BRSVD_ERR_ARG;
   if (rows > INT32_MAX || K > INT32_MAX) return BRSVD_ERR_ARG;
-  NGroups ng = column_groups(Lp);
-  AnPlan p = an_plan(rows, K, ng.nt);
-  const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && K >= 4 && (K % 4 == 0);
-  if (scratch_bytes < (uint64_t)p.nsplit * rows * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
+  constexpr int esz = (int)sizeof(T);
+  NGroups ng = column_groups(Lp, esz);
+  AnPlan p = an_plan(rows, K, ng.nt, esz);
+  const bool vec = vec_ok(A, lda, K);
+  if (scratch_bytes < (uint64_t)p.nsplit * rows * Lp * esz) return BRSVD_ERR_BUDGET;
   if (verbose())
-    fprintf(stderr, "[brsvd] gemm_an rows=%ld K=%ld Lp=%d: %d whole tiles + %d leftover tiles x %d splits + tail of %d chunks "
-            "(%d per workgroup), %d chunks per tile, %d workgroups, vec=%d\n", (long)rows, (long)K, Lp, p.sh.whole, p.sh.lt,
-            p.sh.f, p.sh.x, p.sh.j, p.sh.C, p.wgs, (int)vec);
-  float* part = (float*)scratch;
+    fprintf(stderr, "[brsvd] gemm_an f%d rows=%ld K=%ld Lp=%d: %d whole tiles + %d leftover tiles x %d splits + tail of %d "
+            "chunks (%d per workgroup), %d chunks per tile, %d workgroups, vec=%d\n", esz * 8, (long)rows, (long)K, Lp,
+            p.sh.whole, p.sh.lt, p.sh.f, p.sh.x, p.sh.j, p.sh.C, p.wgs, (int)vec);
+  T* part = (T*)scratch;
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
     int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
     if (nt <= 0) break;
     int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group (may be <= 0)
-    BRSVD_TRY(launch_an(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr, Lp,
-                        rows * Lp, p, stream));
+    BRSVD_TRY(launch_an<T>(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr,
+                           Lp, rows * Lp, p, stream));
   }
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
   if (p.nsplit > 0) {
     // rows of the leftover tiles: their partial panels, in split order
     const int64_t r0 = (int64_t)p.sh.whole * p.tile_rows;
-    BRSVD_TRY(reduce_f32(part + r0 * Lp, p.nsplit, rows * Lp, rows - r0, ncols, Lp, Y + r0 * ldy, ldy, false, stream));
+    BRSVD_TRY(reduce_splits<T>(part + r0 * Lp, p.nsplit, rows * Lp, rows - r0, ncols, Lp, Y + r0 * ldy, ldy, false,
+                               stream));
   }
   return BRSVD_OK;
+}
+int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp, float* Y, int64_t ldy,
+            int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
+  return gemm_an_t<float>(A, lda, rows, K, X, Lp, Y, ldy, ncols, scratch, scratch_bytes, stream, ev);
+}
+int gemm_an(const double* A, int64_t lda, int64_t rows, int64_t K, const double* X, int Lp, double* Y, int64_t ldy,
+            int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
+  return gemm_an_t<double>(A, lda, rows, K, X, Lp, Y, ldy, ncols, scratch, scratch_bytes, stream, ev);
 }
 
 // ---- gemm_at ----
 struct AtPlan {
   int mt, waves, col_tiles, nblocks, sub, rows_per_sub, nsplit;
 };
-static int at_mt(int nt) { return nt <= 8 ? 4 : 2; }
+static int at_mt(int nt, int esz) { return (esz == 4 && nt <= 8) ? 4 : 2; }
 constexpr int kAtWaves = 8;
 constexpr int kAtKC = 32;
 // Narrow A (tall-skinny inputs, n of a few hundred at most) with a narrow panel: workgroups of two
@@ -656,18 +716,23 @@ constexpr int kAtKC = 32;
 constexpr int kAtNarrowWaves = 2;
 constexpr int kAtNarrowMaxNT = 4;
 constexpr int kAtNarrowMaxN = 256;
-static int at_waves(int64_t n, int nt) { return (nt <= kAtNarrowMaxNT && n <= kAtNarrowMaxN) ? kAtNarrowWaves : kAtWaves; }
+static int at_waves(int64_t n, int nt, int esz) {
+  return (esz == 4 && nt <= kAtNarrowMaxNT && n <= kAtNarrowMaxN) ? kAtNarrowWaves : kAtWaves;
+}
+static int at_ld(int nt, int esz) {
+  const int bm = esz == 8 ? 32 : 64;
+  return nt * 16 + ((16 - (nt * 16) % bm) + bm) % bm;
+}
 
-static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
+static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows, int esz) {
   AtPlan p;
-  p.mt = at_mt(nt);
-  p.waves = at_waves(n, nt);
+  p.mt = at_mt(nt, esz);
+  p.waves = at_waves(n, nt, esz);
   p.col_tiles = (int)ceil_div(n, p.waves * p.mt * 16);
   if (block_rows <= 0 || block_rows > rows) block_rows = rows;
   p.nblocks = (int)ceil_div(rows, block_rows);
   const int max_sub = (int)ceil_div(block_rows, kAtKC);
-  const int ld = nt * 16 + ((16 - (nt * 16) % 64) + 64) % 64;
-  const int lds_bytes = 2 * kAtKC * ld * 4;
+  const int lds_bytes = 2 * kAtKC * at_ld(nt, esz) * esz;
   // one partial panel (n x Lp) per split, against block_rows x n of A read per block
   const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, p.waves == kAtWaves ? 1 : 8), max_sub,
                                (double)(nt * 16) / (double)block_rows, traffic_weight(nt), "BRSVD_AT_SPLITS");
@@ -679,19 +744,19 @@ static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows) {
   return p;
 }
 
-uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows) {
-  NGroups ng = column_groups(Lp);
-  AtPlan p = at_plan(rows, n, ng.nt, block_rows);
-  return (uint64_t)p.nsplit * n * Lp * sizeof(float);
+uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_rows, int esz) {
+  NGroups ng = column_groups(Lp, esz);
+  AtPlan p = at_plan(rows, n, ng.nt, block_rows, esz);
+  return (uint64_t)p.nsplit * n * Lp * esz;
 }
 
-template <int NT, int MT, int WAVES, bool VEC>
-static int launch_at_inst(const float* A, int64_t lda, int64_t rows, int n, const float* Q, int ldq,
-                          float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
-                          hipStream_t stream) {
-  auto kern = k_gemm_at<NT, MT, WAVES, kAtKC, VEC>;
-  constexpr int LD = NT * 16 + ((16 - (NT * 16) % 64) + 64) % 64;
-  constexpr int lds_bytes = 2 * kAtKC * LD * (int)sizeof(float);
+template <typename T, int NT, int MT, int WAVES, bool VEC>
+static int launch_at_inst(const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp, int ldz,
+                          int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
+  auto kern = k_gemm_at<T, NT, MT, WAVES, kAtKC, VEC>;
+  constexpr int BM = El<T>::kBankMod;
+  constexpr int LD = NT * 16 + ((16 - (NT * 16) % BM) + BM) % BM;
+  constexpr int lds_bytes = 2 * kAtKC * LD * (int)sizeof(T);
   static bool attr_set = false;
   if (!attr_set) {
     BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -705,81 +770,117 @@ static int launch_at_inst(const float* A, int64_t lda, int64_t rows, int n, cons
   return BRSVD_OK;
 }
 
-template <int NT>
-static int launch_at_nt(bool vec, const float* A, int64_t lda, int64_t rows, int n, const float* Q, int ldq,
-                        float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
-                        hipStream_t stream) {
-  constexpr int MT = NT <= 8 ? 4 : 2;
-  if constexpr (NT <= kAtNarrowMaxNT) {
-    if (p.waves == kAtNarrowWaves) {
+template <typename T, int NT>
+static int launch_at_nt(bool vec, const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
+                        int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
+  if constexpr (sizeof(T) == 8) {
+    if constexpr (NT > 8) {
+      return BRSVD_ERR_ARG;
+    } else {
       if (vec)
-        return launch_at_inst<NT, MT, kAtNarrowWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
-                                                            block_rows, p, stream);
-      return launch_at_inst<NT, MT, kAtNarrowWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
-                                                           block_rows, p, stream);
+        return launch_at_inst<T, NT, 2, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                        stream);
+      return launch_at_inst<T, NT, 2, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                       stream);
     }
+  } else {
+    constexpr int MT = NT <= 8 ? 4 : 2;
+    if constexpr (NT <= kAtNarrowMaxNT) {
+      if (p.waves == kAtNarrowWaves) {
+        if (vec)
+          return launch_at_inst<T, NT, MT, kAtNarrowWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
+                                                                 block_rows, p, stream);
+        return launch_at_inst<T, NT, MT, kAtNarrowWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
+                                                                block_rows, p, stream);
+      }
+    }
+    if (vec)
+      return launch_at_inst<T, NT, MT, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                       stream);
+    return launch_at_inst<T, NT, MT, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                      stream);
   }
-  if (vec)
-    return launch_at_inst<NT, MT, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                  stream);
-  return launch_at_inst<NT, MT, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                 stream);
 }
 
-static int launch_at(int nt, bool vec, const float* A, int64_t lda, int64_t rows, int n, const float* Q,
-                     int ldq, float* Zp, int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p,
-                     hipStream_t stream) {
-#define CALL(N) launch_at_nt<N>(vec, A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream)
+template <typename T>
+static int launch_at(int nt, bool vec, const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
+                     int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
+#define CALL(N) launch_at_nt<T, N>(vec, A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream)
   BRSVD_NT_SWITCH(nt, CALL)
 #undef CALL
 }
 
-int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp, float* Z,
-            bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream,
-            const KernelEvents* ev) {
+template <typename T>
+static int gemm_at_t(const T* A, int64_t lda, int64_t rows, int64_t n, const T* Q, int Lp, T* Z, bool accumulate,
+                     int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream,
+                     const KernelEvents* ev) {
   if (rows <= 0 || n <= 0 || Lp <= 0 || Lp % 16) return BRSVD_ERR_ARG;
   if (n > INT32_MAX) return BRSVD_ERR_ARG;
   if (block_rows <= 0 || block_rows > rows) block_rows = rows;
-  NGroups ng = column_groups(Lp);
-  AtPlan p = at_plan(rows, n, ng.nt, block_rows);
+  constexpr int esz = (int)sizeof(T);
+  NGroups ng = column_groups(Lp, esz);
+  AtPlan p = at_plan(rows, n, ng.nt, block_rows, esz);
   if (p.nsplit > 65535) return BRSVD_ERR_ARG;
-  if (scratch_bytes < (uint64_t)p.nsplit * n * Lp * sizeof(float)) return BRSVD_ERR_BUDGET;
-  const bool vec = (lda % 4 == 0) && (((uintptr_t)A) % 16 == 0) && (n % 4 == 0) && n >= 4;
-  float* part = (float*)scratch;
+  if (scratch_bytes < (uint64_t)p.nsplit * n * Lp * esz) return BRSVD_ERR_BUDGET;
+  const bool vec = vec_ok(A, lda, n);
+  T* part = (T*)scratch;
   if (verbose())
-    fprintf(stderr, "[brsvd] gemm_at rows=%ld n=%ld Lp=%d: %d col tiles (%d waves) x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
-            (long)rows, (long)n, Lp, p.col_tiles, p.waves, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
+    fprintf(stderr, "[brsvd] gemm_at f%d rows=%ld n=%ld Lp=%d: %d col tiles (%d waves) x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
+            esz * 8, (long)rows, (long)n, Lp, p.col_tiles, p.waves, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
     int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
     if (nt <= 0) break;
-    BRSVD_TRY(launch_at(nt, vec, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
+    BRSVD_TRY(launch_at<T>(nt, vec, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
   }
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
-  return reduce_f32(part, p.nsplit, n * Lp, n, Lp, Lp, Z, Lp, accumulate, stream);
+  return reduce_splits<T>(part, p.nsplit, n * Lp, n, Lp, Lp, Z, Lp, accumulate, stream);
+}
+int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp, float* Z, bool accumulate,
+            int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
+  return gemm_at_t<float>(A, lda, rows, n, Q, Lp, Z, accumulate, block_rows, scratch, scratch_bytes, stream, ev);
+}
+int gemm_at(const double* A, int64_t lda, int64_t rows, int64_t n, const double* Q, int Lp, double* Z, bool accumulate,
+            int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
+  return gemm_at_t<double>(A, lda, rows, n, Q, Lp, Z, accumulate, block_rows, scratch, scratch_bytes, stream, ev);
 }
 
-int pad_panel(const float* src, int64_t rows, int l, float* dst, int Lp, hipStream_t stream) {
+template <typename T>
+static int pad_panel_t(const T* src, int64_t rows, int l, T* dst, int Lp, hipStream_t stream) {
   int64_t total = rows * Lp;
-  hipLaunchKernelGGL(k_pad_panel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, l, dst, Lp);
+  hipLaunchKernelGGL(k_pad_panel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, l, dst, Lp);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
-
-int unpad_panel(const float* src, int64_t rows, int Lp, int l, float* dst, bool accumulate, hipStream_t stream) {
+template <typename T>
+static int unpad_panel_t(const T* src, int64_t rows, int Lp, int l, T* dst, bool accumulate, hipStream_t stream) {
   int64_t total = rows * l;
-  hipLaunchKernelGGL(k_unpad_panel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, Lp, l,
+  hipLaunchKernelGGL(k_unpad_panel<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream, src, rows, Lp, l,
                      dst, accumulate ? 1 : 0);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
-
-int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, hipStream_t stream) {
+template <typename T>
+static int transpose_panel_t(const T* src, int64_t rows, int Lp, int l, T* dst, hipStream_t stream) {
   dim3 grid((unsigned)ceil_div(rows, 32), (unsigned)ceil_div(l, 32));
-  hipLaunchKernelGGL(k_transpose_panel, grid, dim3(256), 0, stream, src, rows, Lp, l, dst);
+  hipLaunchKernelGGL(k_transpose_panel<T>, grid, dim3(256), 0, stream, src, rows, Lp, l, dst);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
+}
+int pad_panel(const float* s, int64_t rows, int l, float* d, int Lp, hipStream_t st) { return pad_panel_t(s, rows, l, d, Lp, st); }
+int pad_panel(const double* s, int64_t rows, int l, double* d, int Lp, hipStream_t st) { return pad_panel_t(s, rows, l, d, Lp, st); }
+int unpad_panel(const float* s, int64_t rows, int Lp, int l, float* d, bool acc, hipStream_t st) {
+  return unpad_panel_t(s, rows, Lp, l, d, acc, st);
+}
+int unpad_panel(const double* s, int64_t rows, int Lp, int l, double* d, bool acc, hipStream_t st) {
+  return unpad_panel_t(s, rows, Lp, l, d, acc, st);
+}
+int transpose_panel(const float* s, int64_t rows, int Lp, int l, float* d, hipStream_t st) {
+  return transpose_panel_t(s, rows, Lp, l, d, st);
+}
+int transpose_panel(const double* s, int64_t rows, int Lp, int l, double* d, hipStream_t st) {
+  return transpose_panel_t(s, rows, Lp, l, d, st);
 }
 
 }  // namespace brsvd
