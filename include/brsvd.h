@@ -192,6 +192,15 @@ int brsvd_gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const fl
 
 uint64_t brsvd_gemm_scratch_bytes(int64_t rows, int64_t n, int32_t l);
 
+/* The same two products in double precision (the precision the paper measures in, Sec. 4), on the
+ * fp64 matrix cores.  Arguments as above with double elements; scratch of at least
+ * brsvd_gemm_scratch_bytes_f64(rows, n, l). */
+int brsvd_gemm_an_f64(const double* A, int64_t lda, int64_t rows, int64_t n, const double* X, int32_t l,
+                      double* Y, void* scratch, uint64_t scratch_bytes, void* stream);
+int brsvd_gemm_at_f64(const double* A, int64_t lda, int64_t rows, int64_t n, const double* Q, int32_t l,
+                      double* Z, int32_t accumulate, void* scratch, uint64_t scratch_bytes, void* stream);
+uint64_t brsvd_gemm_scratch_bytes_f64(int64_t rows, int64_t n, int32_t l);
+
 /* In-place orthonormalisation of a tall panel P (rows x l, rows >= l) -- Alg. 1 step 3.
  * method is BRSVD_ORTH_*.  Optionally returns the l x l upper-triangular factor R (fp64,
  * row-major, DEVICE, may be NULL) with P_in = P_out * R.  Synchronises `stream`.

@@ -55,6 +55,7 @@ class brsvd_stats(C.Structure):
 EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
            "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
+           "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
            "brsvd_orth", "brsvd_small_svd"]
 
 _lib = None
@@ -93,10 +94,14 @@ def lib() -> C.CDLL:
     L.brsvd_gemm_at.argtypes = [vp, i64, i64, i64, vp, i32, vp, i32, vp, u64, vp]
     L.brsvd_gemm_scratch_bytes.argtypes = [i64, i64, i32]
     L.brsvd_gemm_scratch_bytes.restype = u64
+    L.brsvd_gemm_an_f64.argtypes = L.brsvd_gemm_an.argtypes
+    L.brsvd_gemm_at_f64.argtypes = L.brsvd_gemm_at.argtypes
+    L.brsvd_gemm_scratch_bytes_f64.argtypes = [i64, i64, i32]
+    L.brsvd_gemm_scratch_bytes_f64.restype = u64
     L.brsvd_orth.argtypes = [vp, i64, i32, i32, vp, C.POINTER(i32), vp]
     L.brsvd_small_svd.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
     for name in EXPORTS:
-        if name not in ("brsvd_status_string", "brsvd_gemm_scratch_bytes"):
+        if name not in ("brsvd_status_string", "brsvd_gemm_scratch_bytes", "brsvd_gemm_scratch_bytes_f64"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -252,42 +257,48 @@ def brsvd_norm2_power(handle, A, x0, iters, lda=None) -> float:
     return out.value
 
 
-def brsvd_gemm_scratch_bytes(rows, n, l) -> int:
-    return lib().brsvd_gemm_scratch_bytes(rows, n, l)
+def brsvd_gemm_scratch_bytes(rows, n, l, f64=False) -> int:
+    L = lib()
+    return (L.brsvd_gemm_scratch_bytes_f64 if f64 else L.brsvd_gemm_scratch_bytes)(rows, n, l)
 
 
-def _scratch(rows, n, l, device):
+def _scratch(rows, n, l, device, f64=False):
     import torch
-    nbytes = brsvd_gemm_scratch_bytes(rows, n, l)
+    nbytes = brsvd_gemm_scratch_bytes(rows, n, l, f64)
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device), nbytes
 
 
 def brsvd_gemm_an(A, X, Y=None, rows=None, lda=None, stream=None):
-    """Y = A[:rows] @ X on the HIP path.  A (rows, n) fp32 CUDA (row stride lda), X (n, l)."""
+    """Y = A[:rows] @ X on the HIP path.  A (rows, n) CUDA (row stride lda), X (n, l); fp32, or fp64 when
+    A is a float64 tensor (brsvd_gemm_an_f64)."""
     import torch
     rows = A.shape[0] if rows is None else rows
     n = A.shape[1]
     l = X.shape[1]
+    f64 = A.dtype == torch.float64
+    dt = A.dtype
     lda = A.stride(0) if lda is None else lda
-    Y = torch.empty(rows, l, device=X.device) if Y is None else Y
-    scr, nbytes = _scratch(rows, n, l, X.device)
-    _check(lib().brsvd_gemm_an(A.data_ptr(), lda, rows, n, _dev(X, torch.float32, "X"), l,
-                               _dev(Y, torch.float32, "Y"), scr.data_ptr(), nbytes, _stream_ptr(stream)),
-           "brsvd_gemm_an")
+    Y = torch.empty(rows, l, device=X.device, dtype=dt) if Y is None else Y
+    scr, nbytes = _scratch(rows, n, l, X.device, f64)
+    fn = lib().brsvd_gemm_an_f64 if f64 else lib().brsvd_gemm_an
+    _check(fn(A.data_ptr(), lda, rows, n, _dev(X, dt, "X"), l, _dev(Y, dt, "Y"), scr.data_ptr(), nbytes,
+              _stream_ptr(stream)), "brsvd_gemm_an")
     return Y
 
 
 def brsvd_gemm_at(A, Q, Z=None, accumulate=False, lda=None, stream=None):
-    """Z (+)= A^T @ Q on the HIP path.  A (rows, n), Q (rows, l), Z (n, l)."""
+    """Z (+)= A^T @ Q on the HIP path.  A (rows, n), Q (rows, l), Z (n, l); fp32 or fp64 by A's dtype."""
     import torch
     rows, n = A.shape
     l = Q.shape[1]
+    f64 = A.dtype == torch.float64
+    dt = A.dtype
     lda = A.stride(0) if lda is None else lda
-    Z = torch.zeros(n, l, device=Q.device) if Z is None else Z
-    scr, nbytes = _scratch(rows, n, l, Q.device)
-    _check(lib().brsvd_gemm_at(A.data_ptr(), lda, rows, n, _dev(Q, torch.float32, "Q"), l,
-                               _dev(Z, torch.float32, "Z"), 1 if accumulate else 0, scr.data_ptr(), nbytes,
-                               _stream_ptr(stream)), "brsvd_gemm_at")
+    Z = torch.zeros(n, l, device=Q.device, dtype=dt) if Z is None else Z
+    scr, nbytes = _scratch(rows, n, l, Q.device, f64)
+    fn = lib().brsvd_gemm_at_f64 if f64 else lib().brsvd_gemm_at
+    _check(fn(A.data_ptr(), lda, rows, n, _dev(Q, dt, "Q"), l, _dev(Z, dt, "Z"), 1 if accumulate else 0,
+              scr.data_ptr(), nbytes, _stream_ptr(stream)), "brsvd_gemm_at")
     return Z
 
 

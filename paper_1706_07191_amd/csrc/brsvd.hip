@@ -581,6 +581,45 @@ int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, fl
   return run_sync_with(h, fallbacks, [&](int method) { return enqueue_brsvd(h, A, lda, Omega, U, S, Vt, method); });
 }
 
+// ---- step-level GEMM calls (both element types) --------------------------------------------------
+uint64_t step_gemm_scratch_bytes(int64_t rows, int64_t n, int l, int esz) {
+  if (rows < 1 || n < 1 || l < 1 || l > kMaxL) return 0;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * esz);
+  uint64_t part = std::max(gemm_an_scratch_bytes(rows, n, Lp, esz), gemm_at_scratch_bytes(rows, n, Lp, rows, esz));
+  return 2 * panel + align_up(part);
+}
+
+template <typename T>
+int step_gemm_an(const T* A, int64_t lda, int64_t rows, int64_t n, const T* X, int l, T* Y, void* scratch,
+                 uint64_t scratch_bytes, void* stream) {
+  if (!A || !X || !Y || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
+  if (!scratch || scratch_bytes < step_gemm_scratch_bytes(rows, n, l, (int)sizeof(T))) return BRSVD_ERR_BUDGET;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * sizeof(T));
+  T* Xp = (T*)scratch;
+  char* part = (char*)scratch + 2 * panel;
+  hipStream_t s = (hipStream_t)stream;
+  BRSVD_TRY(pad_panel(X, n, l, Xp, Lp, s));
+  return gemm_an(A, lda, rows, n, Xp, Lp, Y, l, l, part, scratch_bytes - 2 * panel, s);
+}
+
+template <typename T>
+int step_gemm_at(const T* A, int64_t lda, int64_t rows, int64_t n, const T* Q, int l, T* Z, int accumulate,
+                 void* scratch, uint64_t scratch_bytes, void* stream) {
+  if (!A || !Q || !Z || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
+  if (!scratch || scratch_bytes < step_gemm_scratch_bytes(rows, n, l, (int)sizeof(T))) return BRSVD_ERR_BUDGET;
+  const int Lp = padded_l(l);
+  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * sizeof(T));
+  T* Qp = (T*)scratch;
+  T* Zp = (T*)((char*)scratch + panel);
+  char* part = (char*)scratch + 2 * panel;
+  hipStream_t s = (hipStream_t)stream;
+  BRSVD_TRY(pad_panel(Q, rows, l, Qp, Lp, s));
+  BRSVD_TRY(gemm_at(A, lda, rows, n, Qp, Lp, Zp, false, rows, part, scratch_bytes - 2 * panel, s));
+  return unpad_panel(Zp, n, Lp, l, Z, accumulate != 0, s);
+}
+
 }  // namespace
 
 // ================================================================================================
@@ -856,40 +895,24 @@ const char* brsvd_status_string(int status) {
 
 // ---- step-level entry points --------------------------------------------------------------------
 
-uint64_t brsvd_gemm_scratch_bytes(int64_t rows, int64_t n, int32_t l) {
-  if (rows < 1 || n < 1 || l < 1 || l > kMaxL) return 0;
-  const int Lp = padded_l(l);
-  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
-  uint64_t part = std::max(gemm_an_scratch_bytes(rows, n, Lp), gemm_at_scratch_bytes(rows, n, Lp, rows));
-  return 2 * panel + align_up(part);
-}
+uint64_t brsvd_gemm_scratch_bytes(int64_t rows, int64_t n, int32_t l) { return step_gemm_scratch_bytes(rows, n, l, 4); }
+uint64_t brsvd_gemm_scratch_bytes_f64(int64_t rows, int64_t n, int32_t l) { return step_gemm_scratch_bytes(rows, n, l, 8); }
 
 int brsvd_gemm_an(const float* A, int64_t lda, int64_t rows, int64_t n, const float* X, int32_t l, float* Y,
                   void* scratch, uint64_t scratch_bytes, void* stream) {
-  if (!A || !X || !Y || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
-  if (!scratch || scratch_bytes < brsvd_gemm_scratch_bytes(rows, n, l)) return BRSVD_ERR_BUDGET;
-  const int Lp = padded_l(l);
-  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
-  float* Xp = (float*)scratch;
-  char* part = (char*)scratch + 2 * panel;
-  hipStream_t s = (hipStream_t)stream;
-  BRSVD_TRY(pad_panel(X, n, l, Xp, Lp, s));
-  return gemm_an(A, lda, rows, n, Xp, Lp, Y, l, l, part, scratch_bytes - 2 * panel, s);
+  return step_gemm_an<float>(A, lda, rows, n, X, l, Y, scratch, scratch_bytes, stream);
 }
-
+int brsvd_gemm_an_f64(const double* A, int64_t lda, int64_t rows, int64_t n, const double* X, int32_t l, double* Y,
+                      void* scratch, uint64_t scratch_bytes, void* stream) {
+  return step_gemm_an<double>(A, lda, rows, n, X, l, Y, scratch, scratch_bytes, stream);
+}
 int brsvd_gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int32_t l, float* Z,
                   int32_t accumulate, void* scratch, uint64_t scratch_bytes, void* stream) {
-  if (!A || !Q || !Z || rows < 1 || n < 1 || l < 1 || l > kMaxL || lda < n) return BRSVD_ERR_ARG;
-  if (!scratch || scratch_bytes < brsvd_gemm_scratch_bytes(rows, n, l)) return BRSVD_ERR_BUDGET;
-  const int Lp = padded_l(l);
-  const uint64_t panel = align_up((uint64_t)std::max(rows, n) * Lp * 4);
-  float* Qp = (float*)scratch;
-  float* Zp = (float*)((char*)scratch + panel);
-  char* part = (char*)scratch + 2 * panel;
-  hipStream_t s = (hipStream_t)stream;
-  BRSVD_TRY(pad_panel(Q, rows, l, Qp, Lp, s));
-  BRSVD_TRY(gemm_at(A, lda, rows, n, Qp, Lp, Zp, false, rows, part, scratch_bytes - 2 * panel, s));
-  return unpad_panel(Zp, n, Lp, l, Z, accumulate != 0, s);
+  return step_gemm_at<float>(A, lda, rows, n, Q, l, Z, accumulate, scratch, scratch_bytes, stream);
+}
+int brsvd_gemm_at_f64(const double* A, int64_t lda, int64_t rows, int64_t n, const double* Q, int32_t l, double* Z,
+                      int32_t accumulate, void* scratch, uint64_t scratch_bytes, void* stream) {
+  return step_gemm_at<double>(A, lda, rows, n, Q, l, Z, accumulate, scratch, scratch_bytes, stream);
 }
 
 int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int32_t* fallback_taken,

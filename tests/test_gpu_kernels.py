@@ -174,3 +174,34 @@ def test_small_svd_jacobi(l):
     if l <= 30:   # the loop-level twin agrees too
         _, s2, _ = loops.jacobi_svd(R)
         assert np.max(np.abs(S - s2) / s2) < 1e-8            # both Jacobi codes are relatively accurate
+
+
+# ---- the same two products in double precision (fp64 matrix cores) ------------------------------
+
+EPS64 = float(np.finfo(np.float64).eps)
+
+
+@pytest.mark.parametrize("rows,n,l", GEMM_SHAPES)
+def test_gemm_f64_matches_oracle(rows, n, l):
+    """fp64 path against the fp64 oracle: elementwise within 8 sqrt(K) eps64 (|A| |X|), both products,
+    the accumulate flag, and an unaligned view (scalar load path)."""
+    dev = need_gpu()
+    A = synth.gaussian(rows, n, 201, dtype=torch.float64)
+    X = synth.gaussian(n, l, 202, dtype=torch.float64)
+    Q = synth.gaussian(rows, l, 203, dtype=torch.float64)
+    An, Xn, Qn = A.numpy(), X.numpy(), Q.numpy()
+    Y = B.brsvd_gemm_an(A.to(dev), X.to(dev))
+    assert Y.dtype == torch.float64
+    ref = O.a_times(An, Xn, b=128)
+    assert np.all(np.abs(Y.cpu().numpy() - ref) <= 8.0 * np.sqrt(n) * EPS64 * (np.abs(An) @ np.abs(Xn)) + 1e-300)
+    Z = B.brsvd_gemm_at(A.to(dev), Q.to(dev))
+    refz = O.at_times(An, Qn, b=100)
+    bz = 8.0 * np.sqrt(rows) * EPS64 * (np.abs(An.T) @ np.abs(Qn)) + 1e-300
+    assert np.all(np.abs(Z.cpu().numpy() - refz) <= bz)
+    Z2 = B.brsvd_gemm_at(A.to(dev), Q.to(dev), Z=Z.clone(), accumulate=True)
+    assert np.all(np.abs(Z2.cpu().numpy() - 2 * refz) <= 2 * bz)
+    if n > 8:
+        Av = A.to(dev)[:, 1:n - 2]          # odd offset: rows not 32-byte aligned
+        Yv = B.brsvd_gemm_an(Av, X.to(dev)[1:n - 2].contiguous())
+        refv = An[:, 1:n - 2] @ Xn[1:n - 2]
+        assert np.max(np.abs(Yv.cpu().numpy() - refv)) <= 1e-11 * max(1.0, np.max(np.abs(refv)))
