@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_MFMA_F32_TFLOPS = 157.3  # dense fp32 MFMA
+PEAK_MFMA_F64_TFLOPS = 78.6   # dense fp64 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a plain
 # 1 GiB copy (profiles/gemm_thin_C2_hbm_traffic.md).  Counters cannot be read from inside the timed run.
 MEASURED_HBM_TRAFFIC = {"C2:gemm_an": 1.749e9, "C2:gemm_at": 1.909e9}
@@ -37,6 +38,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fused", action="store_true",
                     help="q+1 fused passes over A instead of the 2q+2 separate ones the headline metric is quoted on")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "f64"],
+                    help="f64 runs the same workload in double precision (brsvd_run_f64); the headline metric is f32")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region) so that a rocprofv3 "
                          "--pmc run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE with")
@@ -60,16 +63,23 @@ def main() -> int:
     cfg = synth.CONFIGS[args.config]
     m, n, k, p, q, l = cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, cfg.l
 
+    f64 = args.dtype == "f64"
+    tdt = torch.float64 if f64 else torch.float32
+    esz = 8 if f64 else 4
     A = cfg.make_A(device=dev)
     Om = cfg.make_Omega(device=dev)
+    if f64:
+        A = A.double()
+        Om = Om.double()
     torch.cuda.synchronize()
 
     prm = B.make_params(m, n, k, p, q, row_block=cfg.row_block,
-                        pass_mode=B.BRSVD_PASSES_FUSED if args.fused else B.BRSVD_PASSES_SEPARATE)
+                        pass_mode=B.BRSVD_PASSES_FUSED if args.fused else B.BRSVD_PASSES_SEPARATE,
+                        dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32)
     h = B.brsvd_create(prm)
-    U = torch.empty(m, l, device=dev)
-    S = torch.empty(l, device=dev)
-    Vt = torch.empty(l, n, device=dev)
+    U = torch.empty(m, l, device=dev, dtype=tdt)
+    S = torch.empty(l, device=dev, dtype=tdt)
+    Vt = torch.empty(l, n, device=dev, dtype=tdt)
     for _ in range(args.warmup):
         B.brsvd_run(h, A, Om, U, S, Vt, want_stats=False)
     torch.cuda.synchronize()
@@ -91,7 +101,7 @@ def main() -> int:
     t1 = time.perf_counter()
     sec = (t1 - t0) / args.steps
     passes = q + 1 if args.fused else 2 * q + 2
-    bytes_a = passes * 4.0 * m * n
+    bytes_a = passes * float(esz) * m * n
     gbs = bytes_a / sec / 1e9
 
     # dominant kernel: whichever thin GEMM took longer in total
@@ -103,14 +113,15 @@ def main() -> int:
         kname, kt, kn = "gemm_at", at_t, at_n
     avg = kt / max(kn, 1)
     flops_launch = 2.0 * m * n * l            # algorithmic flops of one launch (device-resident A: all of A)
-    bytes_launch = 4.0 * m * n + 4.0 * (m + n) * l
+    bytes_launch = float(esz) * m * n + float(esz) * (m + n) * l
     ai = flops_launch / bytes_launch
-    ridge = PEAK_MFMA_F32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    traffic = MEASURED_HBM_TRAFFIC.get(f"{args.config}:{kname}")
+    peak_mfma = PEAK_MFMA_F64_TFLOPS if f64 else PEAK_MFMA_F32_TFLOPS
+    ridge = peak_mfma * 1e12 / (PEAK_HBM_GBS * 1e9)
+    traffic = None if f64 else MEASURED_HBM_TRAFFIC.get(f"{args.config}:{kname}")
     if ai >= ridge:
         ach = flops_launch / avg / 1e12
-        roof = {"bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": traffic}
+        roof = {"bound": "mfma", "achieved": ach, "peak": peak_mfma, "unit": "TFLOP/s",
+                "frac": ach / peak_mfma, "traffic": traffic}
     else:
         ach = bytes_launch / avg / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -144,8 +155,8 @@ def main() -> int:
         "metric": "GB/s of A streamed per rank-k BRSVD (seconds per BRSVD in ms_per_step)",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "seconds_per_brsvd": sec, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name} in-core: A fp32 {m}x{n}, k={k}, p={p}, q={q}, row_block={cfg.row_block}, "
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} in-core: A {'fp64' if f64 else 'fp32'} {m}x{n}, k={k}, p={p}, q={q}, row_block={cfg.row_block}, "
                                f"{passes} passes over A" + (" (fused)" if args.fused else ""), "m": m, "n": n, "k": k, "p": p, "q": q,
                    "row_block": cfg.row_block, "a_location": "device"},
         "roofline": roof, "cpu_baseline": cpu, "breakdown_ms": breakdown, "parity": parity,

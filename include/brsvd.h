@@ -43,6 +43,9 @@ enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
  * from which B^T = C^T R^-1 (Y = Q R): q+1 passes -- the paper's "only twice" for q = 1 -- at the
  * price of one skipped re-orthonormalisation per pass (panels of condition up to (s_1/s_l)^2). */
 enum { BRSVD_PASSES_SEPARATE = 0, BRSVD_PASSES_FUSED = 1 };
+/* Element type of A, Omega and the results.  F32: brsvd_run and everything else.  F64 (the precision
+ * the paper measures in, Sec. 4): brsvd_run_f64 only -- the same path on the fp64 matrix cores. */
+enum { BRSVD_DTYPE_F32 = 0, BRSVD_DTYPE_F64 = 1 };
 
 /* Problem statement of Alg. 1 / Alg. 2 (inputs A, k, p, q and the partition), plus where A
  * lives and how much device memory may be used (Sec. 4: the block size is chosen from the
@@ -60,6 +63,8 @@ typedef struct {
   void* compute_stream;         /* hipStream_t for all kernels; NULL = the null stream         */
   void* copy_stream;            /* hipStream_t for host->device block copies (host-resident A);
                                    NULL = the library creates one (default priority)           */
+  int32_t dtype;                /* BRSVD_DTYPE_*                                               */
+  int32_t reserved;             /* must be 0                                                   */
 } brsvd_params;
 
 /* Timings are measured with HIP events recorded on compute_stream (copy_stream for the
@@ -106,6 +111,12 @@ int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out);
  * On error the outputs are unspecified; the handle stays usable and destroyable. */
 int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega,
               float* U, float* S, float* Vt, brsvd_stats* stats);
+
+/* brsvd_run in double precision, for a handle created with dtype == BRSVD_DTYPE_F64: same arguments
+ * with double elements, same pass modes, A in device or pinned host memory, same error behaviour.
+ * bytes_A_streamed counts 8 bytes per element. */
+int brsvd_run_f64(brsvd_handle h, const double* A, int64_t lda, const double* Omega,
+                  double* U, double* S, double* Vt, brsvd_stats* stats);
 
 /* The block-local scheme exactly as Alg. 2 prints it: the power iteration is run inside each block
  * while the block is resident, Y += (A_J A_J^T)^q A_J Omega_j (Sec. 3, Eq. (4) for the order of the

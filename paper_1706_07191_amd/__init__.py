@@ -28,6 +28,8 @@ BRSVD_ORTH_CHOLQR2 = 1
 BRSVD_ORTH_TSQR = 2
 BRSVD_PASSES_SEPARATE = 0
 BRSVD_PASSES_FUSED = 1
+BRSVD_DTYPE_F32 = 0
+BRSVD_DTYPE_F64 = 1
 
 
 class brsvd_params(C.Structure):
@@ -35,7 +37,8 @@ class brsvd_params(C.Structure):
                 ("k", C.c_int32), ("p", C.c_int32), ("q", C.c_int32), ("a_location", C.c_int32),
                 ("row_block", C.c_int64), ("device_budget_bytes", C.c_uint64),
                 ("orth_method", C.c_int32), ("pass_mode", C.c_int32),
-                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
+                ("dtype", C.c_int32), ("reserved", C.c_int32)]
 
 
 class brsvd_stats(C.Structure):
@@ -52,7 +55,7 @@ class brsvd_stats(C.Structure):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
-EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
+EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
            "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
@@ -80,6 +83,7 @@ def lib() -> C.CDLL:
     L.brsvd_workspace_bytes.argtypes = [C.POINTER(brsvd_params), C.POINTER(u64)]
     L.brsvd_create.argtypes = [C.POINTER(brsvd_params), C.POINTER(vp)]
     L.brsvd_run.argtypes = [vp, vp, i64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
+    L.brsvd_run_f64.argtypes = L.brsvd_run.argtypes
     L.brsvd_rpca_ialm.argtypes = [vp, vp, vp, i32, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
                                   C.POINTER(brsvd_stats)]
     L.brsvd_rpca_ialm_tol.argtypes = [vp, vp, vp, i32, dbl, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
@@ -134,11 +138,12 @@ def _dev(t, dtype, name):
 
 def make_params(m, n, k, p, q, row_block=0, device_budget_bytes=0, a_location=BRSVD_A_DEVICE,
                 orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None,
-                pass_mode=BRSVD_PASSES_SEPARATE) -> brsvd_params:
+                pass_mode=BRSVD_PASSES_SEPARATE, dtype=BRSVD_DTYPE_F32) -> brsvd_params:
     return brsvd_params(m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
                         device_budget_bytes=device_budget_bytes, orth_method=orth_method, pass_mode=pass_mode,
                         compute_stream=_stream_ptr(compute_stream),
-                        copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None)
+                        copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None,
+                        dtype=dtype, reserved=0)
 
 
 def brsvd_workspace_bytes(params: brsvd_params) -> int:
@@ -159,25 +164,27 @@ def brsvd_destroy(handle) -> None:
 
 def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = None, want_stats=True,
               pinned=False):
-    """A: (m, n) fp32 CUDA tensor (or pinned host tensor for a host-resident handle), row stride
-    lda; Omega: (n, l) fp32 CUDA.  pinned=True vouches for a host A that torch did not allocate itself
-    (see PinnedMatrix).  Returns (U, S, Vt, stats) as CUDA tensors m x l, l, l x n."""
+    """A: (m, n) CUDA tensor (or pinned host tensor for a host-resident handle), row stride lda, fp32 -- or
+    fp64 for a handle created with dtype=BRSVD_DTYPE_F64 (brsvd_run_f64); Omega: (n, l) CUDA, same dtype.
+    pinned=True vouches for a host A that torch did not allocate itself (see PinnedMatrix).
+    Returns (U, S, Vt, stats) as CUDA tensors m x l, l, l x n."""
     import torch
     m, n = A.shape
     l = Omega.shape[1]
-    if A.dtype != torch.float32 or A.stride(1) != 1:
-        raise TypeError("A must be fp32 with unit column stride")
+    dt = A.dtype
+    if dt not in (torch.float32, torch.float64) or A.stride(1) != 1:
+        raise TypeError("A must be fp32 or fp64 with unit column stride")
     if not A.is_cuda and not (pinned or A.is_pinned()):
         raise TypeError("a host-resident A must be pinned")
     lda = lda if lda is not None else A.stride(0)
     dev = Omega.device
-    U = torch.empty(m, l, device=dev) if U is None else U
-    S = torch.empty(l, device=dev) if S is None else S
-    Vt = torch.empty(l, n, device=dev) if Vt is None else Vt
+    U = torch.empty(m, l, device=dev, dtype=dt) if U is None else U
+    S = torch.empty(l, device=dev, dtype=dt) if S is None else S
+    Vt = torch.empty(l, n, device=dev, dtype=dt) if Vt is None else Vt
     st = brsvd_stats()
-    status = lib().brsvd_run(handle, A.data_ptr(), lda, _dev(Omega, torch.float32, "Omega"),
-                             _dev(U, torch.float32, "U"), _dev(S, torch.float32, "S"),
-                             _dev(Vt, torch.float32, "Vt"), C.byref(st) if want_stats else None)
+    fn = lib().brsvd_run_f64 if dt == torch.float64 else lib().brsvd_run
+    status = fn(handle, A.data_ptr(), lda, _dev(Omega, dt, "Omega"), _dev(U, dt, "U"), _dev(S, dt, "S"),
+                _dev(Vt, dt, "Vt"), C.byref(st) if want_stats else None)
     _check(status, "brsvd_run")
     return U, S, Vt, (st.as_dict() if want_stats else None)
 

@@ -57,8 +57,9 @@ struct brsvd_handle_s {
   bool timing;
   int64_t launches[CAT_COUNT];
 
-  float* Pm(int i) { return (float*)(arena + lay.Pm[i]); }
-  float* Pn(int i) { return (float*)(arena + lay.Pn[i]); }
+  int esz() const { return prm.dtype == BRSVD_DTYPE_F64 ? 8 : 4; }
+  template <typename T = float> T* Pm(int i) { return (T*)(arena + lay.Pm[i]); }
+  template <typename T = float> T* Pn(int i) { return (T*)(arena + lay.Pn[i]); }
   template <typename T> T* at(uint64_t off) { return (T*)(arena + off); }
 };
 
@@ -74,6 +75,7 @@ int validate(const brsvd_params* p) {
   if (p->orth_method < BRSVD_ORTH_AUTO || p->orth_method > BRSVD_ORTH_TSQR) return BRSVD_ERR_ARG;
   if (p->row_block < 0) return BRSVD_ERR_ARG;
   if (p->pass_mode != BRSVD_PASSES_SEPARATE && p->pass_mode != BRSVD_PASSES_FUSED) return BRSVD_ERR_ARG;
+  if (p->dtype != BRSVD_DTYPE_F32 && p->dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
   return BRSVD_OK;
 }
 
@@ -84,38 +86,40 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   const int l = p.k + p.p, Lp = padded_l(l);
   const int64_t m = p.m, n = p.n;
   const bool host = p.a_location == BRSVD_A_HOST_PINNED;
+  const int esz = p.dtype == BRSVD_DTYPE_F64 ? 8 : 4;      // element size of A and of the panels
   uint64_t off = 0;
   auto take = [&](uint64_t bytes) { uint64_t o = off; off += align_up(bytes); return o; };
-  for (int i = 0; i < 2; ++i) L.Pm[i] = take((uint64_t)m * Lp * 4);
-  for (int i = 0; i < 2; ++i) L.Pn[i] = take((uint64_t)n * Lp * 4);
+  for (int i = 0; i < 2; ++i) L.Pm[i] = take((uint64_t)m * Lp * esz);
+  for (int i = 0; i < 2; ++i) L.Pn[i] = take((uint64_t)n * Lp * esz);
   // split-sum scratch: the largest of every GEMM shape issued by the driver
   uint64_t gs = 0;
   if (host) {
-    gs = std::max(gs, gemm_an_scratch_bytes(b, n, Lp));
-    gs = std::max(gs, gemm_at_scratch_bytes(b, n, Lp, b));
+    gs = std::max(gs, gemm_an_scratch_bytes(b, n, Lp, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(b, n, Lp, b, esz));
   } else {
-    gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp));
-    gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b));
+    gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b, esz));
   }
-  if (!host) {   // single-vector products of the spectral-norm power method (16-column panels)
+  if (!host && esz == 4) {   // single-vector products of the spectral-norm power method (16-column panels)
     gs = std::max(gs, gemm_an_scratch_bytes(m, n, kTile));
     gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, b));
   }
-  gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp));
-  gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp));
+  gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp, esz));
+  gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp, esz));
   L.gemm_scratch_bytes = gs;
   L.gemm_scratch = take(gs);
   L.gram_chunks = (int)std::max(orth_gram_slots(m, Lp), orth_gram_slots(n, Lp));
   L.gram_part = take((uint64_t)L.gram_chunks * Lp * Lp * 8);
   const uint64_t sq8 = (uint64_t)Lp * Lp * 8, sq4 = (uint64_t)Lp * Lp * 4;
   L.G = take(sq8); L.R0 = take(sq8); L.R1 = take(sq8); L.Xinv = take(sq8); L.Rtot = take(sq8);
-  L.Rinv = take(sq4); L.XV = take(sq4); L.XU = take(sq4);
+  const uint64_t sqe = (uint64_t)Lp * Lp * esz;
+  L.Rinv = take(sqe); L.XV = take(sqe); L.XU = take(sqe);
   L.svdW = take(sq8); L.svdJ = take(sq8);
   L.sig = take((uint64_t)3 * Lp * 8);
-  L.S32 = take((uint64_t)Lp * 4);
+  L.S32 = take((uint64_t)Lp * esz);
   L.flags = take(64);
   L.scal = take(64);
-  if (!host) {   // results of the inner SVDs of the robust-PCA loop, and its reduction scratch
+  if (!host && esz == 4) {   // results of the inner SVDs of the robust-PCA loop, and its reduction scratch
     L.rpcaU = take((uint64_t)m * l * 4);
     L.rpcaVt = take((uint64_t)l * n * 4);
     L.rpca_part = take(rpca_part_doubles(m, n) * 8);
@@ -123,7 +127,7 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   L.tsqr_bytes = std::max(tsqr_work_bytes(m, Lp), tsqr_work_bytes(n, Lp));
   L.tsqr = take(L.tsqr_bytes);
   if (host) {
-    L.stage_bytes = (uint64_t)b * n * 4;
+    L.stage_bytes = (uint64_t)b * n * esz;
     for (int i = 0; i < 2; ++i) L.stage[i] = take(L.stage_bytes);
   }
   L.total = off;
@@ -190,15 +194,16 @@ bool kernel_events(brsvd_handle h, int cat, KernelEvents* ke) {
   return true;
 }
 
-OrthWork orth_work(brsvd_handle h) {
-  OrthWork w;
+template <typename T = float>
+OrthWorkT<T> orth_work(brsvd_handle h) {
+  OrthWorkT<T> w;
   w.gram_part = h->at<double>(h->lay.gram_part);
   w.gram_chunks_max = h->lay.gram_chunks;
   w.G = h->at<double>(h->lay.G);
   w.R[0] = h->at<double>(h->lay.R0);
   w.R[1] = h->at<double>(h->lay.R1);
   w.Xinv = h->at<double>(h->lay.Xinv);
-  w.Rinv = h->at<float>(h->lay.Rinv);
+  w.Rinv = h->at<T>(h->lay.Rinv);
   w.flags = h->at<int>(h->lay.flags);
   w.gemm_scratch = h->arena + h->lay.gemm_scratch;
   w.gemm_scratch_bytes = h->lay.gemm_scratch_bytes;
@@ -211,34 +216,36 @@ OrthWork orth_work(brsvd_handle h) {
 // Host-resident A: software pipeline over the two staging buffers.
 struct Streamer {
   brsvd_handle h;
-  const float* A;
+  const char* A;   // host-resident matrix, elements of h->esz() bytes
   int64_t lda;
   int issued;   // blocks whose copy has been enqueued in this pass
-  Streamer(brsvd_handle h_, const float* A_, int64_t lda_) : h(h_), A(A_), lda(lda_), issued(0) {}
+  Streamer(brsvd_handle h_, const void* A_, int64_t lda_) : h(h_), A((const char*)A_), lda(lda_), issued(0) {}
   int64_t rows_of(int i) const { return std::min<int64_t>(h->b, h->prm.m - (int64_t)i * h->b); }
   int enqueue_copy(int i) {
     const int buf = i & 1;
     // the buffer must have been consumed by the GEMM that last used it
     BRSVD_HIP_TRY(hipStreamWaitEvent(h->copy, h->drained[buf], 0));
-    float* dst = h->at<float>(h->lay.stage[buf]);
-    const float* src = A + (int64_t)i * h->b * lda;
+    char* dst = h->at<char>(h->lay.stage[buf]);
+    const size_t esz = (size_t)h->esz();
+    const char* src = A + (int64_t)i * h->b * lda * esz;
     const int64_t rows = rows_of(i), n = h->prm.n;
     Region r(h, CAT_COPY, h->copy);
     if (lda == n) {
-      BRSVD_HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * n * 4, hipMemcpyHostToDevice, h->copy));
+      BRSVD_HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * n * esz, hipMemcpyHostToDevice, h->copy));
     } else {
-      BRSVD_HIP_TRY(hipMemcpy2DAsync(dst, (size_t)n * 4, src, (size_t)lda * 4, (size_t)n * 4, (size_t)rows,
+      BRSVD_HIP_TRY(hipMemcpy2DAsync(dst, (size_t)n * esz, src, (size_t)lda * esz, (size_t)n * esz, (size_t)rows,
                                      hipMemcpyHostToDevice, h->copy));
     }
     BRSVD_HIP_TRY(hipEventRecord(h->filled[buf], h->copy));
     return BRSVD_OK;
   }
   // make block i available to the compute stream; prefetch block i+1
-  int acquire(int i, const float** blk) {
+  template <typename T>
+  int acquire(int i, const T** blk) {
     if (issued == 0) { BRSVD_TRY(enqueue_copy(0)); issued = 1; }
     if (i + 1 < h->nblocks && issued == i + 1) { BRSVD_TRY(enqueue_copy(i + 1)); issued = i + 2; }
     BRSVD_HIP_TRY(hipStreamWaitEvent(h->compute, h->filled[i & 1], 0));
-    *blk = h->at<float>(h->lay.stage[i & 1]);
+    *blk = h->at<T>(h->lay.stage[i & 1]);
     return BRSVD_OK;
   }
   int release(int i) {
@@ -247,7 +254,8 @@ struct Streamer {
   }
 };
 
-int pass_an(brsvd_handle h, const float* A, int64_t lda, const float* X, float* Y) {
+template <typename T>
+int pass_an(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Y) {
   const int Lp = h->Lp;
   const int64_t m = h->prm.m, n = h->prm.n;
   void* scr = h->arena + h->lay.gemm_scratch;
@@ -258,7 +266,7 @@ int pass_an(brsvd_handle h, const float* A, int64_t lda, const float* X, float* 
   }
   Streamer st(h, A, lda);
   for (int i = 0; i < h->nblocks; ++i) {
-    const float* blk;
+    const T* blk;
     BRSVD_TRY(st.acquire(i, &blk));
     KernelEvents ke;
     bool t = kernel_events(h, CAT_AN, &ke);
@@ -269,7 +277,8 @@ int pass_an(brsvd_handle h, const float* A, int64_t lda, const float* X, float* 
   return BRSVD_OK;
 }
 
-int pass_at(brsvd_handle h, const float* A, int64_t lda, const float* Q, float* Z) {
+template <typename T>
+int pass_at(brsvd_handle h, const T* A, int64_t lda, const T* Q, T* Z) {
   const int Lp = h->Lp;
   const int64_t m = h->prm.m, n = h->prm.n;
   void* scr = h->arena + h->lay.gemm_scratch;
@@ -281,7 +290,7 @@ int pass_at(brsvd_handle h, const float* A, int64_t lda, const float* Q, float* 
   }
   Streamer st(h, A, lda);
   for (int i = 0; i < h->nblocks; ++i) {
-    const float* blk;
+    const T* blk;
     BRSVD_TRY(st.acquire(i, &blk));
     KernelEvents ke;
     bool t = kernel_events(h, CAT_AT, &ke);
@@ -294,19 +303,20 @@ int pass_at(brsvd_handle h, const float* A, int64_t lda, const float* Q, float* 
 
 // One read of A doing both products of a power step: T_I = A_I * X and Z += A_I^T * T_I while block I
 // is resident (device-resident A: two launches over the whole matrix).
-int pass_fused(brsvd_handle h, const float* A, int64_t lda, const float* X, float* T, float* Z) {
+template <typename T>
+int pass_fused(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Tm_, T* Z) {
   const int Lp = h->Lp;
   const int64_t n = h->prm.n;
   void* scr = h->arena + h->lay.gemm_scratch;
   if (!h->host_a) {
-    BRSVD_TRY(pass_an(h, A, lda, X, T));
-    return pass_at(h, A, lda, T, Z);
+    BRSVD_TRY(pass_an<T>(h, A, lda, X, Tm_));
+    return pass_at<T>(h, A, lda, Tm_, Z);
   }
   Streamer st(h, A, lda);
   for (int i = 0; i < h->nblocks; ++i) {
-    const float* blk;
+    const T* blk;
     BRSVD_TRY(st.acquire(i, &blk));
-    float* Ti = T + (int64_t)i * h->b * Lp;
+    T* Ti = Tm_ + (int64_t)i * h->b * Lp;
     KernelEvents ke;
     bool t = kernel_events(h, CAT_AN, &ke);
     BRSVD_TRY(gemm_an(blk, n, st.rows_of(i), n, X, Lp, Ti, Lp, Lp, scr, h->lay.gemm_scratch_bytes, h->compute,
@@ -320,70 +330,70 @@ int pass_fused(brsvd_handle h, const float* A, int64_t lda, const float* X, floa
 }
 
 // The whole factorisation, enqueued asynchronously on the handle's streams.
-int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S,
-                  float* Vt, int method) {
+template <typename T>
+int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int method) {
   const int l = h->l, Lp = h->Lp, q = h->prm.q;
   const int64_t m = h->prm.m, n = h->prm.n;
   hipStream_t cs = h->compute;
-  OrthWork ow = orth_work(h);
+  OrthWorkT<T> ow = orth_work<T>(h);
   void* scr = h->arena + h->lay.gemm_scratch;
   const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
 
-  float* Xn = h->Pn(0);    // current n x Lp panel (Omega, then W)
-  float* Tn = h->Pn(1);
-  float* Ym = h->Pm(0);    // current m x Lp panel
-  float* Tm = h->Pm(1);
-  float* res;
+  T* Xn = h->Pn<T>(0);    // current n x Lp panel (Omega, then W)
+  T* Tn = h->Pn<T>(1);
+  T* Ym = h->Pm<T>(0);    // current m x Lp panel
+  T* Tm = h->Pm<T>(1);
+  T* res;
 
   BRSVD_TRY(pad_panel(Omega, n, l, Xn, Lp, cs));
   if (h->prm.pass_mode == BRSVD_PASSES_FUSED) {
     // q passes Z = A^T (A X), X <- orth(Z), then one pass Y = A X, C^T = A^T Y; with Y = Q R the
     // projection is B^T = A^T Q = C^T R^-1, so R^-1 is applied to both panels.
     for (int it = 0; it < q; ++it) {
-      BRSVD_TRY(pass_fused(h, A, lda, Xn, Ym, Tn));
+      BRSVD_TRY(pass_fused<T>(h, A, lda, Xn, Ym, Tn));
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Tn, Xn, n, l, Lp, method, false, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel<T>(Tn, Xn, n, l, Lp, method, false, ow, nullptr, &res, cs));
       if (res != Xn) std::swap(Xn, Tn);
     }
-    BRSVD_TRY(pass_fused(h, A, lda, Xn, Ym, Tn));
+    BRSVD_TRY(pass_fused<T>(h, A, lda, Xn, Ym, Tn));
     {
       Region r(h, CAT_ORTH, cs);
       ow.comp = Tn; ow.comp_tmp = Xn; ow.comp_rows = n;
-      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, true, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel<T>(Ym, Tm, m, l, Lp, method, true, ow, nullptr, &res, cs));
       if (res != Ym) std::swap(Ym, Tm);
       Xn = ow.comp; Tn = ow.comp_tmp;     // B^T and a free n x Lp buffer
       ow.comp = ow.comp_tmp = nullptr; ow.comp_rows = 0;
     }
   } else {
-    BRSVD_TRY(pass_an(h, A, lda, Xn, Ym));
+    BRSVD_TRY(pass_an<T>(h, A, lda, Xn, Ym));
     {
       Region r(h, CAT_ORTH, cs);
-      BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, q == 0, ow, nullptr, &res, cs));
+      BRSVD_TRY(orth_panel<T>(Ym, Tm, m, l, Lp, method, q == 0, ow, nullptr, &res, cs));
       if (res != Ym) std::swap(Ym, Tm);
     }
     for (int it = 0; it < q; ++it) {
-      BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+      BRSVD_TRY(pass_at<T>(h, A, lda, Ym, Xn));
       {
         Region r(h, CAT_ORTH, cs);
-        BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, false, ow, nullptr, &res, cs));
+        BRSVD_TRY(orth_panel<T>(Xn, Tn, n, l, Lp, method, false, ow, nullptr, &res, cs));
         if (res != Xn) std::swap(Xn, Tn);
       }
-      BRSVD_TRY(pass_an(h, A, lda, Xn, Tm));
+      BRSVD_TRY(pass_an<T>(h, A, lda, Xn, Tm));
       std::swap(Ym, Tm);
       {
         Region r(h, CAT_ORTH, cs);
-        BRSVD_TRY(orth_panel(Ym, Tm, m, l, Lp, method, it == q - 1, ow, nullptr, &res, cs));
+        BRSVD_TRY(orth_panel<T>(Ym, Tm, m, l, Lp, method, it == q - 1, ow, nullptr, &res, cs));
         if (res != Ym) std::swap(Ym, Tm);
       }
     }
     // projection B^T = A^T Q
-    BRSVD_TRY(pass_at(h, A, lda, Ym, Xn));
+    BRSVD_TRY(pass_at<T>(h, A, lda, Ym, Xn));
   }
   // thin QR of B^T, the small SVD, the lifts
   double* Rtot = h->at<double>(h->lay.Rtot);
   {
     Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Xn, Tn, n, l, Lp, method, true, ow, Rtot, &res, cs));
+    BRSVD_TRY(orth_panel<T>(Xn, Tn, n, l, Lp, method, true, ow, Rtot, &res, cs));
     if (res != Xn) std::swap(Xn, Tn);
   }
   SvdWork sw;
@@ -391,11 +401,11 @@ int enqueue_brsvd(brsvd_handle h, const float* A, int64_t lda, const float* Omeg
   sw.J = h->at<double>(h->lay.svdJ);
   sw.sig = h->at<double>(h->lay.sig);
   sw.info = h->at<int>(h->lay.flags) + 4;
-  float* XV = h->at<float>(h->lay.XV);
-  float* XU = h->at<float>(h->lay.XU);
+  T* XV = h->at<T>(h->lay.XV);
+  T* XU = h->at<T>(h->lay.XU);
   {
     Region r(h, CAT_SVD, cs);
-    BRSVD_TRY(small_svd(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
+    BRSVD_TRY(small_svd<T>(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
   }
   {
     Region r(h, CAT_LIFT, cs);
@@ -521,7 +531,7 @@ void fill_stats(brsvd_handle h, brsvd_stats* st, int passes, int fallbacks) {
   st->gemm_an_launches = h->launches[CAT_AN];
   st->gemm_at_launches = h->launches[CAT_AT];
   st->passes_over_A = passes;
-  st->bytes_A_streamed = (int64_t)passes * 4 * h->prm.m * h->prm.n;
+  st->bytes_A_streamed = (int64_t)passes * h->esz() * h->prm.m * h->prm.n;
   st->orth_fallbacks = fallbacks;
   st->jacobi_sweeps = h->host_flags[1];
   st->row_block = (int32_t)h->b;
@@ -576,9 +586,26 @@ int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
   return BRSVD_ERR_ORTH_BREAKDOWN;
 }
 
-int run_sync(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
-             int* fallbacks) {
-  return run_sync_with(h, fallbacks, [&](int method) { return enqueue_brsvd(h, A, lda, Omega, U, S, Vt, method); });
+template <typename T>
+int run_sync(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int* fallbacks) {
+  return run_sync_with(h, fallbacks, [&](int method) { return enqueue_brsvd<T>(h, A, lda, Omega, U, S, Vt, method); });
+}
+
+template <typename T>
+int run_with_stats(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, brsvd_stats* stats) {
+  if (!A || !Omega || !U || !S || !Vt) return BRSVD_ERR_ARG;
+  if (lda < h->prm.n) return BRSVD_ERR_ARG;
+  reset_timing(h, stats != nullptr);
+  int fallbacks = 0, status;
+  {
+    Region total(h, CAT_TOTAL, h->compute);
+    status = run_sync<T>(h, A, lda, Omega, U, S, Vt, &fallbacks);
+  }
+  if (stats) {
+    (void)hipStreamSynchronize(h->compute);
+    fill_stats(h, stats, passes_per_run(h) * (1 + fallbacks), fallbacks);
+  }
+  return status;
 }
 
 // ---- step-level GEMM calls (both element types) --------------------------------------------------
@@ -713,25 +740,20 @@ int brsvd_destroy(brsvd_handle h) {
 
 int brsvd_run(brsvd_handle h, const float* A, int64_t lda, const float* Omega, float* U, float* S, float* Vt,
               brsvd_stats* stats) {
-  if (!h || !A || !Omega || !U || !S || !Vt) return BRSVD_ERR_ARG;
-  if (lda < h->prm.n) return BRSVD_ERR_ARG;
-  reset_timing(h, stats != nullptr);
-  int fallbacks = 0, status;
-  {
-    Region total(h, CAT_TOTAL, h->compute);
-    status = run_sync(h, A, lda, Omega, U, S, Vt, &fallbacks);
-  }
-  if (stats) {
-    (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, passes_per_run(h) * (1 + fallbacks), fallbacks);
-  }
-  return status;
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
+  return run_with_stats<float>(h, A, lda, Omega, U, S, Vt, stats);
+}
+
+int brsvd_run_f64(brsvd_handle h, const double* A, int64_t lda, const double* Omega, double* U, double* S,
+                  double* Vt, brsvd_stats* stats) {
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  return run_with_stats<double>(h, A, lda, Omega, U, S, Vt, stats);
 }
 
 int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega, float* U,
                    float* S, float* Vt, brsvd_stats* stats) {
   if (!h || !A || !U || !S || !Vt) return BRSVD_ERR_ARG;
-  if (lda < h->prm.n) return BRSVD_ERR_ARG;
+  if (lda < h->prm.n || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
   reset_timing(h, stats != nullptr);
   int fallbacks = 0, status;
   {
@@ -756,6 +778,7 @@ int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int
                         double* residuals, int32_t* iters_done, brsvd_stats* stats) {
   if (iters_done) *iters_done = 0;
   if (!h || !M || !Omegas || !L || !S || !work || max_iters < 1) return BRSVD_ERR_ARG;
+  if (h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
   if (h->host_a || !(lambda > 0.f) || !(mu0 > 0.f) || !(rho > 1.f) || !(tol >= 0.0)) return BRSVD_ERR_ARG;
   const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
   const int l = h->l;
@@ -853,6 +876,7 @@ int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t
 int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* x0, int32_t iters,
                       double* norm2_out) {
   if (!h || !A || !x0 || !norm2_out || iters < 1 || lda < h->prm.n || h->host_a) return BRSVD_ERR_ARG;
+  if (h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
   const int64_t m = h->prm.m, n = h->prm.n;
   const int L1 = kTile;                 // the vector travels as column 0 of a 16-column padded panel
   hipStream_t cs = h->compute;
@@ -988,7 +1012,7 @@ int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* V
   w.J = (double*)(buf + sq8);
   w.sig = (double*)(buf + 2 * sq8);
   w.info = (int*)(buf + 2 * sq8 + align_up((uint64_t)3 * Lp * 8));
-  int status = small_svd(R, l, l, Lp, w, nullptr, S, nullptr, nullptr, nullptr, Ur, Vr, s);
+  int status = small_svd<float>(R, l, l, Lp, w, nullptr, S, nullptr, nullptr, nullptr, Ur, Vr, s);
   int info[2] = {0, 0};
   if (status == BRSVD_OK) {
     if (hipMemcpyAsync(info, w.info, sizeof(info), hipMemcpyDeviceToHost, s) != hipSuccess ||

@@ -69,13 +69,15 @@ int transpose_panel(const float* src, int64_t rows, int Lp, int l, float* dst, h
 int transpose_panel(const double* src, int64_t rows, int Lp, int l, double* dst, hipStream_t stream);
 
 // ---- orthonormalisation (orth.hip, tsqr.hip) -----------------------------------------------
-struct OrthWork {
+// T = element type of the panels (float or double); the l x l factors are fp64 either way.
+template <typename T>
+struct OrthWorkT {
   double* gram_part;   // gram_chunks_max slots of Lp x Lp partial Gram sums (orth_gram_slots)
   int gram_chunks_max;
   double* G;           // Lp x Lp
   double* R[2];        // upper-triangular factors of the two CholeskyQR sweeps (stride Lp)
   double* Xinv;        // Lp x Lp fp64 scratch for R^-1
-  float* Rinv;         // Lp x Lp fp32 zero-padded inverse factor (right operand of the apply GEMM)
+  T* Rinv;             // Lp x Lp zero-padded inverse factor in the panels' type (right operand of the apply GEMM)
   int* flags;          // device: [0] = breakdown flag (0 = none, else 1 + column)
   void* gemm_scratch;
   uint64_t gemm_scratch_bytes;
@@ -83,12 +85,13 @@ struct OrthWork {
   uint64_t tsqr_bytes;
   // Optional companion panel (comp_rows x Lp): every R^-1 applied to the panel being orthonormalised
   // is applied to it as well (comp <- comp * R^-1, ping-ponging with comp_tmp; the result is in comp).
-  float* comp = nullptr;
-  float* comp_tmp = nullptr;
+  T* comp = nullptr;
+  T* comp_tmp = nullptr;
   int64_t comp_rows = 0;
 };
+typedef OrthWorkT<float> OrthWork;
 // Applies the current w.Rinv to the companion panel, if any.
-int apply_to_companion(OrthWork& w, int Lp, hipStream_t stream);
+template <typename T> int apply_to_companion(OrthWorkT<T>& w, int Lp, hipStream_t stream);
 uint64_t orth_gram_slots(int64_t rows, int Lp);   // Lp x Lp fp64 slots of partial Gram sums for such a panel
 uint64_t tsqr_work_bytes(int64_t rows, int Lp);
 // Orthonormalises the columns of P (rows x Lp padded panel, rows >= l).  tmp is a second
@@ -96,8 +99,19 @@ uint64_t tsqr_work_bytes(int64_t rows, int Lp);
 // Rtot (stride Lp, fp64, may be null) receives the triangular factor with P_in = Q * Rtot.
 // Asynchronous: a CholeskyQR breakdown is only reported through w.flags[0] on the device.
 // final_basis = false: the panel only seeds the next power half step (one CholeskyQR sweep).
-int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bool final_basis,
-               OrthWork& w, double* Rtot, float** result, hipStream_t stream);
+template <typename T>
+int orth_panel(T* P, T* tmp, int64_t rows, int l, int Lp, int method, bool final_basis, OrthWorkT<T>& w,
+               double* Rtot, T** result, hipStream_t stream);
+// Pieces shared between the CholeskyQR and the Householder-tree routes (orth.hip, tsqr.hip).
+template <typename T>
+int cholqr_sweeps(T* P, T* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWorkT<T>& w, double* Rtot,
+                  T** result, hipStream_t stream, bool strict_last);
+template <typename T>
+int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, T* Rinv, int* flags, hipStream_t stream);
+template <typename T>
+int tsqr_panel(T* P, T* tmp, int64_t rows, int l, int Lp, OrthWorkT<T>& w, double* Rtot, T** result,
+               hipStream_t stream);
+int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream);
 
 // ---- small SVD (small_svd.hip) -------------------------------------------------------------
 struct SvdWork {
@@ -106,12 +120,12 @@ struct SvdWork {
   double* sig;   // 3 * Lp
   int* info;     // device: [0] sweeps, [1] converged
 };
-// R (l x l fp64, stride ldr): R = Ur diag(S) Vr^T.  Writes S (descending) as fp64 and/or fp32,
-// the fp32 zero-padded (Lp x Lp) operands XV = Vr and XU = Ur used by the lifts, and optional
-// dense fp64 l x l Ur / Vr.  Skips the work when *breakdown_flag != 0.
+// R (l x l fp64, stride ldr): R = Ur diag(S) Vr^T.  Writes S (descending) as fp64 and/or in the
+// panels' type TO, the zero-padded (Lp x Lp) operands XV = Vr and XU = Ur used by the lifts (type TO),
+// and optional dense fp64 l x l Ur / Vr.  Skips the work when *breakdown_flag != 0.
+template <typename TO>
 int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag,
-              double* S, float* S32, float* XV, float* XU, double* Ur, double* Vr,
-              hipStream_t stream);
+              double* S, TO* S32, TO* XV, TO* XU, double* Ur, double* Vr, hipStream_t stream);
 
 // ---- robust-PCA elementwise kernels (rpca.hip) ---------------------------------------------
 // Number of doubles of partial-sum scratch the reductions below need.

@@ -15,7 +15,7 @@ namespace brsvd {
 
 // ---- Gram matrix -----------------------------------------------------------------------------
 // G = P^T P on the fp64 matrix cores (v_mfma_f64_16x16x4_f64; products of fp32 values are exact in
-// fp64).  G is cut into blocks of TB x TB tiles of 16 x 16; grid = (row chunks, pairs bi <= bj of
+// fp64; the panel may also be fp64).  G is cut into blocks of TB x TB tiles of 16 x 16; grid = (row chunks, pairs bi <= bj of
 // blocks).  For a step of four panel rows, lane (r, g) of a wave holds P[row + g][16*tile + r] for
 // each tile of the two blocks: that value is at once the A operand (entry [i = r][k = g] of the
 // transposed tile) and the B operand ([k = g][j = r]), so the panel goes from global memory straight
@@ -29,9 +29,9 @@ __device__ __forceinline__ doublex4 mfma_f64(double a, double b, doublex4 c) {
   return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
-template <int TB>
+template <typename T, int TB>
 __global__ void __launch_bounds__(kGramWaves * 64)
-k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk, double* __restrict__ Gpart) {
+k_gram(const T* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk, double* __restrict__ Gpart) {
   __shared__ double red[kGramWaves][256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = lane & 15, g = lane >> 4;
   const int NT = Lp / 16, nb = (NT + TB - 1) / TB;
@@ -42,8 +42,8 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
   const bool diag = bi == bj;
   const int64_t rbeg = (int64_t)blockIdx.x * rows_per_chunk;
   const int64_t rend = min(rows, rbeg + rows_per_chunk);
-  const float* pi = P + 16 * (bi * TB) + r;
-  const float* pj = P + 16 * (bj * TB) + r;
+  const T* pi = P + 16 * (bi * TB) + r;
+  const T* pj = P + 16 * (bj * TB) + r;
 
   doublex4 acc[TB][TB];
 #pragma unroll
@@ -51,15 +51,15 @@ k_gram(const float* __restrict__ P, int64_t rows, int Lp, int64_t rows_per_chunk
 #pragma unroll
     for (int j = 0; j < TB; ++j) acc[i][j] = doublex4{0.0, 0.0, 0.0, 0.0};
 
-  float an[TB], bn[TB];
+  T an[TB], bn[TB];
   auto load = [&](int64_t row0) {
     const int64_t row = row0 + g;
     const bool valid = row < rend;
     const int64_t off = (valid ? row : rbeg) * Lp;
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
-      an[t] = (valid && t < ti_n) ? pi[off + 16 * t] : 0.f;
-      bn[t] = (valid && t < tj_n && !diag) ? pj[off + 16 * t] : 0.f;
+      an[t] = (valid && t < ti_n) ? pi[off + 16 * t] : T(0);
+      bn[t] = (valid && t < tj_n && !diag) ? pj[off + 16 * t] : T(0);
     }
   };
   int64_t row0 = rbeg + 4 * wave;
@@ -224,17 +224,17 @@ __device__ __forceinline__ void trailing_tile(double* M, int64_t ld, const doubl
 // 16 x 16 tile.  Schedule of the factorisation: wave 0 factors the diagonal block of step k+1 (after
 // updating that one tile) while the other waves finish the trailing update of step k, which takes
 // the 16-step pivot chain off the critical path of all but the first block.
-template <bool IN_LDS>
+template <bool IN_LDS, typename TO>
 __global__ void __launch_bounds__(1024)
 k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
-           float* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored, int lenient) {
+           TO* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored, int lenient) {
   extern __shared__ double smem[];
   __shared__ int bad;
   double* Rkk = smem;                 // 16 x 17
   double* d0 = smem + 16 * 17;        // kMaxL
   double* rest = d0 + kMaxL;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < Lp * Lp; i += 1024) Rinv32[i] = 0.f;
+  for (int i = tid; i < Lp * Lp; i += 1024) Rinv32[i] = TO(0);
   if (flag[0] != 0) return;           // an earlier panel already broke down: results are void anyway
   double* M;
   int ld;
@@ -424,7 +424,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   }
   for (int idx = tid; idx < l * l; idx += 1024) {
     int i = idx / l, c = idx - i * l;
-    if (c >= i) Rinv32[(int64_t)i * Lp + c] = (float)M[(int64_t)i * ld + c];
+    if (c >= i) Rinv32[(int64_t)i * Lp + c] = (TO)M[(int64_t)i * ld + c];
   }
 }
 
@@ -470,7 +470,8 @@ __global__ void k_reduce_groups(const double* __restrict__ part, int nsplit, int
   out[(int64_t)blockIdx.y * count + idx] = s;
 }
 
-static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t stream) {
+template <typename T>
+static int gram(const T* P, int64_t rows, int Lp, OrthWorkT<T>& w, hipStream_t stream) {
   int chunks = (int)orth_gram_chunks(rows, Lp);
   if ((int64_t)orth_gram_slots(rows, Lp) > w.gram_chunks_max) return BRSVD_ERR_BUDGET;
   int64_t rpc = ceil_div(rows, chunks);
@@ -479,10 +480,10 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
   const int nt = Lp / 16, nb = (nt + 3) / 4;       // blocks of (up to) four tiles; a single smaller block when nt < 4
   dim3 grid(chunks, nb * (nb + 1) / 2), block(kGramWaves * 64);
   switch (nt) {
-    case 1: hipLaunchKernelGGL(k_gram<1>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
-    case 2: hipLaunchKernelGGL(k_gram<2>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
-    case 3: hipLaunchKernelGGL(k_gram<3>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
-    default: hipLaunchKernelGGL(k_gram<4>, grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    case 1: hipLaunchKernelGGL((k_gram<T, 1>), grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    case 2: hipLaunchKernelGGL((k_gram<T, 2>), grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    case 3: hipLaunchKernelGGL((k_gram<T, 3>), grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
+    default: hipLaunchKernelGGL((k_gram<T, 4>), grid, block, 0, stream, P, rows, Lp, rpc, w.gram_part); break;
   }
   BRSVD_HIP_TRY(hipGetLastError());
   const int64_t count = (int64_t)Lp * Lp;
@@ -502,44 +503,41 @@ static int gram(const float* P, int64_t rows, int Lp, OrthWork& w, hipStream_t s
 
 // lenient != 0: pivots below tol * (original diagonal) are clamped and the factorisation goes on;
 // otherwise such a pivot raises the breakdown flag and ends the kernel.
-static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags, double tol,
+template <typename TO>
+static int chol_inv(double* G, int l, int Lp, double* Rout, double* Xtmp, TO* Rinv, int* flags, double tol,
                     hipStream_t stream, int factored = 0, int lenient = 0) {
   const bool in_lds = Lp <= kCholLdsMaxLp;
   const size_t lds = (16 * 17 + kMaxL + (in_lds ? (size_t)Lp * (Lp + 1) : (size_t)kNB * kMaxL)) * sizeof(double);
   static bool attr_set = false;
   if (!attr_set) {
     const int max_lds = (16 * 17 + kMaxL + kCholLdsMaxLp * (kCholLdsMaxLp + 1)) * (int)sizeof(double);
-    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<true, TO>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       max_lds));
-    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)k_chol_inv<false, TO>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       (16 * 17 + kMaxL + kNB * kMaxL) * (int)sizeof(double)));
     attr_set = true;
   }
   if (in_lds)
-    hipLaunchKernelGGL(k_chol_inv<true>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags, tol,
+    hipLaunchKernelGGL((k_chol_inv<true, TO>), dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv, flags, tol,
                        factored, lenient);
   else
-    hipLaunchKernelGGL(k_chol_inv<false>, dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv32, flags,
+    hipLaunchKernelGGL((k_chol_inv<false, TO>), dim3(1), dim3(1024), lds, stream, G, l, Lp, Rout, Xtmp, Rinv, flags,
                        tol, factored, lenient);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
-int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot,
-               float** result, hipStream_t stream);
-int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream, bool strict_last = true);
-
-int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags,
-                      hipStream_t stream) {
-  return chol_inv(G, l, Lp, Rout, Xtmp, Rinv32, flags, 0.0, stream, 1);
+template <typename T>
+int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, T* Rinv, int* flags, hipStream_t stream) {
+  return chol_inv<T>(G, l, Lp, Rout, Xtmp, Rinv, flags, 0.0, stream, 1);
 }
 
-int apply_to_companion(OrthWork& w, int Lp, hipStream_t stream) {
+template <typename T>
+int apply_to_companion(OrthWorkT<T>& w, int Lp, hipStream_t stream) {
   if (!w.comp) return BRSVD_OK;
   BRSVD_TRY(gemm_an(w.comp, Lp, w.comp_rows, Lp, w.Rinv, Lp, w.comp_tmp, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes,
                     stream));
-  float* t = w.comp; w.comp = w.comp_tmp; w.comp_tmp = t;
+  T* t = w.comp; w.comp = w.comp_tmp; w.comp_tmp = t;
   return BRSVD_OK;
 }
 
@@ -556,18 +554,19 @@ int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hi
 // the numerically dependent directions of an exactly rank-deficient panel -- the paper's own test
 // inputs have rank k < l -- come out as damped rounding noise, which the next sweep or the next
 // power step treats like any other direction; P = Q R holds exactly either way.
-int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream, bool strict_last) {
+template <typename T>
+int cholqr_sweeps(T* P, T* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWorkT<T>& w, double* Rtot,
+                  T** result, hipStream_t stream, bool strict_last) {
   const double tol = 1e-12;
-  float* src = P;
-  float* dst = tmp;
+  T* src = P;
+  T* dst = tmp;
   for (int sweep = 0; sweep < nsweeps; ++sweep) {
-    BRSVD_TRY(gram(src, rows, Lp, w, stream));
+    BRSVD_TRY(gram<T>(src, rows, Lp, w, stream));
     const int lenient = (sweep + 1 < nsweeps || !strict_last) ? 1 : 0;
-    BRSVD_TRY(chol_inv(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream, 0, lenient));
+    BRSVD_TRY(chol_inv<T>(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream, 0, lenient));
     BRSVD_TRY(gemm_an(src, Lp, rows, Lp, w.Rinv, Lp, dst, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
-    BRSVD_TRY(apply_to_companion(w, Lp, stream));
-    float* t = src; src = dst; dst = t;
+    BRSVD_TRY(apply_to_companion<T>(w, Lp, stream));
+    T* t = src; src = dst; dst = t;
   }
   *result = src;
   if (Rtot) {
@@ -580,14 +579,24 @@ int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps
   return BRSVD_OK;
 }
 
-int orth_panel(float* P, float* tmp, int64_t rows, int l, int Lp, int method, bool final_basis, OrthWork& w,
-               double* Rtot, float** result, hipStream_t stream) {
+template <typename T>
+int orth_panel(T* P, T* tmp, int64_t rows, int l, int Lp, int method, bool final_basis, OrthWorkT<T>& w,
+               double* Rtot, T** result, hipStream_t stream) {
   if (rows < l) return BRSVD_ERR_ARG;
-  if (method == BRSVD_ORTH_TSQR) return tsqr_panel(P, tmp, rows, l, Lp, w, Rtot, result, stream);
+  if (method == BRSVD_ORTH_TSQR) return tsqr_panel<T>(P, tmp, rows, l, Lp, w, Rtot, result, stream);
   // A panel that only seeds the next power half step needs a well-conditioned basis, not one
   // orthonormal to working precision: one CholeskyQR sweep (fp64 Gram) leaves ||Q^T Q - I|| of
   // order eps32 * cond(P).  The bases that reach the output (Q behind U, W_B behind V) get two.
-  return cholqr_sweeps(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream, final_basis);
+  return cholqr_sweeps<T>(P, tmp, rows, l, Lp, final_basis ? 2 : 1, w, Rtot, result, stream, final_basis);
 }
+
+#define BRSVD_ORTH_INSTANTIATE(T)                                                                               \
+  template int chol_inv_factored<T>(double*, int, int, double*, double*, T*, int*, hipStream_t);                \
+  template int apply_to_companion<T>(OrthWorkT<T>&, int, hipStream_t);                                          \
+  template int cholqr_sweeps<T>(T*, T*, int64_t, int, int, int, OrthWorkT<T>&, double*, T**, hipStream_t, bool); \
+  template int orth_panel<T>(T*, T*, int64_t, int, int, int, bool, OrthWorkT<T>&, double*, T**, hipStream_t);
+BRSVD_ORTH_INSTANTIATE(float)
+BRSVD_ORTH_INSTANTIATE(double)
+#undef BRSVD_ORTH_INSTANTIATE
 
 }  // namespace brsvd

@@ -398,16 +398,17 @@ k_jacobi_publish(double* __restrict__ W, int l, int Lp, double* __restrict__ sig
 
 // Sorted factors.  Vr[t][i] = W[o_i][t] / s_i;  Ur[kk][i] = sum_t R[kk][t] Vr[t][i] / s_i.
 // XV / XU: fp32 zero-padded Lp x Lp right operands of the lifts; Ur / Vr: optional dense fp64.
+template <typename TO>
 __global__ void k_svd_outputs(const double* __restrict__ R, int ldr, const double* __restrict__ W,
                               const double* __restrict__ sig, int l, int Lp, double* __restrict__ S,
-                              float* __restrict__ S32, float* __restrict__ XV, float* __restrict__ XU,
+                              TO* __restrict__ S32, TO* __restrict__ XV, TO* __restrict__ XU,
                               double* __restrict__ Ur, double* __restrict__ Vr,
                               const int* __restrict__ breakdown_flag) {
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= Lp * Lp) return;
   if (breakdown_flag && breakdown_flag[0] != 0) return;   // nothing was computed
   int kk = idx / Lp, i = idx - kk * Lp;
-  float xv = 0.f, xu = 0.f;
+  TO xv = TO(0), xu = TO(0);
   if (kk < l && i < l) {
     const int o = min(max((int)sig[2 * Lp + i], 0), l - 1);   // stays in range even for NaN input
     const double s = sig[i];
@@ -420,12 +421,12 @@ __global__ void k_svd_outputs(const double* __restrict__ R, int ldr, const doubl
       for (int t = 0; t < l; ++t) acc = fma(rrow[t], wrow[t], acc);
       u = acc / (s * s);
     }
-    xv = (float)v; xu = (float)u;
+    xv = (TO)v; xu = (TO)u;
     if (Vr) Vr[(int64_t)kk * l + i] = v;
     if (Ur) Ur[(int64_t)kk * l + i] = u;
     if (kk == 0) {
       if (S) S[i] = s;
-      if (S32) S32[i] = (float)s;
+      if (S32) S32[i] = (TO)s;
     }
   }
   if (XV) XV[idx] = xv;
@@ -471,8 +472,9 @@ static int launch_jacobi_block(double* W, int l, int Lp, int nblk2, int outer, d
   return launch_jacobi_block_inst<32>(W, l, Lp, nblk2, outer, tol, rotated, stream);
 }
 
+template <typename TO>
 int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* breakdown_flag, double* S,
-              float* S32, float* XV, float* XU, double* Ur, double* Vr, hipStream_t stream) {
+              TO* S32, TO* XV, TO* XU, double* Ur, double* Vr, hipStream_t stream) {
   if (l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
   const double tol = 1e-13;
   if (l <= kJacobiLdsMaxL) {
@@ -513,10 +515,15 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
                          sweeps, converged);
     BRSVD_HIP_TRY(hipGetLastError());
   }
-  hipLaunchKernelGGL(k_svd_outputs, dim3((unsigned)ceil_div((int64_t)Lp * Lp, 256)), dim3(256), 0, stream, R, ldr,
+  hipLaunchKernelGGL(k_svd_outputs<TO>, dim3((unsigned)ceil_div((int64_t)Lp * Lp, 256)), dim3(256), 0, stream, R, ldr,
                      w.W, w.sig, l, Lp, S, S32, XV, XU, Ur, Vr, breakdown_flag);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
+
+template int small_svd<float>(const double*, int, int, int, SvdWork&, const int*, double*, float*, float*, float*,
+                              double*, double*, hipStream_t);
+template int small_svd<double>(const double*, int, int, int, SvdWork&, const int*, double*, double*, double*, double*,
+                               double*, double*, hipStream_t);
 
 }  // namespace brsvd

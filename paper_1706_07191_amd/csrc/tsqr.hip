@@ -113,13 +113,8 @@ uint64_t tsqr_work_bytes(int64_t rows, int Lp) {
   return scratch + 2 * stack + 1024;
 }
 
-int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, float* Rinv32, int* flags,
-                      hipStream_t stream);
-int cholqr_sweeps(float* P, float* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWork& w, double* Rtot,
-                  float** result, hipStream_t stream, bool strict_last = true);
-int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream);
-
-int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, double* Rtot, float** result,
+template <typename T>
+int tsqr_panel(T* P, T* tmp, int64_t rows, int l, int Lp, OrthWorkT<T>& w, double* Rtot, T** result,
                hipStream_t stream) {
   if (w.tsqr_bytes < tsqr_work_bytes(rows, Lp)) return BRSVD_ERR_BUDGET;
   const int64_t c0 = chunks_of(rows);
@@ -127,8 +122,8 @@ int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, d
   double* stack[2];
   stack[0] = scratch + (uint64_t)c0 * kTsqrC * Lp;
   stack[1] = stack[0] + (uint64_t)c0 * Lp * Lp;
-  // level 0: the fp32 panel
-  hipLaunchKernelGGL(k_tsqr_chunk<float>, dim3((unsigned)c0), dim3(1024), 0, stream, P, rows, (int64_t)Lp, l, Lp,
+  // level 0: the panel itself
+  hipLaunchKernelGGL(k_tsqr_chunk<T>, dim3((unsigned)c0), dim3(1024), 0, stream, P, rows, (int64_t)Lp, l, Lp,
                      scratch, stack[0]);
   BRSVD_HIP_TRY(hipGetLastError());
   int cur = 0;
@@ -145,14 +140,18 @@ int tsqr_panel(float* P, float* tmp, int64_t rows, int l, int Lp, OrthWork& w, d
   hipLaunchKernelGGL(k_tsqr_finish, dim3(1), dim3(1024), 0, stream, stack[cur], l, Lp, w.G);
   BRSVD_HIP_TRY(hipGetLastError());
   double* Rt = stack[cur ^ 1];    // free now: keeps the TSQR factor for the product R2 * R
-  BRSVD_TRY(chol_inv_factored(w.G, l, Lp, Rt, w.Xinv, w.Rinv, w.flags, stream));
+  BRSVD_TRY(chol_inv_factored<T>(w.G, l, Lp, Rt, w.Xinv, w.Rinv, w.flags, stream));
   BRSVD_TRY(gemm_an(P, Lp, rows, Lp, w.Rinv, Lp, tmp, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
-  BRSVD_TRY(apply_to_companion(w, Lp, stream));
-  float* res = nullptr;
-  BRSVD_TRY(cholqr_sweeps(tmp, P, rows, l, Lp, 1, w, nullptr, &res, stream));
+  BRSVD_TRY(apply_to_companion<T>(w, Lp, stream));
+  T* res = nullptr;
+  BRSVD_TRY(cholqr_sweeps<T>(tmp, P, rows, l, Lp, 1, w, nullptr, &res, stream, true));
   *result = res;
   if (Rtot) BRSVD_TRY(triu_mul(w.R[0], Rt, l, Lp, Rtot, stream));
   return BRSVD_OK;
 }
+
+template int tsqr_panel<float>(float*, float*, int64_t, int, int, OrthWorkT<float>&, double*, float**, hipStream_t);
+template int tsqr_panel<double>(double*, double*, int64_t, int, int, OrthWorkT<double>&, double*, double**,
+                                hipStream_t);
 
 }  // namespace brsvd

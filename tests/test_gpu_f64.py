@@ -1,0 +1,116 @@
+"""brsvd_run_f64: the whole path in double precision against the fp64 oracle on the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1706_07191_amd as B
+from oracle import brsvd_oracle as O
+from paper_1706_07191_amd import synth
+from tests.gpu_util import need_gpu, note
+
+pytestmark = pytest.mark.gpu
+
+# Both sides compute in fp64; they differ in summation order, in the orthonormaliser (CholeskyQR2 against
+# Householder) and in the small SVD (one-sided Jacobi with rotation threshold 1e-13 against LAPACK), so
+# agreement is limited by eps64 times the condition of the sketch panels, and the orthogonality of V =
+# W_B (R V_R / sigma) by the Jacobi threshold times sigma_1 / sigma_l (a few hundred here): observed
+# sigma 4e-15 .. 4e-14, U 2e-13 .. 7e-13, V 1e-12 .. 2e-11, reconstruction errors equal to 15 digits.
+SIGMA_RTOL64 = 1e-11
+ORTH_TOL64 = 1e-10
+RECON_RTOL64 = 1e-10
+
+
+def _run64(cfg, A, Om, b, **kw):
+    dev = need_gpu()
+    prm = B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=b, dtype=B.BRSVD_DTYPE_F64, **kw)
+    h = B.brsvd_create(prm)
+    try:
+        Ad = A if not A.is_cuda and kw.get("a_location") == B.BRSVD_A_HOST_PINNED else A.to(dev)
+        U, S, Vt, st = B.brsvd_run(h, Ad, Om.to(dev))
+        torch.cuda.synchronize()
+    finally:
+        B.brsvd_destroy(h)
+    return U, S, Vt, st
+
+
+def _check64(A, Om, cfg, b, U, S, Vt, tag, sig_tol=SIGMA_RTOL64):
+    An, On = A.numpy(), Om.numpy()
+    Uo, so, Vto = O.brsvd(An, On, cfg.k, cfg.p, cfg.q, row_block=b)
+    Ug, sg, Vg = U.cpu().numpy(), S.cpu().numpy(), Vt.cpu().numpy()
+    k = cfg.k
+    f = {"sigma_rel": float(np.max(np.abs(sg[:k] - so[:k]) / so[:k])), "orthU": O.orth_defect(Ug),
+         "orthV": O.orth_defect(Vg.T), "err_gpu": O.recon_error(An, Ug, sg, Vg, k=k),
+         "err_oracle": O.recon_error(An, Uo, so, Vto, k=k)}
+    note(f"[f64 {tag}] " + " ".join(f"{k_}={v:.3e}" for k_, v in f.items()))
+    assert U.dtype == torch.float64 and S.dtype == torch.float64
+    assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0)
+    assert f["sigma_rel"] <= sig_tol, f
+    assert f["orthU"] <= ORTH_TOL64 and f["orthV"] <= ORTH_TOL64, f
+    assert abs(f["err_gpu"] - f["err_oracle"]) <= RECON_RTOL64 * f["err_oracle"], f
+    return f
+
+
+def _inputs(name, m, n, b):
+    cfg = synth.CONFIGS[name].scaled(m, n, b)
+    A = cfg.make_A().double()                      # the fp32 recipe, widened: same matrix on both sides
+    A = A + 1e-9 * synth.gaussian(m, n, cfg.seed + 555, dtype=torch.float64)   # genuinely fp64 content
+    Om = synth.gaussian(n, cfg.l, cfg.seed + 556, dtype=torch.float64)
+    return cfg, A, Om
+
+
+@pytest.mark.parametrize("name,m,n,b", [("C1", 2000, 1000, 512), ("C2", 3000, 2500, 700), ("C3", 4000, 3000, 1024),
+                                         ("C4", 3000, 3500, 900), ("C1", 333, 271, 100)])
+def test_f64_scaled_configs(name, m, n, b):
+    cfg, A, Om = _inputs(name, m, n, b)
+    U, S, Vt, st = _run64(cfg, A, Om, b)
+    assert st["passes_over_A"] == 2 * cfg.q + 2 and st["orth_fallbacks"] == 0
+    assert st["bytes_A_streamed"] == st["passes_over_A"] * 8 * m * n
+    _check64(A, Om, cfg, b, U, S, Vt, f"{name} {m}x{n}")
+
+
+def test_f64_fused_tsqr_and_streaming():
+    cfg, A, Om = _inputs("C4", 2600, 1500, 640)
+    U, S, Vt, st = _run64(cfg, A, Om, 640, pass_mode=B.BRSVD_PASSES_FUSED)
+    assert st["passes_over_A"] == cfg.q + 1
+    _check64(A, Om, cfg, 640, U, S, Vt, "fused", sig_tol=1e-9)
+    U, S, Vt, st = _run64(cfg, A, Om, 640, orth_method=B.BRSVD_ORTH_TSQR)
+    _check64(A, Om, cfg, 640, U, S, Vt, "tsqr")
+    Ah = A.pin_memory()
+    U, S, Vt, st = _run64(cfg, Ah, Om, 640, a_location=B.BRSVD_A_HOST_PINNED)
+    assert st["copy_seconds"] > 0 and st["n_blocks"] == 5
+    _check64(A, Om, cfg, 640, U, S, Vt, "host")
+
+
+def test_f64_exact_rank_reaches_double_precision_error():
+    """The paper reports an approximation error of 1e-15 in double precision on exactly rank-k inputs."""
+    r, k, p = 12, 16, 8
+    s = torch.linspace(10.0, 1.0, r, dtype=torch.float64)
+    A = synth.exact_spectrum_matrix(1500, 900, s, seed=77, dtype=torch.float64)
+    Om = synth.gaussian(900, k + p, 78, dtype=torch.float64)
+    cfg = synth.Config("rank", 1500, 900, k, p, 1, 400, r, lambda i: i, 0.0, 0)
+    U, S, Vt, st = _run64(cfg, A, Om, 400)
+    sg = S.cpu().numpy()
+    assert np.max(np.abs(sg[:r] - s.numpy()) / s.numpy()) < 1e-13
+    err = O.recon_error(A.numpy(), U.cpu().numpy(), sg, Vt.cpu().numpy())
+    note(f"[f64 exact rank] err={err:.3e} fallbacks={st['orth_fallbacks']}")
+    assert err < 1e-13
+    assert O.orth_defect(U.cpu().numpy()) <= 1e-10
+
+
+def test_f64_dtype_mismatch_is_rejected():
+    dev = need_gpu()
+    cfg, A, Om = _inputs("C1", 300, 200, 100)
+    h64 = B.brsvd_create(B.make_params(300, 200, cfg.k, cfg.p, cfg.q, dtype=B.BRSVD_DTYPE_F64))
+    h32 = B.brsvd_create(B.make_params(300, 200, cfg.k, cfg.p, cfg.q))
+    try:
+        with pytest.raises(B.BrsvdError):
+            B.brsvd_run(h64, A.float().to(dev), Om.float().to(dev))
+        with pytest.raises(B.BrsvdError):
+            B.brsvd_run(h32, A.to(dev), Om.to(dev))
+        with pytest.raises(B.BrsvdError):
+            B.brsvd_run_alg2(h64, A.float().to(dev), cfg.l)
+        with pytest.raises(B.BrsvdError):
+            B.brsvd_create(B.make_params(300, 200, cfg.k, cfg.p, cfg.q, dtype=7))
+    finally:
+        B.brsvd_destroy(h64)
+        B.brsvd_destroy(h32)
