@@ -3,7 +3,7 @@
   python -m paper_1706_07191_amd.sweep gemm   [--shape MxN ...] [--l L ...]
       the two pass kernels alone, one launch over all of A: ms, Tflop/s and GB/s of the algorithmic
       bytes 4*m*n + 4*(m+n)*l.  Narrow panels (l <= 32) are the HBM-bound side of the ridge.
-  python -m paper_1706_07191_amd.sweep shapes [--family tall|square] [--gb G ...] [--q Q] [--p P]
+  python -m paper_1706_07191_amd.sweep shapes [--family tall|square] [--gb G ...] [--q Q] [--p P] [--dtype f32|f64]
       whole rank-k BRSVDs over growing inputs at the two aspect ratios of the paper's Fig. 2
       (tall-skinny m:n:k = 1024:32:1, square m:n:k = 256:256:1): seconds, Tflop/s with the flop
       count of the paper's Table 1 terms written out, 2*m*n*l*(2q+2) for the passes plus
@@ -36,16 +36,16 @@ def _time_ms(fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def _gaussian_product(m, n, r, dev, seed):
+def _gaussian_product(m, n, r, dev, seed, dtype):
     import torch
     g = torch.Generator(device=dev)
     g.manual_seed(seed)
-    A = torch.empty(m, n, device=dev)
-    G2 = torch.randn(r, n, device=dev, generator=g)
-    step = max(1, (1 << 28) // max(n, 1))
+    A = torch.empty(m, n, device=dev, dtype=dtype)
+    G2 = torch.randn(r, n, device=dev, generator=g, dtype=dtype)
+    step = max(1, (1 << 27) // max(n, 1))
     for r0 in range(0, m, step):
         r1 = min(m, r0 + step)
-        A[r0:r1] = torch.randn(r1 - r0, r, device=dev, generator=g) @ G2
+        A[r0:r1] = torch.randn(r1 - r0, r, device=dev, generator=g, dtype=dtype) @ G2
     return A
 
 
@@ -79,19 +79,22 @@ def sweep_shapes(args):
     import paper_1706_07191_amd as B
     dev = torch.device("cuda:0")
     fams = {"tall": (1024, 32), "square": (256, 256)}
+    f64 = args.dtype == "f64"
+    tdt, esz = (torch.float64, 8) if f64 else (torch.float32, 4)
     for fam in args.family:
         rm, rn = fams[fam]
         for gb in args.gb:
-            # m = rm*k, n = rn*k with 4*m*n = gb * 1e9 bytes
-            k = max(2, int(round((gb * 1e9 / 4.0 / (rm * rn)) ** 0.5)))
+            # m = rm*k, n = rn*k with esz*m*n = gb * 1e9 bytes
+            k = max(2, int(round((gb * 1e9 / esz / (rm * rn)) ** 0.5)))
             m, n, p, q = rm * k, rn * k, args.p, args.q
             l = k + p
             if l > min(m, n, 512):
                 print(json.dumps({"family": fam, "gb": gb, "skipped": f"l = {l} exceeds min(m, n, 512)"}), flush=True)
                 continue
-            A = _gaussian_product(m, n, k, dev, 1000 + k)
-            Om = torch.randn(n, l, device=dev)
-            h = B.brsvd_create(B.make_params(m, n, k, p, q, row_block=0))
+            A = _gaussian_product(m, n, k, dev, 1000 + k, tdt)
+            Om = torch.randn(n, l, device=dev, dtype=tdt)
+            h = B.brsvd_create(B.make_params(m, n, k, p, q, row_block=0,
+                                             dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32))
             try:
                 B.brsvd_run(h, A, Om, want_stats=False)
                 best = None
@@ -105,7 +108,8 @@ def sweep_shapes(args):
             flops = 2.0 * m * n * l * (2 * q + 2) + 2.0 * (m + n) * l * l * (sweeps + 1)
             t = best["total_seconds"]
             err = float(torch.linalg.norm(A[:4096] - (U[:4096] * S) @ Vt) / torch.linalg.norm(A[:4096]))
-            print(json.dumps({"family": fam, "m": m, "n": n, "k": k, "p": p, "q": q, "bytes_A_GB": round(4.0 * m * n / 1e9, 3),
+            print(json.dumps({"family": fam, "dtype": args.dtype, "m": m, "n": n, "k": k, "p": p, "q": q,
+                              "bytes_A_GB": round(float(esz) * m * n / 1e9, 3),
                               "seconds": round(t, 6), "tflops": round(flops / t / 1e12, 2),
                               "A_GBps": round(best["bytes_A_streamed"] / t / 1e9, 1),
                               "share": {key[:-8]: round(best[key] / t, 3) for key in
@@ -168,6 +172,7 @@ def main(argv=None) -> int:
     s.add_argument("--p", type=int, default=10)
     s.add_argument("--q", type=int, default=1)
     s.add_argument("--reps", type=int, default=3)
+    s.add_argument("--dtype", default="f32", choices=["f32", "f64"])
     r = sub.add_parser("rpca")
     r.add_argument("--shape", nargs="+", default=["76800x2000", "2073600x100", "32256x2383"])
     r.add_argument("--iters", type=int, default=30)
