@@ -1,4 +1,5 @@
-// Thin-panel GEMMs of the randomized range finder on fp32 MFMA (gfx950, wave64).
+// Thin-panel GEMMs of the randomized range finder on the matrix cores (gfx950, wave64): fp32 on
+// v_mfma_f32_16x16x4_f32 and, from the same templates, fp64 on v_mfma_f64_16x16x4_f64.
 //
 //   gemm_an:  Y_I = A_I * X        sketch Y = A*Omega and the power step Y = A*W
 //                                  (Alg. 1 step 2, Alg. 2 line 4, Eq. (4) right-to-left order)
@@ -9,11 +10,11 @@
 // A-operand registers (no LDS round trip for A), while the thin panel (X or Q) is staged
 // through a double-buffered LDS tile shared by the waves of a workgroup.
 //
-// MFMA used: v_mfma_f32_16x16x4_f32.  Operand layout (lane = 16*g + r, g = 0..3, r = 0..15):
+// Operand layout of both instructions (lane = 16*g + r, g = 0..3, r = 0..15):
 //   A operand: lane holds a[i = r][k = g];  B operand: lane holds b[k = g][j = r];
-//   D: lane holds d[i = 4*g + v][j = r] in component v = 0..3.
-// Because the contraction index may be visited in any order, a lane's float4 of four
-// consecutive k (gemm_an) or four consecutive columns (gemm_at) feeds four MFMAs directly.
+//   D: lane holds d[i = 4*g + v][j = r] (fp32) or d[i = g + 4*v][j = r] (fp64) in component v = 0..3.
+// Because the contraction index may be visited in any order, a lane's vector of four
+// consecutive k (gemm_an) or of MT consecutive columns (gemm_at) feeds that many MFMAs directly.
 #include <algorithm>
 #include <cmath>
 #include <cstdio>

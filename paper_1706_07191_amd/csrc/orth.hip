@@ -227,14 +227,14 @@ __device__ __forceinline__ void trailing_tile(double* M, int64_t ld, const doubl
 template <bool IN_LDS, typename TO>
 __global__ void __launch_bounds__(1024)
 k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, double* __restrict__ Xtmp,
-           TO* __restrict__ Rinv32, int* __restrict__ flag, double tol, int factored, int lenient) {
+           TO* __restrict__ Rinv_out, int* __restrict__ flag, double tol, int factored, int lenient) {
   extern __shared__ double smem[];
   __shared__ int bad;
   double* Rkk = smem;                 // 16 x 17
   double* d0 = smem + 16 * 17;        // kMaxL
   double* rest = d0 + kMaxL;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < Lp * Lp; i += 1024) Rinv32[i] = TO(0);
+  for (int i = tid; i < Lp * Lp; i += 1024) Rinv_out[i] = TO(0);
   if (flag[0] != 0) return;           // an earlier panel already broke down: results are void anyway
   double* M;
   int ld;
@@ -424,7 +424,7 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   }
   for (int idx = tid; idx < l * l; idx += 1024) {
     int i = idx / l, c = idx - i * l;
-    if (c >= i) Rinv32[(int64_t)i * Lp + c] = (TO)M[(int64_t)i * ld + c];
+    if (c >= i) Rinv_out[(int64_t)i * Lp + c] = (TO)M[(int64_t)i * ld + c];
   }
 }
 
