@@ -478,13 +478,13 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
   if (l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
   const double tol = 1e-13;
   if (l <= kJacobiLdsMaxL) {
-    // 16 lanes per pair measured faster than 8 (1.12 vs 1.23 ms at l = 110): with 16 waves the
-    // instruction streams hide each other's latency better than 8 longer ones do.
+    // Lanes per pair: 16 for l <= 96; above that 8 (fewer, longer instruction streams: the per-pair
+    // rotation arithmetic and reductions are issued half as often; 0.88 against 0.92 ms at l = 110).
     if (l <= 32) BRSVD_TRY((launch_jacobi_lds<2, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
     else if (l <= 64) BRSVD_TRY((launch_jacobi_lds<4, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
     else if (l <= 96) BRSVD_TRY((launch_jacobi_lds<6, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
-    else if (l <= 112) BRSVD_TRY((launch_jacobi_lds<7, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
-    else BRSVD_TRY((launch_jacobi_lds<8, 16>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else if (l <= 112) BRSVD_TRY((launch_jacobi_lds<14, 8>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
+    else BRSVD_TRY((launch_jacobi_lds<16, 8>(R, ldr, l, Lp, w, breakdown_flag, tol, stream)));
   } else {
     // Host-driven sweeps: the convergence flag is read back once per sweep.
     int* rotated = w.info + 2;
