@@ -64,7 +64,10 @@ typedef struct {
   void* copy_stream;            /* hipStream_t for host->device block copies (host-resident A);
                                    NULL = the library creates one (default priority)           */
   int32_t dtype;                /* BRSVD_DTYPE_*                                               */
-  int32_t reserved;             /* must be 0                                                   */
+  int32_t timing_level;         /* which phases brsvd_stats times (each timed phase costs two event
+                                   records on the stream, about 0.1 ms per call in all):
+                                   0 = every phase; 1 = pass kernels, copies and the total only,
+                                   the other *_seconds fields stay 0                              */
 } brsvd_params;
 
 /* Timings are measured with HIP events recorded on compute_stream (copy_stream for the

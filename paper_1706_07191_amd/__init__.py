@@ -38,7 +38,7 @@ class brsvd_params(C.Structure):
                 ("row_block", C.c_int64), ("device_budget_bytes", C.c_uint64),
                 ("orth_method", C.c_int32), ("pass_mode", C.c_int32),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
-                ("dtype", C.c_int32), ("reserved", C.c_int32)]
+                ("dtype", C.c_int32), ("timing_level", C.c_int32)]
 
 
 class brsvd_stats(C.Structure):
@@ -138,12 +138,12 @@ def _dev(t, dtype, name):
 
 def make_params(m, n, k, p, q, row_block=0, device_budget_bytes=0, a_location=BRSVD_A_DEVICE,
                 orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None,
-                pass_mode=BRSVD_PASSES_SEPARATE, dtype=BRSVD_DTYPE_F32) -> brsvd_params:
+                pass_mode=BRSVD_PASSES_SEPARATE, dtype=BRSVD_DTYPE_F32, timing_level=0) -> brsvd_params:
     return brsvd_params(m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
                         device_budget_bytes=device_budget_bytes, orth_method=orth_method, pass_mode=pass_mode,
                         compute_stream=_stream_ptr(compute_stream),
                         copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None,
-                        dtype=dtype, reserved=0)
+                        dtype=dtype, timing_level=timing_level)
 
 
 def brsvd_workspace_bytes(params: brsvd_params) -> int:

@@ -76,6 +76,7 @@ int validate(const brsvd_params* p) {
   if (p->row_block < 0) return BRSVD_ERR_ARG;
   if (p->pass_mode != BRSVD_PASSES_SEPARATE && p->pass_mode != BRSVD_PASSES_FUSED) return BRSVD_ERR_ARG;
   if (p->dtype != BRSVD_DTYPE_F32 && p->dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  if (p->timing_level != 0 && p->timing_level != 1) return BRSVD_ERR_ARG;
   return BRSVD_OK;
 }
 
@@ -171,6 +172,8 @@ struct Region {
   int i0;
   Region(brsvd_handle h_, int cat_, hipStream_t s_) : h(h_), cat(cat_), s(s_), i0(-1) {
     if (!h->timing || h->ev_used + 2 > h->ev.size()) return;
+    // timing_level 1: only the pass kernels, the copies and the whole call are timed
+    if (h->prm.timing_level == 1 && cat != CAT_TOTAL && cat != CAT_COPY) return;
     i0 = (int)h->ev_used;
     h->ev_used += 2;
     (void)hipEventRecord(h->ev[i0], s);

@@ -47,7 +47,8 @@ def _p(**kw):
 
 
 @pytest.mark.parametrize("bad", [dict(m=0), dict(n=-1), dict(k=0), dict(p=-1), dict(q=-1),
-                                 dict(k=600, p=0), dict(m=20, n=1000), dict(row_block=-5), dict(pass_mode=7)])
+                                 dict(k=600, p=0), dict(m=20, n=1000), dict(row_block=-5), dict(pass_mode=7), dict(dtype=5),
+                                 dict(timing_level=3)])
 def test_invalid_params_rejected(bad):
     out = C.c_uint64(0)
     assert B.lib().brsvd_workspace_bytes(C.byref(_p(**bad)), C.byref(out)) == B.BRSVD_ERR_ARG
