@@ -111,7 +111,7 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   L.gemm_scratch = take(gs);
   L.gram_chunks = (int)std::max(orth_gram_slots(m, Lp), orth_gram_slots(n, Lp));
   L.gram_part = take((uint64_t)L.gram_chunks * Lp * Lp * 8);
-  const uint64_t sq8 = (uint64_t)Lp * Lp * 8, sq4 = (uint64_t)Lp * Lp * 4;
+  const uint64_t sq8 = (uint64_t)Lp * Lp * 8;
   L.G = take(sq8); L.R0 = take(sq8); L.R1 = take(sq8); L.Xinv = take(sq8); L.Rtot = take(sq8);
   const uint64_t sqe = (uint64_t)Lp * Lp * esz;
   L.Rinv = take(sqe); L.XV = take(sqe); L.XU = take(sqe);

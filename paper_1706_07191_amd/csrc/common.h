@@ -105,7 +105,7 @@ int orth_panel(T* P, T* tmp, int64_t rows, int l, int Lp, int method, bool final
 // Pieces shared between the CholeskyQR and the Householder-tree routes (orth.hip, tsqr.hip).
 template <typename T>
 int cholqr_sweeps(T* P, T* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWorkT<T>& w, double* Rtot,
-                  T** result, hipStream_t stream, bool strict_last);
+                  T** result, hipStream_t stream, bool strict_last, bool publish_R = false);
 template <typename T>
 int chol_inv_factored(double* G, int l, int Lp, double* Rout, double* Xtmp, T* Rinv, int* flags, hipStream_t stream);
 template <typename T>

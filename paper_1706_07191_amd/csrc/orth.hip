@@ -234,7 +234,6 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   double* d0 = smem + 16 * 17;        // kMaxL
   double* rest = d0 + kMaxL;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < Lp * Lp; i += 1024) Rinv_out[i] = TO(0);
   if (flag[0] != 0) return;           // an earlier panel already broke down: results are void anyway
   double* M;
   int ld;
@@ -315,116 +314,92 @@ k_chol_inv(double* __restrict__ G, int l, int Lp, double* __restrict__ Rout, dou
   }
 
   // ---- publish R ----
-  for (int idx = tid; idx < l * l; idx += 1024) {
-    int i = idx / l, c = idx - i * l;
-    Rout[(int64_t)i * Lp + c] = c >= i ? M[(int64_t)i * ld + c] : 0.0;
+  if (Rout) {
+    for (int idx = tid; idx < l * l; idx += 1024) {
+      int i = idx / l, c = idx - i * l;
+      Rout[(int64_t)i * Lp + c] = c >= i ? M[(int64_t)i * ld + c] : 0.0;
+    }
   }
   __syncthreads();
 
-  // ---- inverse, level 0: diagonal blocks, one wave each ----
-  const int nblk = (l + kNB - 1) / kNB;
-  for (int bi = wave; bi < nblk; bi += 16) inv_diag_wave(M, ld, bi * kNB, min(kNB, l - bi * kNB), lane);
+  // ---- inverse, level 0: diagonal blocks, one wave each (the padding block is an identity) ----
+  const int nblk = Lp / kNB;
+  for (int bi = wave; bi < nblk; bi += 16) inv_diag_wave(M, ld, bi * kNB, kNB, lane);
   __syncthreads();
-  // ---- merge levels: X12 = -X11 (R12 X22).  T = R12 X22 is staged in registers (LDS variant:
-  // at most one 4 x 4 tile per thread per level) or in the global scratch Xtmp, so that the
-  // update can be done in place. ----
-  for (int B = kNB; B < l; B *= 2) {
-    const int npair = (l + 2 * B - 1) / (2 * B);
-    const int tr = B / 4, tc_full = B / 4, per = tr * tc_full;
-    int total = 0;
-    for (int p = 0; p < npair; ++p) {
-      int a = 2 * B * p, w = min(a + 2 * B, l) - (a + B);
-      if (w > 0) total += tr * ((w + 3) / 4);
-    }
-    for (int phase = 0; phase < 2; ++phase) {
-      double keep[4][4];
-      bool have = false;
-      int kr0 = 0, kc0 = 0;
-      for (int idx = tid; idx < total; idx += 1024) {
-        // tile -> (pair, tile row, tile column); only the last pair can be narrower than B
-        const int p = idx / per, rem = idx - p * per;
-        const int a0 = 2 * B * p;
-        const int w = min(a0 + 2 * B, l) - (a0 + B);
-        const int tcw = (p == npair - 1) ? (w + 3) / 4 : tc_full;
-        const int ti = rem / tcw, tj = rem - ti * tcw;
-        const int r0 = a0 + 4 * ti, c0 = a0 + B + 4 * tj;
-        double acc[4][4];
+  // ---- merge levels on the fp64 matrix cores: X12 = -X11 (R12 X22), tile by tile.  A pair at level B
+  // (in tiles) joins the inverted blocks [a0, a0+B) and [a0+B, a0+B+w).  Phase 0 forms T = R12 X22
+  // (X22 upper triangular: tiles tk <= tj), phase 1 forms X12 = -X11 T (tiles tk >= ti).  Diagonal tiles
+  // of X11 / X22 are masked to their upper triangle (their lower part holds leftovers of the trailing
+  // updates).  LDS variant: at most 16 tiles per phase, one per wave, held in registers until every
+  // wave has finished reading, then written in place.  Global variant: T goes to the scratch Xtmp. ----
+  {
+    const int r = lane & 15, g = lane >> 4;
+    for (int B = 1; B < nblk; B *= 2) {
+      const int npair = (nblk + 2 * B - 1) / (2 * B);
+      for (int phase = 0; phase < 2; ++phase) {
+        doublex4 keep = {0.0, 0.0, 0.0, 0.0};
+        int kr0 = -1, kc0 = 0;
+        int tile = 0;                                   // running tile index over all pairs of this level
+        for (int p = 0; p < npair; ++p) {
+          const int a0 = 2 * B * p;                     // in tiles
+          const int w = min(a0 + 2 * B, nblk) - (a0 + B);
+          if (w <= 0) continue;
+          for (int t = 0; t < B * w; ++t, ++tile) {
+            if ((tile & 15) != wave) continue;
+            const int ti = t / w, tj = t - ti * w;      // tile row within the left block, tile column within the right
+            const int r0 = (a0 + ti) * kNB, c0 = (a0 + B + tj) * kNB;
+            doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+            if (phase == 0) {
+              for (int tk = 0; tk <= tj; ++tk) {
+                const int k0 = (a0 + B + tk) * kNB;
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+                for (int kk = 0; kk < 4; ++kk) {
+                  const int k = 4 * kk + g;
+                  const double av = M[(int64_t)(r0 + r) * ld + k0 + k];                       // R12[i = r][k]
+                  double bv = M[(int64_t)(k0 + k) * ld + c0 + r];                             // X22[k][j = r]
+                  if (tk == tj && k > r) bv = 0.0;
+                  acc = mfma_f64(av, bv, acc);
+                }
+              }
+            } else {
+              const double* Tm = IN_LDS ? M : Xtmp;
+              const int64_t ldt = IN_LDS ? ld : Lp;
+              for (int tk = ti; tk < B; ++tk) {
+                const int k0 = (a0 + tk) * kNB;
 #pragma unroll
-          for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
-        if (phase == 0) {
-          // T[i][j] = sum_{t <= j} R12[i][t] X22[t][j]
-#pragma unroll 4
-          for (int t = a0 + B; t < min(c0 + 4, l); ++t) {
-            double av[4], bv[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-              av[a] = M[(int64_t)(r0 + a) * ld + t];
-              bv[a] = (c0 + a < l && t <= c0 + a) ? M[(int64_t)t * ld + c0 + a] : 0.0;
+                for (int kk = 0; kk < 4; ++kk) {
+                  const int k = 4 * kk + g;
+                  double av = M[(int64_t)(r0 + r) * ld + k0 + k];                             // X11[i = r][k]
+                  if (tk == ti && r > k) av = 0.0;
+                  const double bv = Tm[(int64_t)(k0 + k) * ldt + c0 + r];                     // T[k][j = r]
+                  acc = mfma_f64(-av, bv, acc);
+                }
+              }
             }
+            // accumulator component v of lane (r, g) is entry [g + 4 v][r] of the tile
+            if (IN_LDS) {
+              keep = acc; kr0 = r0; kc0 = c0;
+            } else {
+              double* dst = phase == 0 ? Xtmp : M;
+              const int64_t ldd = phase == 0 ? Lp : ld;
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-              for (int b = 0; b < 4; ++b) acc[a][b] = fma(av[a], bv[b], acc[a][b]);
-          }
-        } else {
-          // X12[i][j] = -sum_{t >= i} X11[i][t] T[t][j]
-          const double* Tm = IN_LDS ? M : Xtmp;
-          const int ldt = IN_LDS ? ld : Lp;
-#pragma unroll 4
-          for (int t = r0; t < a0 + B; ++t) {
-            double av[4], bv[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-              av[a] = (t >= r0 + a) ? M[(int64_t)(r0 + a) * ld + t] : 0.0;
-              bv[a] = (c0 + a < l) ? Tm[(int64_t)t * ldt + c0 + a] : 0.0;
+              for (int v = 0; v < 4; ++v) dst[(int64_t)(r0 + g + 4 * v) * ldd + c0 + r] = acc[v];
             }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-              for (int b = 0; b < 4; ++b) acc[a][b] = fma(-av[a], bv[b], acc[a][b]);
           }
         }
-        if (IN_LDS || phase == 1) {
-          // in place: hold the tile until every thread has finished reading (total <= 1024 here
-          // for the LDS variant, so each thread holds at most one tile); phase 1 of the global
-          // variant reads T from Xtmp and X11 from M, and writes the X12 region nobody reads
-          if (IN_LDS) {
+        __syncthreads();
+        if (IN_LDS && kr0 >= 0) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-              for (int b = 0; b < 4; ++b) keep[a][b] = acc[a][b];
-            have = true; kr0 = r0; kc0 = c0;
-          } else {
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-              for (int b = 0; b < 4; ++b)
-                if (c0 + b < l) M[(int64_t)(r0 + a) * ld + c0 + b] = acc[a][b];
-          }
-        } else {
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-              if (c0 + b < l) Xtmp[(int64_t)(r0 + a) * Lp + c0 + b] = acc[a][b];
+          for (int v = 0; v < 4; ++v) M[(int64_t)(kr0 + g + 4 * v) * ld + kc0 + r] = keep[v];
         }
+        __syncthreads();
       }
-      __syncthreads();
-      if (IN_LDS && have) {
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-          for (int b = 0; b < 4; ++b)
-            if (kc0 + b < l) M[(int64_t)(kr0 + a) * ld + kc0 + b] = keep[a][b];
-      }
-      __syncthreads();
     }
   }
-  for (int idx = tid; idx < l * l; idx += 1024) {
-    int i = idx / l, c = idx - i * l;
-    if (c >= i) Rinv_out[(int64_t)i * Lp + c] = (TO)M[(int64_t)i * ld + c];
+  // R^-1 in the panels' type, zero below the diagonal and in the padding
+  for (int idx = tid; idx < Lp * Lp; idx += 1024) {
+    const int i = idx / Lp, c = idx - i * Lp;
+    Rinv_out[idx] = (i < l && c < l && c >= i) ? (TO)M[(int64_t)i * ld + c] : TO(0);
   }
 }
 
@@ -556,14 +531,15 @@ int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hi
 // power step treats like any other direction; P = Q R holds exactly either way.
 template <typename T>
 int cholqr_sweeps(T* P, T* tmp, int64_t rows, int l, int Lp, int nsweeps, OrthWorkT<T>& w, double* Rtot,
-                  T** result, hipStream_t stream, bool strict_last) {
+                  T** result, hipStream_t stream, bool strict_last, bool publish_R) {
   const double tol = 1e-12;
   T* src = P;
   T* dst = tmp;
   for (int sweep = 0; sweep < nsweeps; ++sweep) {
     BRSVD_TRY(gram<T>(src, rows, Lp, w, stream));
     const int lenient = (sweep + 1 < nsweeps || !strict_last) ? 1 : 0;
-    BRSVD_TRY(chol_inv<T>(w.G, l, Lp, w.R[sweep], w.Xinv, w.Rinv, w.flags, tol, stream, 0, lenient));
+    double* Rs = (Rtot || publish_R) ? w.R[sweep] : nullptr;      // the factor is only written out when someone reads it
+    BRSVD_TRY(chol_inv<T>(w.G, l, Lp, Rs, w.Xinv, w.Rinv, w.flags, tol, stream, 0, lenient));
     BRSVD_TRY(gemm_an(src, Lp, rows, Lp, w.Rinv, Lp, dst, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
     BRSVD_TRY(apply_to_companion<T>(w, Lp, stream));
     T* t = src; src = dst; dst = t;
@@ -593,7 +569,8 @@ int orth_panel(T* P, T* tmp, int64_t rows, int l, int Lp, int method, bool final
 #define BRSVD_ORTH_INSTANTIATE(T)                                                                               \
   template int chol_inv_factored<T>(double*, int, int, double*, double*, T*, int*, hipStream_t);                \
   template int apply_to_companion<T>(OrthWorkT<T>&, int, hipStream_t);                                          \
-  template int cholqr_sweeps<T>(T*, T*, int64_t, int, int, int, OrthWorkT<T>&, double*, T**, hipStream_t, bool); \
+  template int cholqr_sweeps<T>(T*, T*, int64_t, int, int, int, OrthWorkT<T>&, double*, T**, hipStream_t, bool, \
+                                bool);                                                                          \
   template int orth_panel<T>(T*, T*, int64_t, int, int, int, bool, OrthWorkT<T>&, double*, T**, hipStream_t);
 BRSVD_ORTH_INSTANTIATE(float)
 BRSVD_ORTH_INSTANTIATE(double)

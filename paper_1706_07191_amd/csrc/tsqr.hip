@@ -144,7 +144,7 @@ int tsqr_panel(T* P, T* tmp, int64_t rows, int l, int Lp, OrthWorkT<T>& w, doubl
   BRSVD_TRY(gemm_an(P, Lp, rows, Lp, w.Rinv, Lp, tmp, Lp, Lp, w.gemm_scratch, w.gemm_scratch_bytes, stream));
   BRSVD_TRY(apply_to_companion<T>(w, Lp, stream));
   T* res = nullptr;
-  BRSVD_TRY(cholqr_sweeps<T>(tmp, P, rows, l, Lp, 1, w, nullptr, &res, stream, true));
+  BRSVD_TRY(cholqr_sweeps<T>(tmp, P, rows, l, Lp, 1, w, nullptr, &res, stream, true, Rtot != nullptr));
   *result = res;
   if (Rtot) BRSVD_TRY(triu_mul(w.R[0], Rt, l, Lp, Rtot, stream));
   return BRSVD_OK;
