@@ -129,45 +129,50 @@ __device__ __forceinline__ double rcp_fast(double x) {
   return y;
 }
 
-// Wave-level Cholesky of the nb x nb diagonal block at (kb, kb): lane c (mod 16) keeps column c in
-// registers, pivots and row entries travel by shuffles.  Writes R_kk back and into Rkk (16 x 17).
-__device__ bool chol_diag_wave(double* M, int ld, int kb, int nb, const double* d0, double tol,
+// Wave-level Cholesky of the 16 x 16 diagonal block at (kb, kb).  The tile sits in the MFMA
+// accumulator layout (lane (r, g), component v = entry [g + 4 v][r]), so that the four rows 4p .. 4p+3 of
+// a panel are one register across the wave.  Per panel: the four rows are gathered into every lane
+// (lane r keeps column r of them), factored in four pivot steps with lane broadcasts, and the rest of
+// the tile receives their rank-4 update as a single v_mfma_f64_16x16x4_f64 with the panel as both
+// operands.  Pivots at or below tol * (original diagonal) are clamped (see k_chol_inv); returns false
+// if that happened.  Writes R_kk into M (upper part) and into Rkk (16 x 17, spare column = 1/diagonal).
+__device__ bool chol_diag_wave(double* M, int64_t ld, int kb, int nb, const double* d0, double tol,
                                double* Rkk, int lane) {
-  const int c = lane & 15;
-  double col[kNB];
+  (void)nb;
+  const int r = lane & 15, g = lane >> 4;
+  doublex4 t;
 #pragma unroll
-  for (int i = 0; i < kNB; ++i)
-    col[i] = (i < nb && c < nb) ? (i <= c ? M[(int64_t)(kb + i) * ld + kb + c] : 0.0) : (i == c ? 1.0 : 0.0);
+  for (int v = 0; v < 4; ++v) t[v] = M[(int64_t)(kb + g + 4 * v) * ld + kb + r];
   bool ok = true;
 #pragma unroll
-  for (int j = 0; j < kNB; ++j) {
-    double d = shfl_d(col[j], j);
-    if (j < nb) {
-      // a pivot at or below the threshold is replaced by the threshold (the factor is then that of G
-      // plus a small diagonal bump): R stays finite and P R^-1 cannot blow up; the caller decides
-      // whether such a panel is acceptable
+  for (int p4 = 0; p4 < 4; ++p4) {
+    const int jb = 4 * p4;
+    double pr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double x = __shfl(t[p4], 16 * i + r, 64);           // entry [jb + i][r]
+      pr[i] = r >= jb + i ? x : 0.0;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = jb + i;
+      double d = shfl_d(pr[i], j);
       const double floor_ = tol * d0[kb + j];
       if (!(d > floor_)) { ok = false; d = floor_ > 0.0 ? floor_ : 1.0; }   // an all-zero column keeps R_jj = 1
-    }
-    const double inv = d > 0.0 ? rsqrt_fast(d) : 0.0;
-    const double rj = (c > j) ? col[j] * inv : (c == j ? d * inv : 0.0);
-    col[j] = rj;
+      const double inv = rsqrt_fast(d);
+      const double ri = r > j ? pr[i] * inv : (r == j ? d * inv : 0.0);
+      pr[i] = ri;
 #pragma unroll
-    for (int r = j + 1; r < kNB; ++r) {
-      const double rjr = shfl_d(rj, r);
-      if (c >= r) col[r] -= rjr * rj;
+      for (int i2 = i + 1; i2 < 4; ++i2) {
+        const double s = shfl_d(ri, jb + i2);
+        if (r >= jb + i2) pr[i2] -= s * ri;
+      }
     }
-  }
-  if (lane < kNB) {
-#pragma unroll
-    for (int i = 0; i < kNB; ++i) {
-      Rkk[i * 17 + c] = col[i];
-      if (i <= c && c < nb) M[(int64_t)(kb + i) * ld + kb + c] = col[i];
-    }
-    double dv = 1.0;
-#pragma unroll
-    for (int i = 0; i < kNB; ++i) dv = (i == c) ? col[i] : dv;
-    Rkk[c * 17 + 16] = rcp_fast(dv);          // 1 / R[c][c] in the spare column, for the panel solve
+    const double rowv = g == 0 ? pr[0] : (g == 1 ? pr[1] : (g == 2 ? pr[2] : pr[3]));   // row jb + g, column r
+    if (r >= jb + g) M[(int64_t)(kb + jb + g) * ld + kb + r] = rowv;
+    Rkk[(jb + g) * 17 + r] = rowv;
+    if (r == jb + g) Rkk[(jb + g) * 17 + 16] = rcp_fast(rowv);    // 1 / R[j][j] in the spare column, for the panel solve
+    if (p4 < 3) t = mfma_f64(-rowv, rowv, t);
   }
   return ok;
 }
