@@ -14,6 +14,11 @@
       given shape (default: configuration 5 and the two shapes of the paper's Table 2): iterations,
       seconds, per-phase milliseconds per iteration and the GB/s of the pass and elementwise kernels.
 
+  python -m paper_1706_07191_amd.sweep stream [--rows M] [--modes separate fused alg2]
+      configuration 4 (A fp32 M x 100000 in pinned host memory, k = 128, p = 16, q = 1, blocks of 16384 rows
+      through two staging buffers, 16 GB device budget): seconds per BRSVD, GB/s of A over the host link and the
+      fraction of a plain pinned copy of one block measured in the same run.  M defaults to 160000 (64 GB).
+
 Every line of output is one JSON object.
 """
 from __future__ import annotations
@@ -159,6 +164,58 @@ def sweep_rpca(args):
         del D, L0, S0, Om, L, S, work
 
 
+def sweep_stream(args):
+    import torch
+
+    import paper_1706_07191_amd as B
+    from paper_1706_07191_amd import synth
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["C4"]
+    if args.rows != cfg.m:
+        cfg = cfg.scaled(args.rows, cfg.n)
+    pm = B.PinnedMatrix(cfg.m, cfg.n)
+    Ap = pm.tensor
+    cfg.make_A(device="cpu", out=Ap, gen_device=dev)
+    Om = cfg.make_Omega(device=dev)
+    blk = torch.empty(cfg.row_block, cfg.n, device=dev)
+    h2d = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        blk.copy_(Ap[:cfg.row_block], non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        h2d = max(h2d, blk.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del blk
+    for mode in args.modes:
+        prm = B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, a_location=B.BRSVD_A_HOST_PINNED,
+                            device_budget_bytes=cfg.device_budget,
+                            pass_mode=B.BRSVD_PASSES_FUSED if mode == "fused" else B.BRSVD_PASSES_SEPARATE)
+        h = B.brsvd_create(prm)
+        try:
+            best = None
+            for _ in range(args.reps):
+                if mode == "alg2":
+                    U, S, Vt, st = B.brsvd_run_alg2(h, Ap, cfg.l, seed=777, pinned=True)
+                else:
+                    U, S, Vt, st = B.brsvd_run(h, Ap, Om, pinned=True)
+                if best is None or st["total_seconds"] < best["total_seconds"]:
+                    best = st
+        finally:
+            B.brsvd_destroy(h)
+        t = best["total_seconds"]
+        orth = float(torch.linalg.matrix_norm(U.double().T @ U.double() - torch.eye(cfg.l, device=dev, dtype=torch.float64), 2))
+        print(json.dumps({"mode": mode, "m": cfg.m, "n": cfg.n, "l": cfg.l, "bytes_A_GB": round(4.0 * cfg.m * cfg.n / 1e9, 1),
+                          "workspace_GB": round(B.brsvd_workspace_bytes(prm) / 1e9, 2), "blocks": best["n_blocks"],
+                          "passes": best["passes_over_A"], "seconds": round(t, 4),
+                          "link_GBps": round(best["bytes_A_streamed"] / t / 1e9, 2), "pinned_copy_GBps": round(h2d, 2),
+                          "fraction_of_pinned_copy": round(best["bytes_A_streamed"] / t / 1e9 / h2d, 4),
+                          "copy_seconds": round(best["copy_seconds"], 4),
+                          "gemm_seconds": round(best["gemm_an_seconds"] + best["gemm_at_seconds"], 4),
+                          "orthU": orth}), flush=True)
+        del U, S, Vt
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -178,6 +235,10 @@ def main(argv=None) -> int:
     r.add_argument("--iters", type=int, default=30)
     r.add_argument("--tol", type=float, default=1e-7)
     r.add_argument("--reps", type=int, default=2)
+    t = sub.add_parser("stream")
+    t.add_argument("--rows", type=int, default=160000)
+    t.add_argument("--modes", nargs="+", default=["separate", "fused", "alg2"], choices=["separate", "fused", "alg2"])
+    t.add_argument("--reps", type=int, default=2)
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
@@ -185,7 +246,7 @@ def main(argv=None) -> int:
         return 2
     import paper_1706_07191_amd as B
     B.lib()
-    {"gemm": sweep_gemm, "shapes": sweep_shapes, "rpca": sweep_rpca}[args.cmd](args)
+    {"gemm": sweep_gemm, "shapes": sweep_shapes, "rpca": sweep_rpca, "stream": sweep_stream}[args.cmd](args)
     return 0
 
 
