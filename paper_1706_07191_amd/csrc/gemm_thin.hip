@@ -525,7 +525,7 @@ struct AnCfg {
 };
 // Tile shapes picked from sweeps on MI355X (see the launch templates below, which must agree).
 static AnCfg an_cfg(int nt, int esz) {
-  if (esz == 8) return {2, 4, 32};
+  if (esz == 8) return {nt >= 5 ? 1 : 2, 4, 32};   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
   if (nt <= 8) return {2, 4, 64};
   return {2, 4, 32};
 }
@@ -544,7 +544,7 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
   const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * esz;
-  const int wg_regs = esz == 8 ? (nt <= 4 ? 2 : 1) : (nt <= 14 ? 2 : 1);   // workgroups per CU the registers allow
+  const int wg_regs = esz == 8 ? 2 : (nt <= 14 ? 2 : 1);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
   const char* e = getenv("BRSVD_AN_SPLITS");
@@ -601,7 +601,7 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
   if constexpr (sizeof(T) == 8 && NT > 8) {
     return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
   } else {
-    constexpr int MT = 2;
+    constexpr int MT = (sizeof(T) == 8 && NT >= 5) ? 1 : 2;
     constexpr int WAVES = 4;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
     if (vec)
