@@ -12,6 +12,9 @@ EPS32 = float(np.finfo(np.float32).eps)
 SIGMA_RTOL = 1e-4        # top-k singular values, relative
 ORTH_TOL = 1e-5          # ||U^T U - I||_2
 RECON_RTOL = 1e-2        # reconstruction error within 1 % of the oracle's
+RECON_FLOOR = 1e-6       # ... once it is above the fp32 rounding level of the reconstruction itself (the paper
+                         # reports 1e-7 for single precision on exactly representable inputs): an fp64 oracle
+                         # error of 1e-15 cannot be matched to 1 % by fp32 factors
 
 
 def need_gpu():
@@ -47,6 +50,6 @@ def check_against_oracle(A_host, Om_host, k, p, q, b, U, S, Vt, tag=""):
     assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0), "sigma must be descending and non-negative"
     assert out["sigma_rel"] <= SIGMA_RTOL, out
     assert out["orthU"] <= ORTH_TOL and out["orthV"] <= ORTH_TOL, out
-    assert abs(out["err_gpu"] - out["err_oracle"]) <= RECON_RTOL * out["err_oracle"], out
-    assert abs(out["err_gpu_l"] - out["err_oracle_l"]) <= RECON_RTOL * out["err_oracle_l"], out
+    assert abs(out["err_gpu"] - out["err_oracle"]) <= RECON_RTOL * out["err_oracle"] + RECON_FLOOR, out
+    assert abs(out["err_gpu_l"] - out["err_oracle_l"]) <= RECON_RTOL * out["err_oracle_l"] + RECON_FLOOR, out
     return out

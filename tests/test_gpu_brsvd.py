@@ -64,6 +64,22 @@ def test_largest_sketch_width():
         B.brsvd_create(B.make_params(m, n, 500, 13, q))        # l = 513
 
 
+@pytest.mark.parametrize("m,n,k,p,q,b", [(900, 700, 20, 10, 0, 256),      # no power iteration: sketch and projection only
+                                          (640, 64, 8, 8, 3, 640),        # one block, l = 16 = a single column tile, q = 3
+                                          (70, 4000, 30, 10, 1, 32),      # very wide: fewer rows than a row tile per block
+                                          (4100, 33, 5, 0, 2, 1000),      # p = 0, odd n (scalar load path), ragged tail of 100 rows
+                                          (50, 40, 39, 1, 1, 7)])         # l = min(m, n): the sketch spans everything
+def test_degenerate_shapes_and_parameters(m, n, k, p, q, b):
+    dev = need_gpu()
+    sig = 0.9 ** torch.arange(min(m, n), dtype=torch.float64)
+    A = synth.lowrank_plus_noise(m, n, sig, 1e-3, 5150 + m)
+    Om = synth.gaussian(n, k + p, 5151 + n)
+    cfg = synth.Config("edge", m, n, k, p, q, b, min(m, n), lambda i: i, 1e-3, 5150)
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev))
+    assert st["passes_over_A"] == 2 * q + 2 and st["n_blocks"] == -(-m // b)
+    check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"edge {m}x{n} l={k + p} q={q}")
+
+
 def test_forced_tsqr_matches_oracle():
     dev = need_gpu()
     cfg = synth.CONFIGS["C2"].scaled(3000, 2500, 700)
