@@ -23,7 +23,7 @@ def need_gpu():
 
 
 def note(line: str):
-    """Prints a measurement line and appends it to gpurun_out/parity.log when that folder exists."""
+    """Prints a measurement line and appends it to parity.log in the run's output folder, if there is one."""
     print(line, flush=True)
     log_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     if os.path.isdir(log_dir):
