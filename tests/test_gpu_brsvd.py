@@ -80,6 +80,28 @@ def test_degenerate_shapes_and_parameters(m, n, k, p, q, b):
     check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"edge {m}x{n} l={k + p} q={q}")
 
 
+def test_timing_levels():
+    """timing_level 1 times the pass kernels and the whole call only; the results do not depend on it."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C1"]
+    A, Om = cfg.make_A().to(dev), cfg.make_Omega().to(dev)
+    out = {}
+    for level in (0, 1):
+        h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, timing_level=level))
+        try:
+            out[level] = B.brsvd_run(h, A, Om)
+        finally:
+            B.brsvd_destroy(h)
+    s0, s1 = out[0][3], out[1][3]
+    assert s0["orth_seconds"] > 0 and s0["svd_seconds"] > 0 and s0["lift_seconds"] > 0
+    assert s1["orth_seconds"] == 0 and s1["svd_seconds"] == 0 and s1["lift_seconds"] == 0
+    for s in (s0, s1):
+        assert s["gemm_an_seconds"] > 0 and s["gemm_at_seconds"] > 0
+        assert s["total_seconds"] >= s["gemm_an_seconds"] + s["gemm_at_seconds"]
+        assert s["gemm_an_launches"] == 3 and s["gemm_at_launches"] == 3
+    assert torch.equal(out[0][1], out[1][1]) and torch.equal(out[0][0], out[1][0])
+
+
 def test_forced_tsqr_matches_oracle():
     dev = need_gpu()
     cfg = synth.CONFIGS["C2"].scaled(3000, 2500, 700)
