@@ -229,6 +229,14 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R,
 int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr,
                     int32_t* sweeps, void* stream);
 
+/* Measured peaks of the device, to put next to the published ones in roofline figures (Sec. 4 of the
+ * paper quotes its machine's peaks the same way).  One timed launch after one warm-up launch.
+ *   kind 0: streaming read of `amount` bytes from buf (DEVICE, at least `amount` bytes);
+ *   kind 1: `amount` iterations of 16 independent fp32 MFMAs (v_mfma_f32_16x16x4_f32) per wave on 2048
+ *           workgroups of four waves; buf (DEVICE) receives 2048*256 floats.
+ * *seconds (HOST) = duration of the launch, *work (HOST) = bytes read or flops done. */
+int brsvd_probe(int32_t kind, void* buf, uint64_t amount, double* seconds, double* work, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -56,7 +56,7 @@ class brsvd_stats(C.Structure):
 
 
 EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
-           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_destroy",
+           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_probe", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
            "brsvd_orth", "brsvd_small_svd"]
@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
     L.brsvd_norm2_power.argtypes = [vp, vp, i64, vp, i32, C.POINTER(dbl)]
     L.brsvd_run_alg2.argtypes = [vp, vp, i64, u64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
     L.brsvd_philox_normal.argtypes = [u64, i64, i64, i32, vp, vp]
+    L.brsvd_probe.argtypes = [i32, vp, u64, C.POINTER(dbl), C.POINTER(dbl), vp]
     L.brsvd_destroy.argtypes = [vp]
     L.brsvd_status_string.argtypes = [C.c_int]
     L.brsvd_status_string.restype = C.c_char_p
@@ -210,6 +211,14 @@ def brsvd_run_alg2(handle, A, l, seed=0, Omega=None, lda: Optional[int] = None, 
                                   U.data_ptr(), S.data_ptr(), Vt.data_ptr(), C.byref(st) if want_stats else None)
     _check(status, "brsvd_run_alg2")
     return U, S, Vt, (st.as_dict() if want_stats else None)
+
+
+def brsvd_probe(kind, buf, amount):
+    """Measured device peaks: kind 0 streaming read of `amount` bytes of buf, kind 1 an fp32 MFMA loop.
+    Returns (seconds, work) with work in bytes or flops."""
+    sec, work = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().brsvd_probe(kind, buf.data_ptr(), int(amount), C.byref(sec), C.byref(work), None), "brsvd_probe")
+    return sec.value, work.value
 
 
 def brsvd_philox_normal(seed, rows, cols, row0=0, device="cuda:0", stream=None):

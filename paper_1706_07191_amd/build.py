@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libbrsvd.so")
-SOURCES = ["gemm_thin.hip", "orth.hip", "tsqr.hip", "small_svd.hip", "rpca.hip", "philox.hip", "brsvd.hip"]
+SOURCES = ["gemm_thin.hip", "orth.hip", "tsqr.hip", "small_svd.hip", "rpca.hip", "philox.hip", "probe.hip", "brsvd.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -771,6 +771,10 @@ int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, c
   return status;
 }
 
+int brsvd_probe(int32_t kind, void* buf, uint64_t amount, double* seconds, double* work, void* stream) {
+  return probe(kind, buf, amount, seconds, work, (hipStream_t)stream);
+}
+
 int brsvd_philox_normal(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, float* out, void* stream) {
   if (!out || rows < 1 || cols < 1 || row0 < 0) return BRSVD_ERR_ARG;
   return philox_normal(seed, row0, rows, cols, out, cols, (hipStream_t)stream);

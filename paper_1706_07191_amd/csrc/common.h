@@ -153,4 +153,7 @@ int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream);
 // e = row*l + col from output e&3 of counter e>>2) into out (rows x ld, columns l..ld-1 zeroed).
 int philox_normal(uint64_t seed, int64_t row0, int64_t rows, int l, float* out, int ld, hipStream_t stream);
 
+// ---- machine probes (probe.hip) -------------------------------------------------------------
+int probe(int kind, void* buf, uint64_t amount, double* seconds, double* work, hipStream_t stream);
+
 }  // namespace brsvd

@@ -19,6 +19,10 @@
       through two staging buffers, 16 GB device budget): seconds per BRSVD, GB/s of A over the host link and the
       fraction of a plain pinned copy of one block measured in the same run.  M defaults to 160000 (64 GB).
 
+  python -m paper_1706_07191_amd.sweep peaks
+      measured peaks of this device next to the published ones: streaming read of 8 GiB of HBM, an fp32
+      MFMA loop, a pinned host-to-device copy of 1 GiB.
+
 Every line of output is one JSON object.
 """
 from __future__ import annotations
@@ -216,6 +220,32 @@ def sweep_stream(args):
         del U, S, Vt
 
 
+def sweep_peaks(args):
+    import torch
+
+    import paper_1706_07191_amd as B
+    dev = torch.device("cuda:0")
+    buf = torch.randn(1 << 31, device=dev)                 # 8 GiB of fp32
+    sec, work = B.brsvd_probe(0, buf, buf.numel() * 4)
+    print(json.dumps({"probe": "hbm streaming read", "GBps": round(work / sec / 1e9, 1), "published_GBps": 8000}), flush=True)
+    del buf
+    out = torch.empty(2048 * 256, device=dev)
+    sec, work = B.brsvd_probe(1, out, 20000)
+    print(json.dumps({"probe": "fp32 MFMA 16x16x4, random operands", "TFLOPs": round(work / sec / 1e12, 1),
+                      "published_TFLOPs": 157.3}), flush=True)
+    host = torch.empty(1 << 28, dtype=torch.float32, pin_memory=True)
+    d = torch.empty(1 << 28, device=dev)
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        d.copy_(host, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, d.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    print(json.dumps({"probe": "pinned host-to-device copy of 1 GiB", "GBps": round(best, 1)}), flush=True)
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -235,6 +265,7 @@ def main(argv=None) -> int:
     r.add_argument("--iters", type=int, default=30)
     r.add_argument("--tol", type=float, default=1e-7)
     r.add_argument("--reps", type=int, default=2)
+    sub.add_parser("peaks")
     t = sub.add_parser("stream")
     t.add_argument("--rows", type=int, default=160000)
     t.add_argument("--modes", nargs="+", default=["separate", "fused", "alg2"], choices=["separate", "fused", "alg2"])
@@ -246,7 +277,7 @@ def main(argv=None) -> int:
         return 2
     import paper_1706_07191_amd as B
     B.lib()
-    {"gemm": sweep_gemm, "shapes": sweep_shapes, "rpca": sweep_rpca, "stream": sweep_stream}[args.cmd](args)
+    {"gemm": sweep_gemm, "shapes": sweep_shapes, "rpca": sweep_rpca, "stream": sweep_stream, "peaks": sweep_peaks}[args.cmd](args)
     return 0
 
 
