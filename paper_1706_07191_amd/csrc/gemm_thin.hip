@@ -407,6 +407,23 @@ __global__ void k_reduce_splits(const T* __restrict__ part, int nsplit, int64_t 
   out[row * ldo + col] = s;
 }
 
+// The same sum for partial panels that are contiguous (all ldi columns summed, ldo == ldi): 16 bytes per
+// thread, splits unrolled so that several loads are in flight.
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_reduce_splits_flat(const T* __restrict__ part, int nsplit, int64_t split_stride, int64_t count16,
+                     T* __restrict__ out, int accumulate) {
+  typedef typename El<T>::u16 unit16;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= count16) return;
+  constexpr int EPU = El<T>::kPerU16;
+  const T* p = part + idx * EPU;
+  unit16 s = accumulate ? *(const unit16*)(out + idx * EPU) : unit16{};
+#pragma unroll 8
+  for (int i = 0; i < nsplit; ++i) s += *(const unit16*)(p + (int64_t)i * split_stride);
+  *(unit16*)(out + idx * EPU) = s;
+}
+
 // In-place first level of a long split sum: slot g*fan <- sum of the slots [g*fan, min((g+1)*fan, nsplit))
 // in slot order (blockIdx.y = g).  Each thread only touches its own element of every slot.
 template <typename T>
@@ -649,8 +666,15 @@ static int reduce_splits(T* part, int nsplit, int64_t split_stride, int64_t rows
     nsplit = groups;
     split_stride *= kReduceFan;
   }
-  hipLaunchKernelGGL(k_reduce_splits<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
-                     part, nsplit, split_stride, rows, ncols, ldi, out, ldo, accumulate ? 1 : 0);
+  constexpr int EPU = 16 / (int)sizeof(T);
+  const bool flat = ncols == ldi && ldo == ldi && total % EPU == 0 && split_stride % EPU == 0 &&
+                    ((uintptr_t)part) % 16 == 0 && ((uintptr_t)out) % 16 == 0;
+  if (flat)
+    hipLaunchKernelGGL(k_reduce_splits_flat<T>, dim3((unsigned)ceil_div(total / EPU, 256)), dim3(256), 0, stream, part,
+                       nsplit, split_stride, total / EPU, out, accumulate ? 1 : 0);
+  else
+    hipLaunchKernelGGL(k_reduce_splits<T>, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, stream,
+                       part, nsplit, split_stride, rows, ncols, ldi, out, ldo, accumulate ? 1 : 0);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
