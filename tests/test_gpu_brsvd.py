@@ -80,6 +80,36 @@ def test_degenerate_shapes_and_parameters(m, n, k, p, q, b):
     check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"edge {m}x{n} l={k + p} q={q}")
 
 
+def test_caller_streams():
+    """Caller-owned compute and copy streams (default priority): in-core on a side stream, and host-resident A
+    with both streams supplied; results equal the default-stream runs bit for bit."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C1"]
+    A, Om = cfg.make_A(), cfg.make_Omega()
+    Ad, Od = A.to(dev), Om.to(dev)
+    U0, S0, Vt0, _ = _run(cfg, Ad, Od)
+    cs, ps = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, compute_stream=cs))
+    try:
+        U1, S1, Vt1, st1 = B.brsvd_run(h, Ad, Od)
+    finally:
+        B.brsvd_destroy(h)
+    assert torch.equal(S0, S1) and torch.equal(U0, U1) and torch.equal(Vt0, Vt1) and st1["total_seconds"] > 0
+    Ah = A.pin_memory()
+    outs = []
+    for kw in (dict(), dict(compute_stream=cs, copy_stream=ps)):
+        h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block,
+                                         a_location=B.BRSVD_A_HOST_PINNED, **kw))
+        try:
+            outs.append(B.brsvd_run(h, Ah, Od))
+        finally:
+            B.brsvd_destroy(h)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][0], outs[1][0])
+    assert outs[1][3]["copy_seconds"] > 0 and outs[1][3]["n_blocks"] == 4
+
+
 def test_timing_levels():
     """timing_level 1 times the pass kernels and the whole call only; the results do not depend on it."""
     dev = need_gpu()
