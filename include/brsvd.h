@@ -229,6 +229,16 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R,
 int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr,
                     int32_t* sweeps, void* stream);
 
+/* How the two thin products would be cut into workgroups (host-only, no GPU call): for checking the
+ * plans' invariants and for reading profiles.  which = 0: Y = A X with A rows x n, out12 = {rows per
+ * tile, row tiles, chunks per tile C, whole tiles, leftover tiles, main splits f, tail chunks x, tail
+ * strips per workgroup j, partial panels per leftover tile, workgroups, column groups, column tiles per
+ * group}.  which = 1: Z += A^T Q, out12 = {m-tiles per wave, waves, column tiles, row blocks,
+ * sub-ranges per block, rows per sub-range, partial panels, chunk rows, column groups, column tiles per
+ * group, 0, 0}.  out12: HOST, 12 ints. */
+int brsvd_gemm_plan(int32_t which, int64_t rows, int64_t n, int32_t l, int64_t block_rows, int32_t dtype,
+                    int32_t* out12);
+
 /* Measured peaks of the device, to put next to the published ones in roofline figures (Sec. 4 of the
  * paper quotes its machine's peaks the same way).  One timed launch after one warm-up launch.
  *   kind 0: streaming read of `amount` bytes from buf (DEVICE, at least `amount` bytes);

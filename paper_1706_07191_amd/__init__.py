@@ -56,7 +56,7 @@ class brsvd_stats(C.Structure):
 
 
 EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
-           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_probe", "brsvd_destroy",
+           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
            "brsvd_orth", "brsvd_small_svd"]
@@ -92,6 +92,7 @@ def lib() -> C.CDLL:
     L.brsvd_run_alg2.argtypes = [vp, vp, i64, u64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
     L.brsvd_philox_normal.argtypes = [u64, i64, i64, i32, vp, vp]
     L.brsvd_probe.argtypes = [i32, vp, u64, C.POINTER(dbl), C.POINTER(dbl), vp]
+    L.brsvd_gemm_plan.argtypes = [i32, i64, i64, i32, i64, i32, C.POINTER(i32)]
     L.brsvd_destroy.argtypes = [vp]
     L.brsvd_status_string.argtypes = [C.c_int]
     L.brsvd_status_string.restype = C.c_char_p
@@ -211,6 +212,13 @@ def brsvd_run_alg2(handle, A, l, seed=0, Omega=None, lda: Optional[int] = None, 
                                   U.data_ptr(), S.data_ptr(), Vt.data_ptr(), C.byref(st) if want_stats else None)
     _check(status, "brsvd_run_alg2")
     return U, S, Vt, (st.as_dict() if want_stats else None)
+
+
+def brsvd_gemm_plan(which, rows, n, l, block_rows=0, dtype=BRSVD_DTYPE_F32):
+    """The launch plan of gemm_an (which = 0) or gemm_at (which = 1) as a list of 12 ints (see brsvd.h)."""
+    out = (C.c_int32 * 12)()
+    _check(lib().brsvd_gemm_plan(which, rows, n, l, block_rows, dtype, out), "brsvd_gemm_plan")
+    return list(out)
 
 
 def brsvd_probe(kind, buf, amount):

@@ -771,6 +771,17 @@ int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, c
   return status;
 }
 
+int brsvd_gemm_plan(int32_t which, int64_t rows, int64_t n, int32_t l, int64_t block_rows, int32_t dtype,
+                    int32_t* out12) {
+  if (!out12 || rows < 1 || n < 1 || l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
+  if (dtype != BRSVD_DTYPE_F32 && dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  const int esz = dtype == BRSVD_DTYPE_F64 ? 8 : 4;
+  if (which == 0) gemm_an_plan_describe(rows, n, padded_l(l), esz, out12);
+  else if (which == 1) gemm_at_plan_describe(rows, n, padded_l(l), block_rows, esz, out12);
+  else return BRSVD_ERR_ARG;
+  return BRSVD_OK;
+}
+
 int brsvd_probe(int32_t kind, void* buf, uint64_t amount, double* seconds, double* work, void* stream) {
   return probe(kind, buf, amount, seconds, work, (hipStream_t)stream);
 }

@@ -58,6 +58,10 @@ int gemm_at(const double* A, int64_t lda, int64_t rows, int64_t n, const double*
             double* Z, bool accumulate, int64_t block_rows, void* scratch, uint64_t scratch_bytes,
             hipStream_t stream, const KernelEvents* ev = nullptr);
 
+// Launch plans as numbers (see brsvd_gemm_plan in the C ABI).
+void gemm_an_plan_describe(int64_t rows, int64_t K, int Lp, int esz, int32_t out[12]);
+void gemm_at_plan_describe(int64_t rows, int64_t n, int Lp, int64_t block_rows, int esz, int32_t out[12]);
+
 // dst (rows x Lp, zero padded) <- src (rows x l dense)
 int pad_panel(const float* src, int64_t rows, int l, float* dst, int Lp, hipStream_t stream);
 int pad_panel(const double* src, int64_t rows, int l, double* dst, int Lp, hipStream_t stream);

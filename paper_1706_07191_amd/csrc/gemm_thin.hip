@@ -593,6 +593,15 @@ uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp, int esz) {
   return (uint64_t)p.nsplit * rows * Lp * esz;
 }
 
+// The launch plans as plain numbers, for host-side checks of their invariants.
+void gemm_an_plan_describe(int64_t rows, int64_t K, int Lp, int esz, int32_t out[12]) {
+  NGroups ng = column_groups(Lp, esz);
+  AnPlan p = an_plan(rows, K, ng.nt, esz);
+  const int32_t v[12] = {p.tile_rows, p.row_tiles, p.sh.C, p.sh.whole, p.sh.lt, p.sh.f, p.sh.x, p.sh.j, p.nsplit, p.wgs,
+                         ng.groups, ng.nt};
+  for (int i = 0; i < 12; ++i) out[i] = v[i];
+}
+
 template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
 static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y, int64_t ldy,
                           int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
@@ -773,6 +782,14 @@ uint64_t gemm_at_scratch_bytes(int64_t rows, int64_t n, int Lp, int64_t block_ro
   NGroups ng = column_groups(Lp, esz);
   AtPlan p = at_plan(rows, n, ng.nt, block_rows, esz);
   return (uint64_t)p.nsplit * n * Lp * esz;
+}
+
+void gemm_at_plan_describe(int64_t rows, int64_t n, int Lp, int64_t block_rows, int esz, int32_t out[12]) {
+  if (block_rows <= 0 || block_rows > rows) block_rows = rows;
+  NGroups ng = column_groups(Lp, esz);
+  AtPlan p = at_plan(rows, n, ng.nt, block_rows, esz);
+  const int32_t v[12] = {p.mt, p.waves, p.col_tiles, p.nblocks, p.sub, p.rows_per_sub, p.nsplit, kAtKC, ng.groups, ng.nt, 0, 0};
+  for (int i = 0; i < 12; ++i) out[i] = v[i];
 }
 
 template <typename T, int NT, int MT, int WAVES, bool VEC>
