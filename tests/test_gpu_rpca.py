@@ -69,6 +69,26 @@ def test_rpca_planted_recovery_matches_oracle():
         assert abs(a - b) <= 2e-2 * b + 1e-6
 
 
+def test_rpca_on_a_fused_pass_handle():
+    """The ALM loop on a handle created with the q+1-pass mode: same decomposition, half the reads per SVD.
+    The inner SVDs are less accurate there in fp32 (one re-orthonormalisation fewer per pass), which shows as
+    a residual floor of about 1e-5 instead of 1e-6 after 30 iterations."""
+    dev = need_gpu()
+    cfg, D, L0, S0, Om = _case(1200, 320)
+    m, n = D.shape
+    lam = 1.0 / np.sqrt(max(m, n))
+    n2 = float(np.linalg.norm(D.double().numpy(), 2))
+    h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=512, pass_mode=B.BRSVD_PASSES_FUSED))
+    try:
+        L, S, res, st = B.brsvd_rpca_ialm(h, D.to(dev), Om.to(dev), 30, lam, 1.25 / n2, 1.5, norm2_M=n2)
+    finally:
+        B.brsvd_destroy(h)
+    assert st["passes_over_A"] == 30 * (cfg.q + 1) and res[-1] < 5e-5
+    Lg = L.double().cpu().numpy()
+    assert np.linalg.norm(Lg - L0.numpy()) <= 5e-3 * np.linalg.norm(L0.numpy())
+    assert float(torch.linalg.norm(D.to(dev) - L - S) / torch.linalg.norm(D.to(dev))) < 5e-5
+
+
 def test_rpca_argument_errors():
     dev = need_gpu()
     cfg, D, L0, S0, Om = _case(300, 200, iters=1)
