@@ -80,6 +80,34 @@ def test_degenerate_shapes_and_parameters(m, n, k, p, q, b):
     check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"edge {m}x{n} l={k + p} q={q}")
 
 
+def test_seeded_random_shapes_against_oracle():
+    """Forty seeded random problems (shape, rank parameters, block size, pass mode, storage): every one within the
+    usual tolerances of the oracle.  Exercises ragged tiles, single-row blocks and the launch plans of odd shapes."""
+    import random
+    dev = need_gpu()
+    rng = random.Random(17060719)
+    for case in range(40):
+        m = rng.choice([rng.randint(40, 400), rng.randint(400, 3000)])
+        n = rng.choice([rng.randint(40, 400), rng.randint(400, 3000)])
+        l = rng.randint(2, min(m, n, 61) - 1)        # sigma_l / sigma_1 >= 0.96^60 = 0.09: resolved in fp32 in either pass mode
+        p = rng.randint(0, min(l - 1, 12))
+        k = l - p
+        q = rng.randint(0, 3)
+        b = rng.choice([0, rng.randint(1, m), rng.randint(max(1, m // 8), m)])
+        fused = rng.random() < 0.3
+        host = rng.random() < 0.25
+        sig = torch.tensor([0.96 ** i for i in range(min(m, n))], dtype=torch.float64)
+        A = synth.lowrank_plus_noise(m, n, sig, 1e-3, 9000 + case)
+        Om = synth.gaussian(n, l, 9500 + case)
+        cfg = synth.Config(f"rand{case}", m, n, k, p, q, b, min(m, n), lambda i: i, 1e-3, 9000 + case)
+        print(f"[case {case}] m={m} n={n} k={k} p={p} q={q} b={b} fused={fused} host={host}", flush=True)
+        U, S, Vt, st = _run(cfg, A.pin_memory() if host else A.to(dev), Om.to(dev),
+                            a_location=B.BRSVD_A_HOST_PINNED if host else B.BRSVD_A_DEVICE,
+                            pass_mode=B.BRSVD_PASSES_FUSED if fused else B.BRSVD_PASSES_SEPARATE)
+        assert st["passes_over_A"] == (q + 1 if fused else 2 * q + 2) * (1 + st["orth_fallbacks"])
+        check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b if b else m, U, S, Vt, f"rand{case}")
+
+
 def test_caller_streams():
     """Caller-owned compute and copy streams (default priority): in-core on a side stream, and host-resident A
     with both streams supplied; results equal the default-stream runs bit for bit."""
