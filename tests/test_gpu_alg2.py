@@ -147,3 +147,34 @@ def test_alg2_argument_errors():
         assert L.brsvd_philox_normal(1, -1, 4, 4, A.data_ptr(), None) == B.BRSVD_ERR_ARG
     finally:
         B.brsvd_destroy(h)
+
+
+def test_alg2_seeded_random_shapes():
+    """Fifteen seeded random problems for the block-local scheme (q <= 1, gently decaying spectrum, so that the
+    unorthonormalised block sketches stay resolved in fp32), Omega drawn on the device."""
+    import random
+    dev = need_gpu()
+    rng = random.Random(2170607)
+    for case in range(15):
+        m = rng.choice([rng.randint(60, 400), rng.randint(400, 2500)])
+        n = rng.choice([rng.randint(60, 400), rng.randint(400, 2500)])
+        l = rng.randint(2, min(m, n, 48) - 1)
+        p = rng.randint(0, min(l - 1, 8))
+        k, q = l - p, rng.randint(0, 1)
+        b = rng.randint(max(1, m // 6), m)
+        sig = torch.tensor([0.97 ** i for i in range(min(m, n))], dtype=torch.float64)
+        A = synth.lowrank_plus_noise(m, n, sig, 1e-3, 9400 + case)
+        seed = 2 ** 35 + 1000 * case + 7
+        Om = PX.philox_normal(seed, m, l)
+        cfg = synth.Config(f"rand-alg2-{case}", m, n, k, p, q, b, min(m, n), lambda i: i, 1e-3, 9400 + case)
+        print(f"[case {case}] m={m} n={n} k={k} p={p} q={q} b={b}", flush=True)
+        h = B.brsvd_create(B.make_params(m, n, k, p, q, row_block=b))
+        try:
+            U, S, Vt, st = B.brsvd_run_alg2(h, A.to(dev), l, seed=seed)
+        finally:
+            B.brsvd_destroy(h)
+        f, _, _ = _figures(A.numpy(), Om, cfg, b, U, S, Vt)
+        note(f"[alg2 rand{case}] " + " ".join(f"{k_}={v:.3e}" for k_, v in f.items()))
+        assert st["passes_over_A"] == 2 * (1 + st["orth_fallbacks"])
+        assert f["sigma_rel"] <= SIGMA_RTOL and f["orthU"] <= ORTH_TOL and f["orthV"] <= ORTH_TOL
+        assert abs(f["err_gpu"] - f["err_oracle"]) <= RECON_RTOL * f["err_oracle"]

@@ -114,3 +114,30 @@ def test_f64_dtype_mismatch_is_rejected():
     finally:
         B.brsvd_destroy(h64)
         B.brsvd_destroy(h32)
+
+
+def test_f64_seeded_random_shapes():
+    """Twenty seeded random problems in double precision (shapes, block sizes, pass modes, storage)."""
+    import random
+    dev = need_gpu()
+    rng = random.Random(64170607)
+    for case in range(20):
+        m = rng.choice([rng.randint(40, 400), rng.randint(400, 2500)])
+        n = rng.choice([rng.randint(40, 400), rng.randint(400, 2500)])
+        l = rng.randint(2, min(m, n, 140) - 1)
+        p = rng.randint(0, min(l - 1, 12))
+        k, q = l - p, rng.randint(0, 2)
+        b = rng.choice([0, rng.randint(1, m), rng.randint(max(1, m // 8), m)])
+        fused, host = rng.random() < 0.3, rng.random() < 0.25
+        sig = torch.tensor([0.96 ** i for i in range(min(m, n))], dtype=torch.float64)
+        A = synth.lowrank_plus_noise(m, n, sig, 1e-3, 9100 + case).double()
+        A = A + 1e-9 * synth.gaussian(m, n, 9200 + case, dtype=torch.float64)
+        Om = synth.gaussian(n, l, 9300 + case, dtype=torch.float64)
+        cfg = synth.Config(f"rand64-{case}", m, n, k, p, q, b, min(m, n), lambda i: i, 1e-3, 9100 + case)
+        kw = dict(pass_mode=B.BRSVD_PASSES_FUSED if fused else B.BRSVD_PASSES_SEPARATE)
+        if host:
+            kw["a_location"] = B.BRSVD_A_HOST_PINNED
+        print(f"[case {case}] m={m} n={n} k={k} p={p} q={q} b={b} fused={fused} host={host}", flush=True)
+        U, S, Vt, st = _run64(cfg, A.pin_memory() if host else A, Om, b, **kw)
+        # the fused mode squares the condition of the sketch panels: eps64 * (sigma_1 / sigma_l)^2 is still tiny
+        _check64(A, Om, cfg, b if b else m, U, S, Vt, f"rand{case}", sig_tol=1e-9 if fused else SIGMA_RTOL64)
