@@ -44,7 +44,8 @@ enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
  * price of one skipped re-orthonormalisation per pass (panels of condition up to (s_1/s_l)^2). */
 enum { BRSVD_PASSES_SEPARATE = 0, BRSVD_PASSES_FUSED = 1 };
 /* Element type of A, Omega and the results.  F32: brsvd_run and everything else.  F64 (the precision
- * the paper measures in, Sec. 4): brsvd_run_f64 only -- the same path on the fp64 matrix cores. */
+ * the paper measures in, Sec. 4): brsvd_run_f64 and brsvd_rpca_ialm_tol_f64 -- the same path on the
+ * fp64 matrix cores. */
 enum { BRSVD_DTYPE_F32 = 0, BRSVD_DTYPE_F64 = 1 };
 
 /* Problem statement of Alg. 1 / Alg. 2 (inputs A, k, p, q and the partition), plus where A
@@ -174,6 +175,13 @@ int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int
                         double tol, float lambda, float mu0, float rho, double norm2_M,
                         float* L, float* S, float* work, double* residuals, int32_t* iters_done,
                         brsvd_stats* stats);
+
+/* The same loop in double precision (the precision of the paper's Table 2), for a handle created with
+ * dtype == BRSVD_DTYPE_F64; arguments as above with double elements. */
+int brsvd_rpca_ialm_tol_f64(brsvd_handle h, const double* M, const double* Omegas, int32_t max_iters,
+                            double tol, double lambda, double mu0, double rho, double norm2_M,
+                            double* L, double* S, double* work, double* residuals,
+                            int32_t* iters_done, brsvd_stats* stats);
 
 /* Spectral norm ||A||_2, the scale of the multiplier initialisation of Alg. 3, by the power method
  * on A^T A: x = x0/|x0|; iters times { y = A x; est = |y|; x = A^T y / |A^T y| }; *norm2_out (HOST)

@@ -55,7 +55,7 @@ class brsvd_stats(C.Structure):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
-EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol",
+EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol", "brsvd_rpca_ialm_tol_f64",
            "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
                                   C.POINTER(brsvd_stats)]
     L.brsvd_rpca_ialm_tol.argtypes = [vp, vp, vp, i32, dbl, flt, flt, flt, dbl, vp, vp, vp, C.POINTER(dbl),
                                       C.POINTER(i32), C.POINTER(brsvd_stats)]
+    L.brsvd_rpca_ialm_tol_f64.argtypes = [vp, vp, vp, i32, dbl, dbl, dbl, dbl, dbl, vp, vp, vp, C.POINTER(dbl),
+                                          C.POINTER(i32), C.POINTER(brsvd_stats)]
     L.brsvd_norm2_power.argtypes = [vp, vp, i64, vp, i32, C.POINTER(dbl)]
     L.brsvd_run_alg2.argtypes = [vp, vp, i64, u64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
     L.brsvd_philox_normal.argtypes = [u64, i64, i64, i32, vp, vp]
@@ -255,19 +257,20 @@ def brsvd_rpca_ialm(handle, M, Omegas, iters, lam, mu0, rho, norm2_M=0.0, L=None
 
 
 def brsvd_rpca_ialm_tol(handle, M, Omegas, max_iters, tol, lam, mu0, rho, norm2_M=0.0, L=None, S=None, work=None):
-    """Returns L, S, the residuals of the iterations run, their number, and the statistics."""
+    """Returns L, S, the residuals of the iterations run, their number, and the statistics.  fp32, or fp64 when M
+    is a float64 tensor (handle created with dtype=BRSVD_DTYPE_F64)."""
     import torch
     m, n = M.shape
+    dt = M.dtype
     L = torch.empty_like(M) if L is None else L
     S = torch.empty_like(M) if S is None else S
-    work = torch.empty(2 * m * n, device=M.device) if work is None else work
+    work = torch.empty(2 * m * n, device=M.device, dtype=dt) if work is None else work
     res = (C.c_double * max_iters)()
     done = C.c_int32(0)
     st = brsvd_stats()
-    status = lib().brsvd_rpca_ialm_tol(handle, _dev(M, torch.float32, "M"), _dev(Omegas, torch.float32, "Omegas"),
-                                       max_iters, tol, lam, mu0, rho, norm2_M, _dev(L, torch.float32, "L"),
-                                       _dev(S, torch.float32, "S"), _dev(work, torch.float32, "work"), res,
-                                       C.byref(done), C.byref(st))
+    fn = lib().brsvd_rpca_ialm_tol_f64 if dt == torch.float64 else lib().brsvd_rpca_ialm_tol
+    status = fn(handle, _dev(M, dt, "M"), _dev(Omegas, dt, "Omegas"), max_iters, tol, lam, mu0, rho, norm2_M,
+                _dev(L, dt, "L"), _dev(S, dt, "S"), _dev(work, dt, "work"), res, C.byref(done), C.byref(st))
     _check(status, "brsvd_rpca_ialm_tol")
     return L, S, list(res)[:done.value], done.value, st.as_dict()
 

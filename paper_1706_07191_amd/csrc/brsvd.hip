@@ -120,9 +120,9 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   L.S32 = take((uint64_t)Lp * esz);
   L.flags = take(64);
   L.scal = take(64);
-  if (!host && esz == 4) {   // results of the inner SVDs of the robust-PCA loop, and its reduction scratch
-    L.rpcaU = take((uint64_t)m * l * 4);
-    L.rpcaVt = take((uint64_t)l * n * 4);
+  if (!host) {   // results of the inner SVDs of the robust-PCA loop, and its reduction scratch
+    L.rpcaU = take((uint64_t)m * l * esz);
+    L.rpcaVt = take((uint64_t)l * n * esz);
     L.rpca_part = take(rpca_part_doubles(m, n) * 8);
   }
   L.tsqr_bytes = std::max(tsqr_work_bytes(m, Lp), tsqr_work_bytes(n, Lp));
@@ -611,6 +611,101 @@ int run_with_stats(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U
   return status;
 }
 
+// ---- robust PCA loop (Alg. 3), both element types -----------------------------------------------
+template <typename T>
+int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, double tol, double lambda, double mu0,
+              double rho, double norm2_M, T* L, T* S, T* work, double* residuals, int32_t* iters_done,
+              brsvd_stats* stats) {
+  if (iters_done) *iters_done = 0;
+  if (!h || !M || !Omegas || !L || !S || !work || max_iters < 1) return BRSVD_ERR_ARG;
+  if (h->host_a || !(lambda > 0.0) || !(mu0 > 0.0) || !(rho > 1.0) || !(tol >= 0.0)) return BRSVD_ERR_ARG;
+  const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
+  const int l = h->l;
+  hipStream_t cs = h->compute;
+  T* Y = work;
+  T* X = work + count;
+  T* Uw = h->at<T>(h->lay.rpcaU);
+  T* Vtw = h->at<T>(h->lay.rpcaVt);
+  T* Sw = h->at<T>(h->lay.S32);
+  double* part = h->at<double>(h->lay.rpca_part);
+  double* scal = h->at<double>(h->lay.scal);
+  brsvd_stats acc;
+  std::memset(&acc, 0, sizeof(acc));
+  auto flush_stats = [&](int passes, int fallbacks) {
+    if (!stats) return;
+    (void)hipStreamSynchronize(cs);
+    brsvd_stats one;
+    fill_stats(h, &one, passes, fallbacks);
+    add_stats(&acc, one);
+    reset_timing(h, true);
+  };
+  reset_timing(h, stats != nullptr);
+
+  // ||M||_max, ||M||_F^2 and, if not supplied, ||M||_2 from one randomized SVD
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_norms<T>(M, count, part, scal, cs));
+  }
+  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal, 2 * sizeof(double), hipMemcpyDeviceToHost, cs));
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
+  if (!(normF > 0.0)) return BRSVD_ERR_ARG;
+  const int passes1 = passes_per_run(h);
+  if (!(norm2_M > 0.0)) {
+    int fb = 0;
+    {
+      Region total(h, CAT_TOTAL, cs);
+      BRSVD_TRY(run_sync<T>(h, M, n, Omegas, Uw, Sw, Vtw, &fb));
+    }
+    T s0 = T(0);
+    BRSVD_HIP_TRY(hipMemcpy(&s0, Sw, sizeof(T), hipMemcpyDeviceToHost));
+    norm2_M = (double)s0;
+    flush_stats(passes1 * (1 + fb), fb);
+    if (!(norm2_M > 0.0)) return BRSVD_ERR_ARG;
+  }
+  const double J = std::max(norm2_M, max_abs / (double)lambda);
+  double mu = mu0;
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_init<T>(M, count, (T)(1.0 / J), (T)(1.0 / mu), Y, S, X, cs));
+  }
+  int it = 0;
+  double mu_last = mu;
+  while (it < max_iters) {
+    int fb = 0;
+    const double mu_next = mu * (double)rho;
+    mu_last = mu;
+    {
+      Region total(h, CAT_TOTAL, cs);
+      BRSVD_TRY(run_sync<T>(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
+      {
+        Region r(h, CAT_ELEM, cs);
+        BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part,
+                                 scal + 2, cs));
+      }
+      BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
+      BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+    }
+    const double res = std::sqrt(h->host_scal[2]) / normF;
+    if (residuals) residuals[it] = res;
+    flush_stats(passes1 * (1 + fb), fb);
+    ++it;
+    if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
+    mu = mu_next;
+  }
+  // L of the last iteration run: its triplets and its mu are still in place
+  {
+    Region r(h, CAT_ELEM, cs);
+    BRSVD_TRY(rpca_lowrank<T>(Uw, Sw, Vtw, m, n, l, (T)mu_last, L, cs));
+  }
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  flush_stats(0, 0);
+  if (iters_done) *iters_done = it;
+  if (stats) *stats = acc;
+  return BRSVD_OK;
+}
+
+
 // ---- step-level GEMM calls (both element types) --------------------------------------------------
 uint64_t step_gemm_scratch_bytes(int64_t rows, int64_t n, int l, int esz) {
   if (rows < 1 || n < 1 || l < 1 || l > kMaxL) return 0;
@@ -795,93 +890,18 @@ int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int
                         float lambda, float mu0, float rho, double norm2_M, float* L, float* S, float* work,
                         double* residuals, int32_t* iters_done, brsvd_stats* stats) {
   if (iters_done) *iters_done = 0;
-  if (!h || !M || !Omegas || !L || !S || !work || max_iters < 1) return BRSVD_ERR_ARG;
-  if (h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
-  if (h->host_a || !(lambda > 0.f) || !(mu0 > 0.f) || !(rho > 1.f) || !(tol >= 0.0)) return BRSVD_ERR_ARG;
-  const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
-  const int l = h->l;
-  hipStream_t cs = h->compute;
-  float* Y = work;
-  float* X = work + count;
-  float* Uw = h->at<float>(h->lay.rpcaU);
-  float* Vtw = h->at<float>(h->lay.rpcaVt);
-  float* Sw = h->at<float>(h->lay.S32);
-  double* part = h->at<double>(h->lay.rpca_part);
-  double* scal = h->at<double>(h->lay.scal);
-  brsvd_stats acc;
-  std::memset(&acc, 0, sizeof(acc));
-  auto flush_stats = [&](int passes, int fallbacks) {
-    if (!stats) return;
-    (void)hipStreamSynchronize(cs);
-    brsvd_stats one;
-    fill_stats(h, &one, passes, fallbacks);
-    add_stats(&acc, one);
-    reset_timing(h, true);
-  };
-  reset_timing(h, stats != nullptr);
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
+  return rpca_loop<float>(h, M, Omegas, max_iters, tol, lambda, mu0, rho, norm2_M, L, S, work, residuals, iters_done,
+                          stats);
+}
 
-  // ||M||_max, ||M||_F^2 and, if not supplied, ||M||_2 from one randomized SVD
-  {
-    Region r(h, CAT_ELEM, cs);
-    BRSVD_TRY(rpca_norms(M, count, part, scal, cs));
-  }
-  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal, 2 * sizeof(double), hipMemcpyDeviceToHost, cs));
-  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-  const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
-  if (!(normF > 0.0)) return BRSVD_ERR_ARG;
-  const int passes1 = passes_per_run(h);
-  if (!(norm2_M > 0.0)) {
-    int fb = 0;
-    {
-      Region total(h, CAT_TOTAL, cs);
-      BRSVD_TRY(run_sync(h, M, n, Omegas, Uw, Sw, Vtw, &fb));
-    }
-    float s0 = 0.f;
-    BRSVD_HIP_TRY(hipMemcpy(&s0, Sw, sizeof(float), hipMemcpyDeviceToHost));
-    norm2_M = s0;
-    flush_stats(passes1 * (1 + fb), fb);
-    if (!(norm2_M > 0.0)) return BRSVD_ERR_ARG;
-  }
-  const double J = std::max(norm2_M, max_abs / (double)lambda);
-  double mu = mu0;
-  {
-    Region r(h, CAT_ELEM, cs);
-    BRSVD_TRY(rpca_init(M, count, (float)(1.0 / J), (float)(1.0 / mu), Y, S, X, cs));
-  }
-  int it = 0;
-  double mu_last = mu;
-  while (it < max_iters) {
-    int fb = 0;
-    const double mu_next = mu * (double)rho;
-    mu_last = mu;
-    {
-      Region total(h, CAT_TOTAL, cs);
-      BRSVD_TRY(run_sync(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
-      {
-        Region r(h, CAT_ELEM, cs);
-        BRSVD_TRY(rpca_update(M, Uw, Sw, Vtw, m, n, l, (float)mu, lambda, (float)mu_next, nullptr, S, Y, X, part,
-                              scal + 2, cs));
-      }
-      BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
-      BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-    }
-    const double res = std::sqrt(h->host_scal[2]) / normF;
-    if (residuals) residuals[it] = res;
-    flush_stats(passes1 * (1 + fb), fb);
-    ++it;
-    if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
-    mu = mu_next;
-  }
-  // L of the last iteration run: its triplets and its mu are still in place
-  {
-    Region r(h, CAT_ELEM, cs);
-    BRSVD_TRY(rpca_lowrank(Uw, Sw, Vtw, m, n, l, (float)mu_last, L, cs));
-  }
-  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-  flush_stats(0, 0);
-  if (iters_done) *iters_done = it;
-  if (stats) *stats = acc;
-  return BRSVD_OK;
+int brsvd_rpca_ialm_tol_f64(brsvd_handle h, const double* M, const double* Omegas, int32_t max_iters, double tol,
+                            double lambda, double mu0, double rho, double norm2_M, double* L, double* S, double* work,
+                            double* residuals, int32_t* iters_done, brsvd_stats* stats) {
+  if (iters_done) *iters_done = 0;
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  return rpca_loop<double>(h, M, Omegas, max_iters, tol, lambda, mu0, rho, norm2_M, L, S, work, residuals, iters_done,
+                           stats);
 }
 
 int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t iters, float lambda, float mu0,
@@ -906,14 +926,14 @@ int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* 
   double* part = h->at<double>(h->lay.rpca_part);
   double* scal = h->at<double>(h->lay.scal);
   BRSVD_TRY(pad_panel(x0, n, 1, xn, L1, cs));
-  BRSVD_TRY(rpca_norms(xn, n * L1, part, scal, cs));
-  BRSVD_TRY(scale_rsqrt(xn, n * L1, scal + 1, cs));
+  BRSVD_TRY(rpca_norms<float>(xn, n * L1, part, scal, cs));
+  BRSVD_TRY(scale_rsqrt<float>(xn, n * L1, scal + 1, cs));
   for (int it = 0; it < iters; ++it) {
     BRSVD_TRY(gemm_an(A, lda, m, n, xn, L1, ym, L1, L1, scr, scr_bytes, cs));              // y = A x
-    BRSVD_TRY(rpca_norms(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
+    BRSVD_TRY(rpca_norms<float>(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
     BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, h->b, scr, scr_bytes, cs));         // z = A^T y
-    BRSVD_TRY(rpca_norms(zn, n * L1, part, scal + 4, cs));
-    BRSVD_TRY(scale_rsqrt(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
+    BRSVD_TRY(rpca_norms<float>(zn, n * L1, part, scal + 4, cs));
+    BRSVD_TRY(scale_rsqrt<float>(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
     std::swap(xn, zn);
   }
   BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal + 3, sizeof(double), hipMemcpyDeviceToHost, cs));

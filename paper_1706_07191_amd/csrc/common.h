@@ -134,23 +134,23 @@ int small_svd(const double* R, int ldr, int l, int Lp, SvdWork& w, const int* br
 // ---- robust-PCA elementwise kernels (rpca.hip) ---------------------------------------------
 // Number of doubles of partial-sum scratch the reductions below need.
 uint64_t rpca_part_doubles(int64_t m, int64_t n);
-// scal[0] = max |M_ij|, scal[1] = ||M||_F^2 (device doubles)
-int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream);
+// scal[0] = max |M_ij|, scal[1] = ||M||_F^2 (device doubles).  T = float or double throughout.
+template <typename T> int rpca_norms(const T* M, int64_t count, double* part, double* scal, hipStream_t stream);
 // Y0 = M * inv_J, S0 = 0, X0 = M - S0 + Y0 * inv_mu
-int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y, float* S, float* X,
-              hipStream_t stream);
+template <typename T>
+int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hipStream_t stream);
 // Fused update after the SVD of X_i: L = U diag(shrink(sig, 1/mu)) Vt (contraction over l),
 // S = shrink(M - L + Y/mu, lambda/mu), Y += mu (M - L - S), *resid2_out = ||M-L-S||_F^2, and the
 // next SVD input X = M - S + Y/mu_next.  U is m x l (ld l), Vt is l x n (ld n).  Lout may be null.
-int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n,
-                int l, float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X,
-                double* part, double* resid2_out, hipStream_t stream);
-
+template <typename T>
+int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
+                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, double* resid2_out, hipStream_t stream);
 // Lout = U diag(shrink(sig, 1/mu)) Vt, the low-rank part of the iteration that used (U, sig, Vt, mu).
-int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l, float mu,
-                 float* Lout, hipStream_t stream);
+template <typename T>
+int rpca_lowrank(const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T* Lout,
+                 hipStream_t stream);
 // P[0..count) *= 1 / sqrt(*s2) (device scalar; a zero scalar zeroes P).
-int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream);
+template <typename T> int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream);
 
 // ---- device-side Gaussian generator (philox.hip) -------------------------------------------
 // Rows [row0, row0 + rows) of the m x l matrix Omega(seed) (Philox4x32-10 + Box-Muller, element

@@ -23,8 +23,9 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
 }
 
 // part[2*b] = max |M| over the block's slice, part[2*b+1] = sum M^2.
+template <typename T>
 __global__ void __launch_bounds__(256)
-k_rpca_norms(const float* __restrict__ M, int64_t count, double* __restrict__ part) {
+k_rpca_norms(const T* __restrict__ M, int64_t count, double* __restrict__ part) {
   __shared__ double sh[4];
   __shared__ double shm[4];
   double mx = 0.0, ss = 0.0;
@@ -78,45 +79,47 @@ k_sum_partials(const double* __restrict__ part, int nblocks, int per, double* __
 
 // Multiplier initialisation of Alg. 3: Y0 = M / J, S0 = 0, and the first SVD input
 // X0 = M - S0 + Y0 / mu0.
-__global__ void k_rpca_init(const float* __restrict__ M, int64_t count, float inv_J, float inv_mu,
-                            float* __restrict__ Y, float* __restrict__ S, float* __restrict__ X) {
+template <typename T>
+__global__ void k_rpca_init(const T* __restrict__ M, int64_t count, T inv_J, T inv_mu,
+                            T* __restrict__ Y, T* __restrict__ S, T* __restrict__ X) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= count) return;
-  const float mv = M[i];
-  const float y = mv * inv_J;
+  const T mv = M[i];
+  const T y = mv * inv_J;
   Y[i] = y;
-  S[i] = 0.f;
-  X[i] = fmaf(y, inv_mu, mv);
+  S[i] = T(0);
+  X[i] = fma(y, inv_mu, mv);
 }
 
-__device__ __forceinline__ float shrinkf(float x, float eps) {
-  return x > eps ? x - eps : (x < -eps ? x + eps : 0.f);
+template <typename T>
+__device__ __forceinline__ T shrinkf(T x, T eps) {
+  return x > eps ? x - eps : (x < -eps ? x + eps : T(0));
 }
 
 constexpr int kRpcaTR = 32;
 
 // acc[i] = row (row0 + rsub + i) of U diag(shrink(sigma, inv_mu)) V^T at column `col` (zero beyond n);
 // `us` (LDS, kRpcaTR x l) receives the block's rows of U scaled by the shrunk singular values.
-template <int RPT>
-__device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const float* __restrict__ sig,
-                                             const float* __restrict__ Vt, int64_t m, int64_t n, int l,
-                                             float inv_mu, int64_t row0, int rsub, int64_t col, float* us,
-                                             float (&acc)[RPT]) {
+template <typename T, int RPT>
+__device__ __forceinline__ void lowrank_tile(const T* __restrict__ U, const T* __restrict__ sig,
+                                             const T* __restrict__ Vt, int64_t m, int64_t n, int l,
+                                             T inv_mu, int64_t row0, int rsub, int64_t col, T* us,
+                                             T (&acc)[RPT]) {
   const int tid = threadIdx.x;
   for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
     const int i = idx / l, t = idx - i * l;
     const int64_t row = row0 + i;
-    const float sv = fmaxf(sig[t] - inv_mu, 0.f);      // shrinkage of a non-negative singular value
-    us[idx] = row < m ? U[row * l + t] * sv : 0.f;
+    const T sv = fmax(sig[t] - inv_mu, T(0));      // shrinkage of a non-negative singular value
+    us[idx] = row < m ? U[row * l + t] * sv : T(0);
   }
   __syncthreads();
 #pragma unroll
-  for (int i = 0; i < RPT; ++i) acc[i] = 0.f;
+  for (int i = 0; i < RPT; ++i) acc[i] = T(0);
   if (col < n) {
     for (int t = 0; t < l; ++t) {
-      const float v = Vt[(int64_t)t * n + col];
+      const T v = Vt[(int64_t)t * n + col];
 #pragma unroll
-      for (int i = 0; i < RPT; ++i) acc[i] = fmaf(us[(rsub + i) * l + t], v, acc[i]);
+      for (int i = 0; i < RPT; ++i) acc[i] = fma(us[(rsub + i) * l + t], v, acc[i]);
     }
   }
 }
@@ -131,21 +134,22 @@ __device__ __forceinline__ void lowrank_tile(const float* __restrict__ U, const 
 // L is stored only when Lout != nullptr.  CW = columns per workgroup (256, 128 or 64: narrow matrices
 // take a narrower tile so that lanes are not wasted beyond column n); the 256 threads are CW columns
 // x 256/CW row slices of kRpcaTR * CW / 256 rows each.
-template <int CW>
+template <typename T, int CW>
 __global__ void __launch_bounds__(256)
-k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const float* __restrict__ sig,
-              const float* __restrict__ Vt, int64_t m, int64_t n, int l, float inv_mu, float mu,
-              float thr_s, float inv_mu_next, float* __restrict__ Lout, float* __restrict__ S,
-              float* __restrict__ Y, float* __restrict__ X, double* __restrict__ part) {
-  extern __shared__ float us[];
+k_rpca_update(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
+              const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
+              T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
+              T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part) {
+  extern __shared__ __align__(16) unsigned char us_raw[];
+  T* us = reinterpret_cast<T*>(us_raw);
   __shared__ double sh[4];
   constexpr int RPT = kRpcaTR * CW / 256;
   const int tid = threadIdx.x;
   const int rsub = (tid / CW) * RPT;
   const int64_t col = (int64_t)blockIdx.x * CW + tid % CW;
   const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  float acc[RPT];
-  lowrank_tile<RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
+  T acc[RPT];
+  lowrank_tile<T, RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
   double z2 = 0.0;
   if (col < n) {
 #pragma unroll
@@ -153,13 +157,13 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
       const int64_t row = row0 + rsub + i;
       if (row < m) {
         const int64_t e = row * n + col;
-        const float mv = M[e], yv = Y[e], lv = acc[i];
-        const float sv = shrinkf(fmaf(yv, inv_mu, mv - lv), thr_s);
-        const float z = mv - lv - sv;
-        const float yn = fmaf(mu, z, yv);
+        const T mv = M[e], yv = Y[e], lv = acc[i];
+        const T sv = shrinkf(fma(yv, inv_mu, mv - lv), thr_s);
+        const T z = mv - lv - sv;
+        const T yn = fma(mu, z, yv);
         S[e] = sv;
         Y[e] = yn;
-        X[e] = fmaf(yn, inv_mu_next, mv - sv);
+        X[e] = fma(yn, inv_mu_next, mv - sv);
         if (Lout) Lout[e] = lv;
         z2 = fma((double)z, (double)z, z2);
       }
@@ -171,17 +175,18 @@ k_rpca_update(const float* __restrict__ M, const float* __restrict__ U, const fl
 
 // L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
 // same tile arithmetic as the update kernel, so it is the L that iteration used.
-template <int CW>
+template <typename T, int CW>
 __global__ void __launch_bounds__(256)
-k_rpca_lowrank(const float* __restrict__ U, const float* __restrict__ sig, const float* __restrict__ Vt,
-               int64_t m, int64_t n, int l, float inv_mu, float* __restrict__ Lout) {
-  extern __shared__ float us[];
+k_rpca_lowrank(const T* __restrict__ U, const T* __restrict__ sig, const T* __restrict__ Vt,
+               int64_t m, int64_t n, int l, T inv_mu, T* __restrict__ Lout) {
+  extern __shared__ __align__(16) unsigned char us_raw[];
+  T* us = reinterpret_cast<T*>(us_raw);
   constexpr int RPT = kRpcaTR * CW / 256;
   const int rsub = (threadIdx.x / CW) * RPT;
   const int64_t col = (int64_t)blockIdx.x * CW + threadIdx.x % CW;
   const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  float acc[RPT];
-  lowrank_tile<RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
+  T acc[RPT];
+  lowrank_tile<T, RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
   if (col < n) {
 #pragma unroll
     for (int i = 0; i < RPT; ++i)
@@ -201,11 +206,12 @@ static int rpca_col_tile(int64_t n) {
 }
 
 // P *= 1 / sqrt(*s2)  (normalisation of a power-method vector held in a padded panel)
-__global__ void k_scale_rsqrt(float* __restrict__ P, int64_t count, const double* __restrict__ s2) {
+template <typename T>
+__global__ void k_scale_rsqrt(T* __restrict__ P, int64_t count, const double* __restrict__ s2) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= count) return;
   const double v = *s2;
-  P[i] = v > 0.0 ? (float)((double)P[i] / sqrt(v)) : 0.f;
+  P[i] = v > 0.0 ? (T)((double)P[i] / sqrt(v)) : T(0);
 }
 
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
@@ -213,31 +219,32 @@ uint64_t rpca_part_doubles(int64_t m, int64_t n) {
   return (uint64_t)std::max<int64_t>(blocks + 64, 2 * kRpcaBlocks);   // + the first-level sums of the residual
 }
 
-int rpca_norms(const float* M, int64_t count, double* part, double* scal, hipStream_t stream) {
-  hipLaunchKernelGGL(k_rpca_norms, dim3(kRpcaBlocks), dim3(256), 0, stream, M, count, part);
+template <typename T>
+int rpca_norms(const T* M, int64_t count, double* part, double* scal, hipStream_t stream) {
+  hipLaunchKernelGGL(k_rpca_norms<T>, dim3(kRpcaBlocks), dim3(256), 0, stream, M, count, part);
   hipLaunchKernelGGL(k_rpca_norms_final, dim3(1), dim3(256), 0, stream, part, kRpcaBlocks, scal);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
-int rpca_init(const float* M, int64_t count, float inv_J, float inv_mu, float* Y, float* S, float* X,
-              hipStream_t stream) {
-  hipLaunchKernelGGL(k_rpca_init, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, M, count, inv_J,
+template <typename T>
+int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hipStream_t stream) {
+  hipLaunchKernelGGL(k_rpca_init<T>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, M, count, inv_J,
                      inv_mu, Y, S, X);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
-int rpca_update(const float* M, const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l,
-                float mu, float lambda, float mu_next, float* Lout, float* S, float* Y, float* X, double* part,
-                double* resid2_out, hipStream_t stream) {
+template <typename T>
+int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
+                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, double* resid2_out, hipStream_t stream) {
   const int cw = rpca_col_tile(n);
   dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
-  const size_t lds = (size_t)kRpcaTR * l * sizeof(float);
-#define BRSVD_RPCA_UPDATE(CW)                                                                                    \
-  hipLaunchKernelGGL(k_rpca_update<CW>, grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, 1.0f / mu, mu,     \
-                     lambda / mu, 1.0f / mu_next, Lout, S, Y, X, part)
+  const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
+#define BRSVD_RPCA_UPDATE(CW)                                                                                      \
+  hipLaunchKernelGGL((k_rpca_update<T, CW>), grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,  \
+                     lambda / mu, T(1) / mu_next, Lout, S, Y, X, part)
   if (cw == 256) BRSVD_RPCA_UPDATE(256);
   else if (cw == 128) BRSVD_RPCA_UPDATE(128);
   else BRSVD_RPCA_UPDATE(64);
@@ -256,23 +263,36 @@ int rpca_update(const float* M, const float* U, const float* sig, const float* V
   return BRSVD_OK;
 }
 
-int rpca_lowrank(const float* U, const float* sig, const float* Vt, int64_t m, int64_t n, int l, float mu,
-                 float* Lout, hipStream_t stream) {
+template <typename T>
+int rpca_lowrank(const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T* Lout,
+                 hipStream_t stream) {
   const int cw = rpca_col_tile(n);
   dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
-  const size_t lds = (size_t)kRpcaTR * l * sizeof(float);
-  if (cw == 256) hipLaunchKernelGGL(k_rpca_lowrank<256>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
-  else if (cw == 128) hipLaunchKernelGGL(k_rpca_lowrank<128>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
-  else hipLaunchKernelGGL(k_rpca_lowrank<64>, grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, 1.0f / mu, Lout);
+  const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
+  if (cw == 256) hipLaunchKernelGGL((k_rpca_lowrank<T, 256>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
+  else if (cw == 128) hipLaunchKernelGGL((k_rpca_lowrank<T, 128>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
+  else hipLaunchKernelGGL((k_rpca_lowrank<T, 64>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
 
-int scale_rsqrt(float* P, int64_t count, const double* s2, hipStream_t stream) {
-  hipLaunchKernelGGL(k_scale_rsqrt, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, P, count, s2);
+template <typename T>
+int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream) {
+  hipLaunchKernelGGL(k_scale_rsqrt<T>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, P, count, s2);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
+
+#define BRSVD_RPCA_INSTANTIATE(T)                                                                                   \
+  template int rpca_norms<T>(const T*, int64_t, double*, double*, hipStream_t);                                     \
+  template int rpca_init<T>(const T*, int64_t, T, T, T*, T*, T*, hipStream_t);                                      \
+  template int rpca_update<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, T, T*, T*, T*,   \
+                              T*, double*, double*, hipStream_t);                                                   \
+  template int rpca_lowrank<T>(const T*, const T*, const T*, int64_t, int64_t, int, T, T*, hipStream_t);            \
+  template int scale_rsqrt<T>(T*, int64_t, const double*, hipStream_t);
+BRSVD_RPCA_INSTANTIATE(float)
+BRSVD_RPCA_INSTANTIATE(double)
+#undef BRSVD_RPCA_INSTANTIATE
 
 }  // namespace brsvd

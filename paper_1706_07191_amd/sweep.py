@@ -9,7 +9,7 @@
       count of the paper's Table 1 terms written out, 2*m*n*l*(2q+2) for the passes plus
       2*(m+n)*l^2 per orthonormalisation sweep and lift, and the share of each phase.
 
-  python -m paper_1706_07191_amd.sweep rpca   [--shape MxN ...] [--iters I] [--tol T]
+  python -m paper_1706_07191_amd.sweep rpca   [--shape MxN ...] [--iters I] [--tol T] [--dtype f32|f64]
       the robust-PCA loop (Alg. 3, k = p = 10, q = 1) on a synthetic rank-5 + 5 % sparse matrix of the
       given shape (default: configuration 5 and the two shapes of the paper's Table 2): iterations,
       seconds, per-phase milliseconds per iteration and the GB/s of the pass and elementwise kernels.
@@ -136,33 +136,43 @@ def sweep_rpca(args):
     from paper_1706_07191_amd import synth
     dev = torch.device("cuda:0")
     cfg = synth.CONFIGS["C5"]
+    f64 = args.dtype == "f64"
+    esz = 8 if f64 else 4
     for shape in args.shape:
         m, n = (int(x) for x in shape.lower().split("x"))
         D, L0, S0 = synth.make_rpca(cfg, device=dev, m=m, n=n)
         Om = synth.rpca_omegas(cfg, n, args.iters, device=dev)
         lam = 1.0 / np.sqrt(max(m, n))
+        # ||M||_2 by the power method (an fp32 entry point), on an fp32 handle
         h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536)))
         try:
             x0 = synth.gaussian(n, 1, cfg.seed + 5, device=dev).reshape(-1).contiguous()
             n2 = B.brsvd_norm2_power(h, D, x0, 20)
+        finally:
+            B.brsvd_destroy(h)
+        if f64:
+            D, L0, S0, Om = D.double(), L0.double(), S0.double(), Om.double()
+        h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536),
+                                         dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32))
+        try:
             L = torch.empty_like(D)
             S = torch.empty_like(D)
-            work = torch.empty(2 * m * n, device=dev)
+            work = torch.empty(2 * m * n, device=dev, dtype=D.dtype)
             for _ in range(args.reps):
                 L, S, res, done, st = B.brsvd_rpca_ialm_tol(h, D, Om, args.iters, args.tol, lam, 1.25 / n2, 1.5,
                                                             norm2_M=n2, L=L, S=S, work=work)
         finally:
             B.brsvd_destroy(h)
-        by = 4.0 * m * n
+        by = float(esz) * m * n
         an = st["gemm_an_seconds"] / max(st["gemm_an_launches"], 1)
         at = st["gemm_at_seconds"] / max(st["gemm_at_launches"], 1)
-        print(json.dumps({"m": m, "n": n, "iterations": done, "tol": args.tol, "residual": res[-1],
+        print(json.dumps({"m": m, "n": n, "dtype": args.dtype, "iterations": done, "tol": args.tol, "residual": res[-1],
                           "seconds": round(st["total_seconds"], 6),
                           "ms_per_iteration": {key[:-8]: round(st[key] / done * 1e3, 4) for key in
                                                ("total_seconds", "gemm_an_seconds", "gemm_at_seconds", "orth_seconds",
                                                 "svd_seconds", "lift_seconds", "elementwise_seconds")},
                           "gemm_an_GBps": round(by / an / 1e9, 1), "gemm_at_GBps": round(by / at / 1e9, 1),
-                          "elementwise_GBps": round(20.0 * m * n / (st["elementwise_seconds"] / done) / 1e9, 1),
+                          "elementwise_GBps": round(5.0 * esz * m * n / (st["elementwise_seconds"] / done) / 1e9, 1),
                           "L_vs_planted": float(torch.linalg.norm(L - L0) / torch.linalg.norm(L0)),
                           "S_vs_planted": float(torch.linalg.norm(S - S0) / torch.linalg.norm(S0))}), flush=True)
         del D, L0, S0, Om, L, S, work
@@ -265,6 +275,7 @@ def main(argv=None) -> int:
     r.add_argument("--iters", type=int, default=30)
     r.add_argument("--tol", type=float, default=1e-7)
     r.add_argument("--reps", type=int, default=2)
+    r.add_argument("--dtype", default="f32", choices=["f32", "f64"])
     sub.add_parser("peaks")
     t = sub.add_parser("stream")
     t.add_argument("--rows", type=int, default=160000)

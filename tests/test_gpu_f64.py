@@ -141,3 +141,32 @@ def test_f64_seeded_random_shapes():
         U, S, Vt, st = _run64(cfg, A.pin_memory() if host else A, Om, b, **kw)
         # the fused mode squares the condition of the sketch panels: eps64 * (sigma_1 / sigma_l)^2 is still tiny
         _check64(A, Om, cfg, b if b else m, U, S, Vt, f"rand{case}", sig_tol=1e-9 if fused else SIGMA_RTOL64)
+
+
+def test_f64_rpca_matches_oracle():
+    """Alg. 3 in double precision (the precision of the paper's Table 2) against the oracle: same iteration
+    count under the stopping rule, L and S to 1e-7, residual history to 1e-6 relative."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C5"]
+    m, n = 1200, 320
+    D, L0, S0 = synth.make_rpca(cfg, m=m, n=n)
+    D = D.double()
+    Om = synth.rpca_omegas(cfg, n, 30).double()
+    lam = 1.0 / np.sqrt(max(m, n))
+    n2 = float(np.linalg.norm(D.numpy(), 2))
+    mu0 = 1.25 / n2
+    Lo, So, reso, ito = O.rpca_ialm_tol(D.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 30, 4e-5, lam, mu0, 1.5, row_block=512)
+    h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=512, dtype=B.BRSVD_DTYPE_F64))
+    try:
+        L, S, res, done, st = B.brsvd_rpca_ialm_tol(h, D.to(dev), Om.to(dev), 30, 4e-5, lam, mu0, 1.5, norm2_M=n2)
+        with pytest.raises(B.BrsvdError):
+            B.brsvd_rpca_ialm_tol(h, D.float().to(dev), Om.float().to(dev), 30, 4e-5, lam, mu0, 1.5, norm2_M=n2)
+    finally:
+        B.brsvd_destroy(h)
+    Lg, Sg = L.cpu().numpy(), S.cpu().numpy()
+    dL, dS = np.linalg.norm(Lg - Lo) / np.linalg.norm(Lo), np.linalg.norm(Sg - So) / np.linalg.norm(So)
+    note(f"[f64 rpca] iterations gpu={done} oracle={ito} L diff {dL:.3e} S diff {dS:.3e} "
+         f"last residual gpu={res[-1]:.6e} oracle={reso[-1]:.6e}")
+    assert L.dtype == torch.float64 and done == ito and st["passes_over_A"] == done * (2 * cfg.q + 2)
+    assert dL <= 1e-7 and dS <= 1e-7
+    assert np.max(np.abs(np.array(res) - reso) / reso) <= 1e-6
