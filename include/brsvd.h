@@ -44,8 +44,7 @@ enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
  * price of one skipped re-orthonormalisation per pass (panels of condition up to (s_1/s_l)^2). */
 enum { BRSVD_PASSES_SEPARATE = 0, BRSVD_PASSES_FUSED = 1 };
 /* Element type of A, Omega and the results.  F32: brsvd_run and everything else.  F64 (the precision
- * the paper measures in, Sec. 4): brsvd_run_f64 and brsvd_rpca_ialm_tol_f64 -- the same path on the
- * fp64 matrix cores. */
+ * the paper measures in, Sec. 4): the *_f64 entry points -- the same path on the fp64 matrix cores. */
 enum { BRSVD_DTYPE_F32 = 0, BRSVD_DTYPE_F64 = 1 };
 
 /* Problem statement of Alg. 1 / Alg. 2 (inputs A, k, p, q and the partition), plus where A
@@ -138,6 +137,11 @@ int brsvd_run_f64(brsvd_handle h, const double* A, int64_t lda, const double* Om
 int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega,
                    float* U, float* S, float* Vt, brsvd_stats* stats);
 
+/* brsvd_run_alg2 in double precision for a handle created with dtype == BRSVD_DTYPE_F64 (Omega, when
+ * drawn by the library, is then transformed in double: brsvd_philox_normal_f64). */
+int brsvd_run_alg2_f64(brsvd_handle h, const double* A, int64_t lda, uint64_t seed, const double* Omega,
+                       double* U, double* S, double* Vt, brsvd_stats* stats);
+
 /* Rows [row0, row0 + rows) of the Gaussian matrix Omega(seed) with `cols` columns that
  * brsvd_run_alg2 draws, written dense to out (DEVICE, rows x cols).  Element e = row*cols + col is
  * output (e & 3) of Philox4x32-10 at counter (e >> 2) with key (seed low word, seed high word),
@@ -145,6 +149,9 @@ int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, c
  * radius*cos, radius*sin of one pair, outputs 2, 3 the second pair.  Asynchronous on `stream`. */
 int brsvd_philox_normal(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, float* out,
                         void* stream);
+/* The same matrix with the Box-Muller transform evaluated in double. */
+int brsvd_philox_normal_f64(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, double* out,
+                            void* stream);
 
 /* Robust PCA by the inexact augmented Lagrange multiplier method, Alg. 3 / Eq. (3), with a
  * FIXED number of iterations; each iteration calls the randomized SVD above on
@@ -190,6 +197,8 @@ int brsvd_rpca_ialm_tol_f64(brsvd_handle h, const double* M, const double* Omega
  * dimension lda; x0: DEVICE, n floats, not zero.  Synchronises compute_stream. */
 int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* x0, int32_t iters,
                       double* norm2_out);
+int brsvd_norm2_power_f64(brsvd_handle h, const double* A, int64_t lda, const double* x0, int32_t iters,
+                          double* norm2_out);   /* the same for a BRSVD_DTYPE_F64 handle */
 
 /* Frees everything the handle owns (never the caller's buffers).  NULL is allowed. */
 int brsvd_destroy(brsvd_handle h);

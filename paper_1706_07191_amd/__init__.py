@@ -56,7 +56,7 @@ class brsvd_stats(C.Structure):
 
 
 EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol", "brsvd_rpca_ialm_tol_f64",
-           "brsvd_norm2_power", "brsvd_run_alg2", "brsvd_philox_normal", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
+           "brsvd_norm2_power", "brsvd_norm2_power_f64", "brsvd_run_alg2", "brsvd_run_alg2_f64", "brsvd_philox_normal", "brsvd_philox_normal_f64", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
            "brsvd_orth", "brsvd_small_svd"]
@@ -91,8 +91,11 @@ def lib() -> C.CDLL:
     L.brsvd_rpca_ialm_tol_f64.argtypes = [vp, vp, vp, i32, dbl, dbl, dbl, dbl, dbl, vp, vp, vp, C.POINTER(dbl),
                                           C.POINTER(i32), C.POINTER(brsvd_stats)]
     L.brsvd_norm2_power.argtypes = [vp, vp, i64, vp, i32, C.POINTER(dbl)]
+    L.brsvd_norm2_power_f64.argtypes = L.brsvd_norm2_power.argtypes
     L.brsvd_run_alg2.argtypes = [vp, vp, i64, u64, vp, vp, vp, vp, C.POINTER(brsvd_stats)]
     L.brsvd_philox_normal.argtypes = [u64, i64, i64, i32, vp, vp]
+    L.brsvd_run_alg2_f64.argtypes = L.brsvd_run_alg2.argtypes
+    L.brsvd_philox_normal_f64.argtypes = L.brsvd_philox_normal.argtypes
     L.brsvd_probe.argtypes = [i32, vp, u64, C.POINTER(dbl), C.POINTER(dbl), vp]
     L.brsvd_gemm_plan.argtypes = [i32, i64, i64, i32, i64, i32, C.POINTER(i32)]
     L.brsvd_destroy.argtypes = [vp]
@@ -195,23 +198,24 @@ def brsvd_run(handle, A, Omega, U=None, S=None, Vt=None, lda: Optional[int] = No
 
 def brsvd_run_alg2(handle, A, l, seed=0, Omega=None, lda: Optional[int] = None, want_stats=True, pinned=False,
                    device=None):
-    """Block-local scheme of Alg. 2.  A as for brsvd_run; Omega (m, l) fp32 CUDA or None (then the library
-    draws it from `seed`).  Returns (U, S, Vt, stats)."""
+    """Block-local scheme of Alg. 2.  A as for brsvd_run (fp32, or fp64 on a BRSVD_DTYPE_F64 handle); Omega
+    (m, l) CUDA of the same dtype or None (then the library draws it from `seed`).  Returns (U, S, Vt, stats)."""
     import torch
     m, n = A.shape
-    if A.dtype != torch.float32 or A.stride(1) != 1:
-        raise TypeError("A must be fp32 with unit column stride")
+    dt = A.dtype
+    if dt not in (torch.float32, torch.float64) or A.stride(1) != 1:
+        raise TypeError("A must be fp32 or fp64 with unit column stride")
     if not A.is_cuda and not (pinned or A.is_pinned()):
         raise TypeError("a host-resident A must be pinned")
     lda = lda if lda is not None else A.stride(0)
     dev = device or (Omega.device if Omega is not None else (A.device if A.is_cuda else torch.device("cuda:0")))
-    U = torch.empty(m, l, device=dev)
-    S = torch.empty(l, device=dev)
-    Vt = torch.empty(l, n, device=dev)
+    U = torch.empty(m, l, device=dev, dtype=dt)
+    S = torch.empty(l, device=dev, dtype=dt)
+    Vt = torch.empty(l, n, device=dev, dtype=dt)
     st = brsvd_stats()
-    status = lib().brsvd_run_alg2(handle, A.data_ptr(), lda, int(seed),
-                                  _dev(Omega, torch.float32, "Omega") if Omega is not None else None,
-                                  U.data_ptr(), S.data_ptr(), Vt.data_ptr(), C.byref(st) if want_stats else None)
+    fn = lib().brsvd_run_alg2_f64 if dt == torch.float64 else lib().brsvd_run_alg2
+    status = fn(handle, A.data_ptr(), lda, int(seed), _dev(Omega, dt, "Omega") if Omega is not None else None,
+                U.data_ptr(), S.data_ptr(), Vt.data_ptr(), C.byref(st) if want_stats else None)
     _check(status, "brsvd_run_alg2")
     return U, S, Vt, (st.as_dict() if want_stats else None)
 
@@ -231,12 +235,12 @@ def brsvd_probe(kind, buf, amount):
     return sec.value, work.value
 
 
-def brsvd_philox_normal(seed, rows, cols, row0=0, device="cuda:0", stream=None):
-    """Rows [row0, row0 + rows) of the Gaussian matrix brsvd_run_alg2 draws from `seed`."""
+def brsvd_philox_normal(seed, rows, cols, row0=0, device="cuda:0", stream=None, f64=False):
+    """Rows [row0, row0 + rows) of the Gaussian matrix brsvd_run_alg2 draws from `seed` (fp32, or fp64)."""
     import torch
-    out = torch.empty(rows, cols, device=device)
-    _check(lib().brsvd_philox_normal(int(seed), row0, rows, cols, out.data_ptr(), _stream_ptr(stream)),
-           "brsvd_philox_normal")
+    out = torch.empty(rows, cols, device=device, dtype=torch.float64 if f64 else torch.float32)
+    fn = lib().brsvd_philox_normal_f64 if f64 else lib().brsvd_philox_normal
+    _check(fn(int(seed), row0, rows, cols, out.data_ptr(), _stream_ptr(stream)), "brsvd_philox_normal")
     return out
 
 
@@ -279,8 +283,8 @@ def brsvd_norm2_power(handle, A, x0, iters, lda=None) -> float:
     import torch
     out = C.c_double(0.0)
     lda = A.stride(0) if lda is None else lda
-    _check(lib().brsvd_norm2_power(handle, A.data_ptr(), lda, _dev(x0, torch.float32, "x0"), iters, C.byref(out)),
-           "brsvd_norm2_power")
+    fn = lib().brsvd_norm2_power_f64 if A.dtype == torch.float64 else lib().brsvd_norm2_power
+    _check(fn(handle, A.data_ptr(), lda, _dev(x0, A.dtype, "x0"), iters, C.byref(out)), "brsvd_norm2_power")
     return out.value
 
 

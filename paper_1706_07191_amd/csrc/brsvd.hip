@@ -101,9 +101,9 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
     gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp, esz));
     gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b, esz));
   }
-  if (!host && esz == 4) {   // single-vector products of the spectral-norm power method (16-column panels)
-    gs = std::max(gs, gemm_an_scratch_bytes(m, n, kTile));
-    gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, b));
+  if (!host) {   // single-vector products of the spectral-norm power method (16-column panels)
+    gs = std::max(gs, gemm_an_scratch_bytes(m, n, kTile, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, b, esz));
   }
   gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp, esz));
   gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp, esz));
@@ -427,29 +427,30 @@ int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U,
 //   second sweep   C_I = A_I Q  (C = B^T, m x l)
 //   C = W_C R, R = Ur diag(s) Vr^T   =>   A ~ (W_C Ur) diag(s) (Q Vr)^T
 // Two reads of A whatever q is.  Omega (m x l, device) overrides the generator when not null.
-int enqueue_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega, float* U,
-                 float* S, float* Vt, int method) {
+template <typename T>
+int enqueue_alg2(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, const T* Omega, T* U, T* S, T* Vt,
+                 int method) {
   const int l = h->l, Lp = h->Lp, q = h->prm.q;
   const int64_t m = h->prm.m, n = h->prm.n;
   hipStream_t cs = h->compute;
-  OrthWork ow = orth_work(h);
+  OrthWorkT<T> ow = orth_work<T>(h);
   void* scr = h->arena + h->lay.gemm_scratch;
   const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
-  float* Yn = h->Pn(0);
-  float* Pn1 = h->Pn(1);
-  float* OmI = h->Pm(0);     // b x Lp windows of the two m x Lp panels
-  float* TI = h->Pm(1);
-  float* res;
+  T* Yn = h->Pn<T>(0);
+  T* Pn1 = h->Pn<T>(1);
+  T* OmI = h->Pm<T>(0);     // b x Lp windows of the two m x Lp panels
+  T* TI = h->Pm<T>(1);
+  T* res;
 
   Streamer st(h, A, lda);
   for (int i = 0; i < h->nblocks; ++i) {
     const int64_t rows = st.rows_of(i), r0 = (int64_t)i * h->b;
     if (Omega) BRSVD_TRY(pad_panel(Omega + r0 * l, rows, l, OmI, Lp, cs));
-    else BRSVD_TRY(philox_normal(seed, r0, rows, l, OmI, Lp, cs));
-    const float* blk = A + r0 * lda;
+    else BRSVD_TRY(philox_normal<T>(seed, r0, rows, l, OmI, Lp, cs));
+    const T* blk = A + r0 * lda;
     int64_t ldb = lda;
     if (h->host_a) { BRSVD_TRY(st.acquire(i, &blk)); ldb = n; }
-    auto at = [&](const float* Qp, float* Z, bool accumulate) {
+    auto at = [&](const T* Qp, T* Z, bool accumulate) {
       KernelEvents ke;
       bool t = kernel_events(h, CAT_AT, &ke);
       return gemm_at(blk, ldb, rows, n, Qp, Lp, Z, accumulate, rows, scr, scr_bytes, cs, t ? &ke : nullptr);
@@ -470,16 +471,16 @@ int enqueue_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, con
   }
   {
     Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Yn, Pn1, n, l, Lp, method, true, ow, nullptr, &res, cs));
+    BRSVD_TRY(orth_panel<T>(Yn, Pn1, n, l, Lp, method, true, ow, nullptr, &res, cs));
     if (res != Yn) std::swap(Yn, Pn1);
   }
-  float* Cm = h->Pm(0);
-  float* Tm = h->Pm(1);
-  BRSVD_TRY(pass_an(h, A, lda, Yn, Cm));                 // second sweep: C = A Q
+  T* Cm = h->Pm<T>(0);
+  T* Tm = h->Pm<T>(1);
+  BRSVD_TRY(pass_an<T>(h, A, lda, Yn, Cm));                 // second sweep: C = A Q
   double* Rtot = h->at<double>(h->lay.Rtot);
   {
     Region r(h, CAT_ORTH, cs);
-    BRSVD_TRY(orth_panel(Cm, Tm, m, l, Lp, method, true, ow, Rtot, &res, cs));
+    BRSVD_TRY(orth_panel<T>(Cm, Tm, m, l, Lp, method, true, ow, Rtot, &res, cs));
     if (res != Cm) std::swap(Cm, Tm);
   }
   SvdWork sw;
@@ -487,11 +488,11 @@ int enqueue_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, con
   sw.J = h->at<double>(h->lay.svdJ);
   sw.sig = h->at<double>(h->lay.sig);
   sw.info = h->at<int>(h->lay.flags) + 4;
-  float* XV = h->at<float>(h->lay.XV);
-  float* XU = h->at<float>(h->lay.XU);
+  T* XV = h->at<T>(h->lay.XV);
+  T* XU = h->at<T>(h->lay.XU);
   {
     Region r(h, CAT_SVD, cs);
-    BRSVD_TRY(small_svd(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
+    BRSVD_TRY(small_svd<T>(Rtot, Lp, l, Lp, sw, ow.flags, nullptr, S, XV, XU, nullptr, nullptr, cs));
   }
   {
     Region r(h, CAT_LIFT, cs);
@@ -610,6 +611,57 @@ int run_with_stats(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U
   }
   return status;
 }
+
+template <typename T>
+int run_alg2_with_stats(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, const T* Omega, T* U, T* S, T* Vt,
+                        brsvd_stats* stats) {
+  if (!A || !U || !S || !Vt) return BRSVD_ERR_ARG;
+  if (lda < h->prm.n) return BRSVD_ERR_ARG;
+  reset_timing(h, stats != nullptr);
+  int fallbacks = 0, status;
+  {
+    Region total(h, CAT_TOTAL, h->compute);
+    status = run_sync_with(h, &fallbacks,
+                           [&](int method) { return enqueue_alg2<T>(h, A, lda, seed, Omega, U, S, Vt, method); });
+  }
+  if (stats) {
+    (void)hipStreamSynchronize(h->compute);
+    fill_stats(h, stats, 2 * (1 + fallbacks), fallbacks);
+  }
+  return status;
+}
+
+// ---- power method for ||A||_2, both element types --------------------------------------------------
+template <typename T>
+int norm2_power_impl(brsvd_handle h, const T* A, int64_t lda, const T* x0, int32_t iters, double* norm2_out) {
+  if (!A || !x0 || !norm2_out || iters < 1 || lda < h->prm.n || h->host_a) return BRSVD_ERR_ARG;
+  const int64_t m = h->prm.m, n = h->prm.n;
+  const int L1 = kTile;                 // the vector travels as column 0 of a 16-column padded panel
+  hipStream_t cs = h->compute;
+  T* xn = h->Pn<T>(0);
+  T* zn = h->Pn<T>(1);
+  T* ym = h->Pm<T>(0);
+  void* scr = h->arena + h->lay.gemm_scratch;
+  const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
+  double* part = h->at<double>(h->lay.rpca_part);
+  double* scal = h->at<double>(h->lay.scal);
+  BRSVD_TRY(pad_panel(x0, n, 1, xn, L1, cs));
+  BRSVD_TRY(rpca_norms<T>(xn, n * L1, part, scal, cs));
+  BRSVD_TRY(scale_rsqrt<T>(xn, n * L1, scal + 1, cs));
+  for (int it = 0; it < iters; ++it) {
+    BRSVD_TRY(gemm_an(A, lda, m, n, xn, L1, ym, L1, L1, scr, scr_bytes, cs));              // y = A x
+    BRSVD_TRY(rpca_norms<T>(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
+    BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, h->b, scr, scr_bytes, cs));         // z = A^T y
+    BRSVD_TRY(rpca_norms<T>(zn, n * L1, part, scal + 4, cs));
+    BRSVD_TRY(scale_rsqrt<T>(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
+    std::swap(xn, zn);
+  }
+  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal + 3, sizeof(double), hipMemcpyDeviceToHost, cs));
+  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
+  *norm2_out = std::sqrt(h->host_scal[0]);
+  return BRSVD_OK;
+}
+
 
 // ---- robust PCA loop (Alg. 3), both element types -----------------------------------------------
 template <typename T>
@@ -850,20 +902,14 @@ int brsvd_run_f64(brsvd_handle h, const double* A, int64_t lda, const double* Om
 
 int brsvd_run_alg2(brsvd_handle h, const float* A, int64_t lda, uint64_t seed, const float* Omega, float* U,
                    float* S, float* Vt, brsvd_stats* stats) {
-  if (!h || !A || !U || !S || !Vt) return BRSVD_ERR_ARG;
-  if (lda < h->prm.n || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
-  reset_timing(h, stats != nullptr);
-  int fallbacks = 0, status;
-  {
-    Region total(h, CAT_TOTAL, h->compute);
-    status = run_sync_with(h, &fallbacks,
-                           [&](int method) { return enqueue_alg2(h, A, lda, seed, Omega, U, S, Vt, method); });
-  }
-  if (stats) {
-    (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, 2 * (1 + fallbacks), fallbacks);
-  }
-  return status;
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
+  return run_alg2_with_stats<float>(h, A, lda, seed, Omega, U, S, Vt, stats);
+}
+
+int brsvd_run_alg2_f64(brsvd_handle h, const double* A, int64_t lda, uint64_t seed, const double* Omega, double* U,
+                       double* S, double* Vt, brsvd_stats* stats) {
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  return run_alg2_with_stats<double>(h, A, lda, seed, Omega, U, S, Vt, stats);
 }
 
 int brsvd_gemm_plan(int32_t which, int64_t rows, int64_t n, int32_t l, int64_t block_rows, int32_t dtype,
@@ -883,7 +929,12 @@ int brsvd_probe(int32_t kind, void* buf, uint64_t amount, double* seconds, doubl
 
 int brsvd_philox_normal(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, float* out, void* stream) {
   if (!out || rows < 1 || cols < 1 || row0 < 0) return BRSVD_ERR_ARG;
-  return philox_normal(seed, row0, rows, cols, out, cols, (hipStream_t)stream);
+  return philox_normal<float>(seed, row0, rows, cols, out, cols, (hipStream_t)stream);
+}
+
+int brsvd_philox_normal_f64(uint64_t seed, int64_t row0, int64_t rows, int32_t cols, double* out, void* stream) {
+  if (!out || rows < 1 || cols < 1 || row0 < 0) return BRSVD_ERR_ARG;
+  return philox_normal<double>(seed, row0, rows, cols, out, cols, (hipStream_t)stream);
 }
 
 int brsvd_rpca_ialm_tol(brsvd_handle h, const float* M, const float* Omegas, int32_t max_iters, double tol,
@@ -913,33 +964,14 @@ int brsvd_rpca_ialm(brsvd_handle h, const float* M, const float* Omegas, int32_t
 
 int brsvd_norm2_power(brsvd_handle h, const float* A, int64_t lda, const float* x0, int32_t iters,
                       double* norm2_out) {
-  if (!h || !A || !x0 || !norm2_out || iters < 1 || lda < h->prm.n || h->host_a) return BRSVD_ERR_ARG;
-  if (h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
-  const int64_t m = h->prm.m, n = h->prm.n;
-  const int L1 = kTile;                 // the vector travels as column 0 of a 16-column padded panel
-  hipStream_t cs = h->compute;
-  float* xn = h->Pn(0);
-  float* zn = h->Pn(1);
-  float* ym = h->Pm(0);
-  void* scr = h->arena + h->lay.gemm_scratch;
-  const uint64_t scr_bytes = h->lay.gemm_scratch_bytes;
-  double* part = h->at<double>(h->lay.rpca_part);
-  double* scal = h->at<double>(h->lay.scal);
-  BRSVD_TRY(pad_panel(x0, n, 1, xn, L1, cs));
-  BRSVD_TRY(rpca_norms<float>(xn, n * L1, part, scal, cs));
-  BRSVD_TRY(scale_rsqrt<float>(xn, n * L1, scal + 1, cs));
-  for (int it = 0; it < iters; ++it) {
-    BRSVD_TRY(gemm_an(A, lda, m, n, xn, L1, ym, L1, L1, scr, scr_bytes, cs));              // y = A x
-    BRSVD_TRY(rpca_norms<float>(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
-    BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, h->b, scr, scr_bytes, cs));         // z = A^T y
-    BRSVD_TRY(rpca_norms<float>(zn, n * L1, part, scal + 4, cs));
-    BRSVD_TRY(scale_rsqrt<float>(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
-    std::swap(xn, zn);
-  }
-  BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal, scal + 3, sizeof(double), hipMemcpyDeviceToHost, cs));
-  BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-  *norm2_out = std::sqrt(h->host_scal[0]);
-  return BRSVD_OK;
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F32) return BRSVD_ERR_ARG;
+  return norm2_power_impl<float>(h, A, lda, x0, iters, norm2_out);
+}
+
+int brsvd_norm2_power_f64(brsvd_handle h, const double* A, int64_t lda, const double* x0, int32_t iters,
+                          double* norm2_out) {
+  if (!h || h->prm.dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
+  return norm2_power_impl<double>(h, A, lda, x0, iters, norm2_out);
 }
 
 const char* brsvd_status_string(int status) {

@@ -155,7 +155,8 @@ template <typename T> int scale_rsqrt(T* P, int64_t count, const double* s2, hip
 // ---- device-side Gaussian generator (philox.hip) -------------------------------------------
 // Rows [row0, row0 + rows) of the m x l matrix Omega(seed) (Philox4x32-10 + Box-Muller, element
 // e = row*l + col from output e&3 of counter e>>2) into out (rows x ld, columns l..ld-1 zeroed).
-int philox_normal(uint64_t seed, int64_t row0, int64_t rows, int l, float* out, int ld, hipStream_t stream);
+template <typename T>
+int philox_normal(uint64_t seed, int64_t row0, int64_t rows, int l, T* out, int ld, hipStream_t stream);
 
 // ---- machine probes (probe.hip) -------------------------------------------------------------
 int probe(int kind, void* buf, uint64_t amount, double* seconds, double* work, hipStream_t stream);

@@ -143,18 +143,13 @@ def sweep_rpca(args):
         D, L0, S0 = synth.make_rpca(cfg, device=dev, m=m, n=n)
         Om = synth.rpca_omegas(cfg, n, args.iters, device=dev)
         lam = 1.0 / np.sqrt(max(m, n))
-        # ||M||_2 by the power method (an fp32 entry point), on an fp32 handle
-        h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536)))
-        try:
-            x0 = synth.gaussian(n, 1, cfg.seed + 5, device=dev).reshape(-1).contiguous()
-            n2 = B.brsvd_norm2_power(h, D, x0, 20)
-        finally:
-            B.brsvd_destroy(h)
+        x0 = synth.gaussian(n, 1, cfg.seed + 5, device=dev).reshape(-1).contiguous()
         if f64:
-            D, L0, S0, Om = D.double(), L0.double(), S0.double(), Om.double()
+            D, L0, S0, Om, x0 = D.double(), L0.double(), S0.double(), Om.double(), x0.double()
         h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536),
                                          dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32))
         try:
+            n2 = B.brsvd_norm2_power(h, D, x0, 20)
             L = torch.empty_like(D)
             S = torch.empty_like(D)
             work = torch.empty(2 * m * n, device=dev, dtype=D.dtype)

@@ -170,3 +170,51 @@ def test_f64_rpca_matches_oracle():
     assert L.dtype == torch.float64 and done == ito and st["passes_over_A"] == done * (2 * cfg.q + 2)
     assert dL <= 1e-7 and dS <= 1e-7
     assert np.max(np.abs(np.array(res) - reso) / reso) <= 1e-6
+
+
+def test_f64_alg2_and_generator_match_oracle():
+    """The block-local scheme and the device-side generator in double precision.  In fp64 even the
+    configuration-2 spectrum with q = 2 ((s_1/s_k)^5 = 4e10, lost in fp32) is resolved."""
+    from oracle import philox as PX
+    dev = need_gpu()
+    g = B.brsvd_philox_normal(2 ** 40 + 17, 257, 110, 12345, f64=True).cpu().numpy()
+    o = PX.philox_normal(2 ** 40 + 17, 257, 110, 12345)
+    assert np.max(np.abs(g - o) / (1.0 + np.abs(o))) <= 1e-14
+    for name, m, n, b, q in (("C2", 3000, 2500, 700, 2), ("C4", 2600, 1500, 640, 1)):
+        cfg = synth.CONFIGS[name].scaled(m, n, b)
+        cfg.q = q
+        A = cfg.make_A().double()
+        seed = 2 ** 33 + 99
+        Om = PX.philox_normal(seed, m, cfg.l)
+        h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, q, row_block=b, dtype=B.BRSVD_DTYPE_F64))
+        try:
+            U, S, Vt, st = B.brsvd_run_alg2(h, A.to(dev), cfg.l, seed=seed)
+        finally:
+            B.brsvd_destroy(h)
+        Uo, so, Vto = O.brsvd_alg2(A.numpy(), Om, cfg.k, cfg.p, q, row_block=b)
+        sg, k = S.cpu().numpy(), cfg.k
+        sig = float(np.max(np.abs(sg[:k] - so[:k]) / so[:k]))
+        eg = O.recon_error(A.numpy(), U.cpu().numpy(), sg, Vt.cpu().numpy(), k=k)
+        eo = O.recon_error(A.numpy(), Uo, so, Vto, k=k)
+        note(f"[f64 alg2 {name} q={q}] sigma_rel={sig:.3e} err_gpu={eg:.6e} err_oracle={eo:.6e} "
+             f"fallbacks={st['orth_fallbacks']}")
+        assert st["passes_over_A"] == 2 * (1 + st["orth_fallbacks"])
+        assert sig <= (1e-6 if q == 2 else 1e-10)         # q = 2: the sketch has condition 4e10, eps64 * that = 1e-5 at worst
+        assert abs(eg - eo) <= 1e-6 * eo
+        assert O.orth_defect(U.cpu().numpy()) <= ORTH_TOL64 and O.orth_defect(Vt.cpu().numpy().T) <= ORTH_TOL64
+
+
+def test_f64_norm2_power_matches_oracle():
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C5"]
+    m, n = 1200, 320
+    D = synth.make_rpca(cfg, m=m, n=n)[0].double()
+    x0 = synth.gaussian(n, 1, cfg.seed + 99, dtype=torch.float64).reshape(-1)
+    h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=256, dtype=B.BRSVD_DTYPE_F64))
+    try:
+        for iters in (1, 3, 20):
+            got = B.brsvd_norm2_power(h, D.to(dev), x0.to(dev), iters)
+            want = O.norm2_power(D.numpy(), x0.numpy(), iters)
+            assert abs(got - want) <= 1e-12 * want
+    finally:
+        B.brsvd_destroy(h)
