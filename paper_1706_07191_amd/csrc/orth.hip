@@ -415,6 +415,7 @@ __global__ void k_triu_mul(const double* __restrict__ R2, const double* __restri
   if (idx >= l * l) return;
   int i = idx / l, c = idx - i * l;
   double s = 0.0;
+#pragma unroll 8
   for (int k = i; k <= c; ++k) s = fma(R2[(int64_t)i * Lp + k], R1[(int64_t)k * Lp + c], s);
   Rtot[(int64_t)i * Lp + c] = s;
 }

@@ -418,6 +418,7 @@ __global__ void k_svd_outputs(const double* __restrict__ R, int ldr, const doubl
       v = wrow[kk] / s;
       const double* rrow = R + (int64_t)kk * ldr;
       double acc = 0.0;
+#pragma unroll 8
       for (int t = 0; t < l; ++t) acc = fma(rrow[t], wrow[t], acc);
       u = acc / (s * s);
     }
