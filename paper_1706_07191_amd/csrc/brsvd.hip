@@ -7,8 +7,8 @@
 //   last pass       B^T = A^T * Q                 gemm_at     B^T = W_B * R_B (orth, R kept)
 //   small SVD       R_B = Ur diag(s) Vr^T         Jacobi
 //   lifts           U = Q * Vr,  V = W_B * Ur, V^T stored
-// Device-resident A: each pass is one launch over all row blocks (the blocks only shape the
-// order of the partial sums of A^T * Q).  Host-resident A: each block is copied into one of two
+// Device-resident A: each pass is one launch over all rows (the row blocks matter only when A is
+// streamed, and in the block-local scheme).  Host-resident A: each block is copied into one of two
 // staging buffers on the copy stream while the other is being multiplied on the compute stream.
 #include <algorithm>
 #include <cmath>
@@ -94,16 +94,18 @@ Layout make_layout(const brsvd_params& p, int64_t b) {
   for (int i = 0; i < 2; ++i) L.Pn[i] = take((uint64_t)n * Lp * esz);
   // split-sum scratch: the largest of every GEMM shape issued by the driver
   uint64_t gs = 0;
-  if (host) {
-    gs = std::max(gs, gemm_an_scratch_bytes(b, n, Lp, esz));
-    gs = std::max(gs, gemm_at_scratch_bytes(b, n, Lp, b, esz));
-  } else {
+  // products on one row block (streamed A, and the block-local scheme on any A), also on a ragged last block
+  for (int64_t rows : {b, m - (m - 1) / b * b}) {
+    gs = std::max(gs, gemm_an_scratch_bytes(rows, n, Lp, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(rows, n, Lp, rows, esz));
+  }
+  if (!host) {   // device-resident A: one launch over all rows
     gs = std::max(gs, gemm_an_scratch_bytes(m, n, Lp, esz));
-    gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, b, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, Lp, m, esz));
   }
   if (!host) {   // single-vector products of the spectral-norm power method (16-column panels)
     gs = std::max(gs, gemm_an_scratch_bytes(m, n, kTile, esz));
-    gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, b, esz));
+    gs = std::max(gs, gemm_at_scratch_bytes(m, n, kTile, m, esz));
   }
   gs = std::max(gs, gemm_an_scratch_bytes(m, Lp, Lp, esz));
   gs = std::max(gs, gemm_an_scratch_bytes(n, Lp, Lp, esz));
@@ -288,7 +290,9 @@ int pass_at(brsvd_handle h, const T* A, int64_t lda, const T* Q, T* Z) {
   if (!h->host_a) {
     KernelEvents ke;
     bool t = kernel_events(h, CAT_AT, &ke);
-    return gemm_at(A, lda, m, n, Q, Lp, Z, false, h->b, scr, h->lay.gemm_scratch_bytes, h->compute,
+    // device-resident A: one launch over all rows; the row range is cut into equal sub-ranges whose partial
+    // panels are added in row order (the row blocks matter only when A is streamed block by block)
+    return gemm_at(A, lda, m, n, Q, Lp, Z, false, m, scr, h->lay.gemm_scratch_bytes, h->compute,
                    t ? &ke : nullptr);
   }
   Streamer st(h, A, lda);
@@ -651,7 +655,7 @@ int norm2_power_impl(brsvd_handle h, const T* A, int64_t lda, const T* x0, int32
   for (int it = 0; it < iters; ++it) {
     BRSVD_TRY(gemm_an(A, lda, m, n, xn, L1, ym, L1, L1, scr, scr_bytes, cs));              // y = A x
     BRSVD_TRY(rpca_norms<T>(ym, m * L1, part, scal + 2, cs));                                  // est^2 = |y|^2
-    BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, h->b, scr, scr_bytes, cs));         // z = A^T y
+    BRSVD_TRY(gemm_at(A, lda, m, n, ym, L1, zn, false, m, scr, scr_bytes, cs));            // z = A^T y
     BRSVD_TRY(rpca_norms<T>(zn, n * L1, part, scal + 4, cs));
     BRSVD_TRY(scale_rsqrt<T>(zn, n * L1, scal + 5, cs));                                       // x = z / |z|
     std::swap(xn, zn);
