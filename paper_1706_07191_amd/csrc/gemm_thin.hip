@@ -508,7 +508,7 @@ static int pick_splits(int64_t tiles, int slots, int64_t units, double out_over_
   if (e && atoi(e) > 0) return (int)std::min<int64_t>(atoi(e), units);
   int best = 1;
   double best_score = -1.0;
-  const int smax = (int)std::min<int64_t>(units, 128);
+  const int smax = (int)std::min<int64_t>(units, 4096);   // long split sums are reduced in two levels
   for (int sp = 1; sp <= smax; ++sp) {
     const int64_t per = ceil_div(units, sp);
     const int64_t eff_sp = ceil_div(units, per);          // splits actually produced
