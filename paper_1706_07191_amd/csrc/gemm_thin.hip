@@ -541,9 +541,12 @@ struct AnCfg {
   int mt, waves, kc;
 };
 // Tile shapes picked from sweeps on MI355X (see the launch templates below, which must agree).
-static AnCfg an_cfg(int nt, int esz) {
+constexpr int64_t kAnWideK = 1024;
+static AnCfg an_cfg(int nt, int esz, int64_t K) {
   if (esz == 8) return {nt >= 5 ? 1 : 2, 4, 32};   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
-  if (nt <= 8) return {2, 4, 64};
+  // eight waves share one staged panel chunk (half the staging per MFMA); short contractions keep four-wave
+  // workgroups, i.e. twice as many of them
+  if (nt <= 8) return {2, K >= kAnWideK ? 8 : 4, 64};
   return {2, 4, 32};
 }
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
@@ -555,13 +558,13 @@ struct AnPlan {
 // See AnShape.  Short contractions (the R^-1 applies and lifts: fewer than 16 chunks) and launches
 // with very many tiles keep one whole tile per workgroup.
 static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
-  AnCfg c = an_cfg(nt, esz);
+  AnCfg c = an_cfg(nt, esz, K);
   AnPlan p;
   p.tile_rows = c.waves * c.mt * 16;
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
   const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * esz;
-  const int wg_regs = esz == 8 ? 2 : (nt <= 14 ? 2 : 1);   // workgroups per CU the registers allow
+  const int wg_regs = esz == 8 ? 2 : (nt <= 8 ? (c.waves == 8 ? 1 : 2) : (nt <= 14 ? 2 : 1));   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
   const char* e = getenv("BRSVD_AN_SPLITS");
@@ -628,13 +631,21 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
     return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
   } else {
     constexpr int MT = (sizeof(T) == 8 && NT >= 5) ? 1 : 2;
-    constexpr int WAVES = 4;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
-    if (vec)
-      return launch_an_inst<T, NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
+    if constexpr (sizeof(T) == 4 && NT <= 8) {
+      if (K >= kAnWideK) {
+        if (vec)
+          return launch_an_inst<T, NT, MT, 8, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
                                                         split_stride, p, stream);
-    return launch_an_inst<T, NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
+        return launch_an_inst<T, NT, MT, 8, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
                                                        split_stride, p, stream);
+      }
+    }
+    if (vec)
+      return launch_an_inst<T, NT, MT, 4, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
+                                                    p, stream);
+    return launch_an_inst<T, NT, MT, 4, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
+                                                   p, stream);
   }
 }
 
