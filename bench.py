@@ -26,7 +26,7 @@ PEAK_MFMA_F32_TFLOPS = 157.3  # dense fp32 MFMA
 PEAK_MFMA_F64_TFLOPS = 78.6   # dense fp64 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a plain
 # 1 GiB copy (profiles/gemm_thin_C2_hbm_traffic.md).  Counters cannot be read from inside the timed run.
-MEASURED_HBM_TRAFFIC = {"C2:gemm_an": 1.799e9, "C2:gemm_at": 1.850e9}
+MEASURED_HBM_TRAFFIC = {"C2:gemm_an": 1.725e9, "C2:gemm_at": 1.850e9}
 
 
 def main() -> int:
