@@ -547,7 +547,7 @@ static AnCfg an_cfg(int nt, int esz, int64_t K) {
   // eight waves share one staged panel chunk (half the staging per MFMA); short contractions keep four-wave
   // workgroups, i.e. twice as many of them
   if (nt <= 8) return {2, K >= kAnWideK ? 8 : 4, 64};
-  return {2, 4, 32};
+  return {nt > 14 ? 1 : 2, 8, 32};
 }
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
 static double traffic_weight(int nt) { return nt <= 2 ? 1.0 : (nt <= 4 ? 0.6 : 0.3); }
@@ -564,7 +564,7 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
   const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * esz;
-  const int wg_regs = esz == 8 ? 2 : (nt <= 8 ? (c.waves == 8 ? 1 : 2) : (nt <= 14 ? 2 : 1));   // workgroups per CU the registers allow
+  const int wg_regs = esz == 8 ? 2 : (c.waves == 8 ? 1 : 2);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
   const char* e = getenv("BRSVD_AN_SPLITS");
@@ -630,7 +630,7 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
   if constexpr (sizeof(T) == 8 && NT > 8) {
     return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
   } else {
-    constexpr int MT = (sizeof(T) == 8 && NT >= 5) ? 1 : 2;
+    constexpr int MT = ((sizeof(T) == 8 && NT >= 5) || NT > 14) ? 1 : 2;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
     if constexpr (sizeof(T) == 4 && NT <= 8) {
       if (K >= kAnWideK) {
@@ -641,10 +641,11 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
                                                        split_stride, p, stream);
       }
     }
+    constexpr int W = NT > 8 ? 8 : 4;
     if (vec)
-      return launch_an_inst<T, NT, MT, 4, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
+      return launch_an_inst<T, NT, MT, W, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
                                                     p, stream);
-    return launch_an_inst<T, NT, MT, 4, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
+    return launch_an_inst<T, NT, MT, W, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
                                                    p, stream);
   }
 }
