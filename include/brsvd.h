@@ -84,8 +84,8 @@ typedef struct {
   int64_t gemm_an_launches;
   int64_t gemm_at_launches;
   int64_t passes_over_A;       /* number of full reads of A                                    */
-  int64_t bytes_A_streamed;    /* passes * 4*m*n                                               */
-  int32_t orth_fallbacks;      /* panels that took the TSQR route after a Cholesky breakdown   */
+  int64_t bytes_A_streamed;    /* passes * element size * m * n                                */
+  int32_t orth_fallbacks;      /* reruns on the TSQR route after a Cholesky breakdown (0 or 1)  */
   int32_t jacobi_sweeps;       /* sweeps of the last small SVD                                 */
   int32_t row_block;           /* rows per block actually used                                 */
   int32_t n_blocks;
