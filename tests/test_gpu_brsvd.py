@@ -108,6 +108,32 @@ def test_seeded_random_shapes_against_oracle():
         check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b if b else m, U, S, Vt, f"rand{case}")
 
 
+def test_zero_and_nonfinite_inputs_end_with_a_status():
+    """A = 0 has no range to orthonormalise: every route reports the breakdown as a status (no hang, no
+    crash); the handle stays usable.  NaN input: the call returns (values unspecified)."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C1"].scaled(600, 400, 256)
+    Om = cfg.make_Omega().to(dev)
+    h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=256))
+    try:
+        with pytest.raises(B.BrsvdError) as ei:
+            B.brsvd_run(h, torch.zeros(cfg.m, cfg.n, device=dev), Om)
+        assert ei.value.status == B.BRSVD_ERR_ORTH_BREAKDOWN
+        A = cfg.make_A().to(dev)
+        U, S, Vt, st = B.brsvd_run(h, A, Om)                      # the same handle afterwards
+        check_against_oracle(A.cpu().numpy(), Om.cpu().numpy(), cfg.k, cfg.p, cfg.q, 256, U, S, Vt, "after-zero")
+        An = A.clone()
+        An[17, 23] = float("nan")
+        try:
+            B.brsvd_run(h, An, Om)
+        except B.BrsvdError:
+            pass
+        U2, S2, Vt2, _ = B.brsvd_run(h, A, Om)
+        assert torch.equal(S, S2)
+    finally:
+        B.brsvd_destroy(h)
+
+
 def test_caller_streams():
     """Caller-owned compute and copy streams (default priority): in-core on a side stream, and host-resident A
     with both streams supplied; results equal the default-stream runs bit for bit."""
