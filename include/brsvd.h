@@ -246,6 +246,18 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R,
 int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr,
                     int32_t* sweeps, void* stream);
 
+/* brsvd_small_svd for callers that cannot allocate device memory (code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and same
+ * results, but the scratch of the Jacobi iteration lives in a device array that is part of the library
+ * (4 MiB per GPU the library is used on, held until the process ends), so the call makes no
+ * hipMalloc / hipFree.  l <= 512 is what the array is sized for; a larger l returns BRSVD_ERR_BUDGET.
+ * The address of the array is looked up on the first call on each device.  All calls on one GPU share
+ * that GPU's array: calls that overlap on one GPU (different streams or threads) race and must be
+ * serialised by the caller.  Nothing in the array has to be cleared between calls (every kernel writes
+ * what it later reads), so a call is not affected by what an earlier, larger one left behind. */
+int brsvd_small_svd_static(const double* R, int32_t l, double* S, double* Ur, double* Vr,
+                           int32_t* sweeps, void* stream);
+
 /* How the two thin products would be cut into workgroups (host-only, no GPU call): for checking the
  * plans' invariants and for reading profiles.  which = 0: Y = A X with A rows x n, out12 = {rows per
  * tile, row tiles, chunks per tile C, whole tiles, leftover tiles, main splits f, tail chunks x, tail

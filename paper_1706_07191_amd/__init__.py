@@ -59,7 +59,7 @@ EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64"
            "brsvd_norm2_power", "brsvd_norm2_power_f64", "brsvd_run_alg2", "brsvd_run_alg2_f64", "brsvd_philox_normal", "brsvd_philox_normal_f64", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
            "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
            "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
-           "brsvd_orth", "brsvd_small_svd"]
+           "brsvd_orth", "brsvd_small_svd", "brsvd_small_svd_static"]
 
 _lib = None
 
@@ -111,6 +111,7 @@ def lib() -> C.CDLL:
     L.brsvd_gemm_scratch_bytes_f64.restype = u64
     L.brsvd_orth.argtypes = [vp, i64, i32, i32, vp, C.POINTER(i32), vp]
     L.brsvd_small_svd.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
+    L.brsvd_small_svd_static.argtypes = L.brsvd_small_svd.argtypes
     for name in EXPORTS:
         if name not in ("brsvd_status_string", "brsvd_gemm_scratch_bytes", "brsvd_gemm_scratch_bytes_f64"):
             getattr(L, name).restype = C.c_int
@@ -344,17 +345,25 @@ def brsvd_orth(P, method=BRSVD_ORTH_AUTO, want_R=False, stream=None):
     return P, R, bool(fb.value)
 
 
-def brsvd_small_svd(R, stream=None):
-    """One-sided Jacobi SVD of an l x l fp64 CUDA matrix: returns (S, Ur, Vr, sweeps)."""
+def brsvd_small_svd(R, stream=None, out=None, static=False):
+    """One-sided Jacobi SVD of an l x l fp64 CUDA matrix: returns (S, Ur, Vr, sweeps).  out = (S, Ur, Vr)
+    reuses the caller's tensors; static=True calls brsvd_small_svd_static (no device allocation in the library)."""
     import torch
     l = R.shape[0]
-    S = torch.empty(l, dtype=torch.float64, device=R.device)
-    Ur = torch.empty(l, l, dtype=torch.float64, device=R.device)
-    Vr = torch.empty(l, l, dtype=torch.float64, device=R.device)
+    if out is None:
+        out = (torch.empty(l, dtype=torch.float64, device=R.device),
+               torch.empty(l, l, dtype=torch.float64, device=R.device),
+               torch.empty(l, l, dtype=torch.float64, device=R.device))
+    S, Ur, Vr = out
     sw = C.c_int32(0)
-    _check(lib().brsvd_small_svd(_dev(R, torch.float64, "R"), l, S.data_ptr(), Ur.data_ptr(), Vr.data_ptr(),
-                                 C.byref(sw), _stream_ptr(stream)), "brsvd_small_svd")
+    fn = lib().brsvd_small_svd_static if static else lib().brsvd_small_svd
+    _check(fn(_dev(R, torch.float64, "R"), l, _dev(S, torch.float64, "S"), _dev(Ur, torch.float64, "Ur"),
+              _dev(Vr, torch.float64, "Vr"), C.byref(sw), _stream_ptr(stream)), "brsvd_small_svd")
     return S, Ur, Vr, sw.value
+
+
+def brsvd_small_svd_static(R, stream=None, out=None):
+    return brsvd_small_svd(R, stream=stream, out=out, static=True)
 
 
 class PinnedMatrix:

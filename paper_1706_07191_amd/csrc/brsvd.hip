@@ -14,6 +14,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -24,7 +25,7 @@ using namespace brsvd;
 namespace {
 
 constexpr uint64_t kAlign = 256;
-inline uint64_t align_up(uint64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+constexpr uint64_t align_up(uint64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 enum Cat { CAT_AN = 0, CAT_AT, CAT_ORTH, CAT_SVD, CAT_LIFT, CAT_COPY, CAT_ELEM, CAT_TOTAL, CAT_COUNT };
 
@@ -801,6 +802,70 @@ int step_gemm_at(const T* A, int64_t lda, int64_t rows, int64_t n, const T* Q, i
   return unpad_panel(Zp, n, Lp, l, Z, accumulate != 0, s);
 }
 
+// ---- small SVD on a given scratch buffer ---------------------------------------------------------
+// Scratch of small_svd: the rows being rotated and one more Lp x Lp fp64 matrix, 3*Lp doubles (norms,
+// sorted values, order) and a few integer flags.  Nothing in it has to be initialised: every kernel
+// writes what it later reads.
+constexpr uint64_t small_svd_scratch_bytes(int Lp) {
+  return 2 * align_up((uint64_t)Lp * Lp * 8) + align_up((uint64_t)3 * Lp * 8) + 256;
+}
+
+int small_svd_on_scratch(const double* R, int l, double* S, double* Ur, double* Vr, int32_t* sweeps, char* buf,
+                         hipStream_t s) {
+  const int Lp = padded_l(l);
+  const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8);
+  SvdWork w;
+  w.W = (double*)buf;
+  w.J = (double*)(buf + sq8);
+  w.sig = (double*)(buf + 2 * sq8);
+  w.info = (int*)(buf + 2 * sq8 + align_up((uint64_t)3 * Lp * 8));
+  int status = small_svd<float>(R, l, l, Lp, w, nullptr, S, nullptr, nullptr, nullptr, Ur, Vr, s);
+  int info[2] = {0, 0};
+  if (status == BRSVD_OK) {
+    if (hipMemcpyAsync(info, w.info, sizeof(info), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      status = BRSVD_ERR_HIP;
+  }
+  (void)hipStreamSynchronize(s);
+  if (status == BRSVD_OK) {
+    if (sweeps) *sweeps = info[0];
+    if (!info[1]) status = BRSVD_ERR_SVD_NOCONV;
+  }
+  return status;
+}
+
+// Scratch of brsvd_small_svd_static: a device array that is part of the loaded code object, so callers
+// that may not allocate device memory can still run the small SVD.  Every GPU the library runs on holds
+// its own copy (4.0 MiB) at its own address until the process ends.  `scratch` is only the host-side name
+// of the symbol: the device address is looked up once per device and kept in g_static_scratch.
+constexpr int kStaticSvdMaxL = 512;
+constexpr uint64_t kStaticScratchBytes = small_svd_scratch_bytes(kStaticSvdMaxL);
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_scratch_mutex;
+char* g_static_scratch[kMaxDevices];
+
+int static_scratch_of_current_device(char** out) {
+  int dev = -1;
+  BRSVD_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return BRSVD_ERR_ARG;
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    BRSVD_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return BRSVD_ERR_HIP;
+    g_static_scratch[dev] = (char*)p;
+  }
+  *out = g_static_scratch[dev];
+  return BRSVD_OK;
+}
+
 }  // namespace
 
 // ================================================================================================
@@ -1075,31 +1140,20 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int
 
 int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps, void* stream) {
   if (!R || !S || !Ur || !Vr || l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
-  const int Lp = padded_l(l);
-  hipStream_t s = (hipStream_t)stream;
-  const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8);
-  const uint64_t total = 2 * sq8 + align_up((uint64_t)3 * Lp * 8) + 256;
   char* buf = nullptr;
-  if (hipMalloc((void**)&buf, total) != hipSuccess) return BRSVD_ERR_ALLOC;
-  SvdWork w;
-  w.W = (double*)buf;
-  w.J = (double*)(buf + sq8);
-  w.sig = (double*)(buf + 2 * sq8);
-  w.info = (int*)(buf + 2 * sq8 + align_up((uint64_t)3 * Lp * 8));
-  int status = small_svd<float>(R, l, l, Lp, w, nullptr, S, nullptr, nullptr, nullptr, Ur, Vr, s);
-  int info[2] = {0, 0};
-  if (status == BRSVD_OK) {
-    if (hipMemcpyAsync(info, w.info, sizeof(info), hipMemcpyDeviceToHost, s) != hipSuccess ||
-        hipStreamSynchronize(s) != hipSuccess)
-      status = BRSVD_ERR_HIP;
-  }
-  (void)hipStreamSynchronize(s);
+  if (hipMalloc((void**)&buf, small_svd_scratch_bytes(padded_l(l))) != hipSuccess) return BRSVD_ERR_ALLOC;
+  const int status = small_svd_on_scratch(R, l, S, Ur, Vr, sweeps, buf, (hipStream_t)stream);
   (void)hipFree(buf);
-  if (status == BRSVD_OK) {
-    if (sweeps) *sweeps = info[0];
-    if (!info[1]) status = BRSVD_ERR_SVD_NOCONV;
-  }
   return status;
+}
+
+int brsvd_small_svd_static(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps,
+                           void* stream) {
+  if (!R || !S || !Ur || !Vr || l < 1) return BRSVD_ERR_ARG;
+  if (l > kStaticSvdMaxL) return BRSVD_ERR_BUDGET;        // beyond what the static array was sized for
+  char* buf = nullptr;
+  BRSVD_TRY(static_scratch_of_current_device(&buf));
+  return small_svd_on_scratch(R, l, S, Ur, Vr, sweeps, buf, (hipStream_t)stream);
 }
 
 }  // extern "C"
