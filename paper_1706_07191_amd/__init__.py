@@ -38,7 +38,8 @@ class brsvd_params(C.Structure):
                 ("row_block", C.c_int64), ("device_budget_bytes", C.c_uint64),
                 ("orth_method", C.c_int32), ("pass_mode", C.c_int32),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
-                ("dtype", C.c_int32), ("timing_level", C.c_int32)]
+                ("dtype", C.c_int32), ("timing_level", C.c_int32),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64)]
 
 
 class brsvd_stats(C.Structure):
@@ -49,17 +50,23 @@ class brsvd_stats(C.Structure):
                 ("gemm_an_launches", C.c_int64), ("gemm_at_launches", C.c_int64),
                 ("passes_over_A", C.c_int64), ("bytes_A_streamed", C.c_int64),
                 ("orth_fallbacks", C.c_int32), ("jacobi_sweeps", C.c_int32),
-                ("row_block", C.c_int32), ("n_blocks", C.c_int32)]
+                ("row_block", C.c_int32), ("n_blocks", C.c_int32),
+                ("split_sum_seconds", C.c_double), ("rpca_update_seconds", C.c_double),
+                ("rpca_update_launches", C.c_int64), ("bytes_A_read_by_kernels", C.c_int64)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}
 
 
-EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm", "brsvd_rpca_ialm_tol", "brsvd_rpca_ialm_tol_f64",
-           "brsvd_norm2_power", "brsvd_norm2_power_f64", "brsvd_run_alg2", "brsvd_run_alg2_f64", "brsvd_philox_normal", "brsvd_philox_normal_f64", "brsvd_probe", "brsvd_gemm_plan", "brsvd_destroy",
-           "brsvd_status_string", "brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes",
-           "brsvd_gemm_an_f64", "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64",
-           "brsvd_orth", "brsvd_small_svd", "brsvd_small_svd_static"]
+# entry points declared in include/brsvd.h (the product calls) and include/brsvd_steps.h (the steps)
+EXPORTS = ["brsvd_workspace_bytes", "brsvd_create", "brsvd_run", "brsvd_run_f64", "brsvd_rpca_ialm",
+           "brsvd_rpca_ialm_tol", "brsvd_rpca_ialm_tol_f64", "brsvd_norm2_power", "brsvd_norm2_power_f64",
+           "brsvd_run_alg2", "brsvd_run_alg2_f64", "brsvd_philox_normal", "brsvd_philox_normal_f64",
+           "brsvd_destroy", "brsvd_status_string"]
+STEP_EXPORTS = ["brsvd_gemm_an", "brsvd_gemm_at", "brsvd_gemm_scratch_bytes", "brsvd_gemm_an_f64",
+                "brsvd_gemm_at_f64", "brsvd_gemm_scratch_bytes_f64", "brsvd_orth", "brsvd_orth_scratch_bytes",
+                "brsvd_small_svd", "brsvd_small_svd_scratch_bytes", "brsvd_small_svd_static", "brsvd_gemm_plan",
+                "brsvd_probe"]
 
 _lib = None
 
@@ -104,16 +111,20 @@ def lib() -> C.CDLL:
     L.brsvd_gemm_an.argtypes = [vp, i64, i64, i64, vp, i32, vp, vp, u64, vp]
     L.brsvd_gemm_at.argtypes = [vp, i64, i64, i64, vp, i32, vp, i32, vp, u64, vp]
     L.brsvd_gemm_scratch_bytes.argtypes = [i64, i64, i32]
-    L.brsvd_gemm_scratch_bytes.restype = u64
     L.brsvd_gemm_an_f64.argtypes = L.brsvd_gemm_an.argtypes
     L.brsvd_gemm_at_f64.argtypes = L.brsvd_gemm_at.argtypes
     L.brsvd_gemm_scratch_bytes_f64.argtypes = [i64, i64, i32]
-    L.brsvd_gemm_scratch_bytes_f64.restype = u64
-    L.brsvd_orth.argtypes = [vp, i64, i32, i32, vp, C.POINTER(i32), vp]
-    L.brsvd_small_svd.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
-    L.brsvd_small_svd_static.argtypes = L.brsvd_small_svd.argtypes
-    for name in EXPORTS:
-        if name not in ("brsvd_status_string", "brsvd_gemm_scratch_bytes", "brsvd_gemm_scratch_bytes_f64"):
+    L.brsvd_orth.argtypes = [vp, i64, i32, i32, vp, C.POINTER(i32), vp, u64, vp]
+    L.brsvd_orth_scratch_bytes.argtypes = [i64, i32]
+    L.brsvd_small_svd.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp, u64, vp]
+    L.brsvd_small_svd_scratch_bytes.argtypes = [i32]
+    L.brsvd_small_svd_static.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32), vp]
+    sizes = ("brsvd_gemm_scratch_bytes", "brsvd_gemm_scratch_bytes_f64", "brsvd_orth_scratch_bytes",
+             "brsvd_small_svd_scratch_bytes")
+    for name in EXPORTS + STEP_EXPORTS:
+        if name in sizes:
+            getattr(L, name).restype = u64
+        elif name != "brsvd_status_string":
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -146,8 +157,12 @@ def _dev(t, dtype, name):
 
 def make_params(m, n, k, p, q, row_block=0, device_budget_bytes=0, a_location=BRSVD_A_DEVICE,
                 orth_method=BRSVD_ORTH_AUTO, compute_stream=None, copy_stream=None,
-                pass_mode=BRSVD_PASSES_SEPARATE, dtype=BRSVD_DTYPE_F32, timing_level=0) -> brsvd_params:
-    return brsvd_params(m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
+                pass_mode=BRSVD_PASSES_SEPARATE, dtype=BRSVD_DTYPE_F32, timing_level=0,
+                workspace=None) -> brsvd_params:
+    """workspace: optional CUDA uint8 tensor the handle uses instead of allocating (keep it alive)."""
+    return brsvd_params(workspace=workspace.data_ptr() if workspace is not None else None,
+                        workspace_bytes=workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                        m=m, n=n, k=k, p=p, q=q, a_location=a_location, row_block=row_block,
                         device_budget_bytes=device_budget_bytes, orth_method=orth_method, pass_mode=pass_mode,
                         compute_stream=_stream_ptr(compute_stream),
                         copy_stream=_stream_ptr(copy_stream) if copy_stream is not None else None,
@@ -334,20 +349,27 @@ def brsvd_gemm_at(A, Q, Z=None, accumulate=False, lda=None, stream=None):
     return Z
 
 
+def _byte_scratch(nbytes, device):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
 def brsvd_orth(P, method=BRSVD_ORTH_AUTO, want_R=False, stream=None):
     """In-place orthonormalisation of the columns of P (rows, l).  Returns (P, R or None, fallback)."""
     import torch
     rows, l = P.shape
     R = torch.empty(l, l, dtype=torch.float64, device=P.device) if want_R else None
     fb = C.c_int32(0)
+    nbytes = lib().brsvd_orth_scratch_bytes(rows, l)
+    scr = _byte_scratch(nbytes, P.device)
     _check(lib().brsvd_orth(_dev(P, torch.float32, "P"), rows, l, method, R.data_ptr() if want_R else None,
-                            C.byref(fb), _stream_ptr(stream)), "brsvd_orth")
+                            C.byref(fb), scr.data_ptr(), nbytes, _stream_ptr(stream)), "brsvd_orth")
     return P, R, bool(fb.value)
 
 
 def brsvd_small_svd(R, stream=None, out=None, static=False):
     """One-sided Jacobi SVD of an l x l fp64 CUDA matrix: returns (S, Ur, Vr, sweeps).  out = (S, Ur, Vr)
-    reuses the caller's tensors; static=True calls brsvd_small_svd_static (no device allocation in the library)."""
+    reuses the caller's tensors; static=True calls brsvd_small_svd_static (scratch inside the library)."""
     import torch
     l = R.shape[0]
     if out is None:
@@ -356,9 +378,14 @@ def brsvd_small_svd(R, stream=None, out=None, static=False):
                torch.empty(l, l, dtype=torch.float64, device=R.device))
     S, Ur, Vr = out
     sw = C.c_int32(0)
-    fn = lib().brsvd_small_svd_static if static else lib().brsvd_small_svd
-    _check(fn(_dev(R, torch.float64, "R"), l, _dev(S, torch.float64, "S"), _dev(Ur, torch.float64, "Ur"),
-              _dev(Vr, torch.float64, "Vr"), C.byref(sw), _stream_ptr(stream)), "brsvd_small_svd")
+    args = (_dev(R, torch.float64, "R"), l, _dev(S, torch.float64, "S"), _dev(Ur, torch.float64, "Ur"),
+            _dev(Vr, torch.float64, "Vr"), C.byref(sw))
+    if static:
+        _check(lib().brsvd_small_svd_static(*args, _stream_ptr(stream)), "brsvd_small_svd_static")
+    else:
+        nbytes = lib().brsvd_small_svd_scratch_bytes(l)
+        scr = _byte_scratch(nbytes, R.device)
+        _check(lib().brsvd_small_svd(*args, scr.data_ptr(), nbytes, _stream_ptr(stream)), "brsvd_small_svd")
     return S, Ur, Vr, sw.value
 
 

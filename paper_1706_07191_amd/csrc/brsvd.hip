@@ -18,6 +18,7 @@
 #include <new>
 #include <vector>
 
+#include "brsvd_steps.h"
 #include "common.h"
 
 using namespace brsvd;
@@ -27,7 +28,7 @@ namespace {
 constexpr uint64_t kAlign = 256;
 constexpr uint64_t align_up(uint64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-enum Cat { CAT_AN = 0, CAT_AT, CAT_ORTH, CAT_SVD, CAT_LIFT, CAT_COPY, CAT_ELEM, CAT_TOTAL, CAT_COUNT };
+enum Cat { CAT_AN = 0, CAT_AT, CAT_ORTH, CAT_SVD, CAT_LIFT, CAT_COPY, CAT_ELEM, CAT_TOTAL, CAT_SUM, CAT_UPD, CAT_COUNT };
 
 struct Layout {
   // offsets into the arena
@@ -56,7 +57,10 @@ struct brsvd_handle_s {
   std::vector<std::pair<int, int>> regions[CAT_COUNT];
   size_t ev_used;
   bool timing;
+  bool own_arena;                  // false: the arena is the caller's workspace
   int64_t launches[CAT_COUNT];
+  int64_t bytes_A_kernels;         // bytes of A (or of its staged blocks) read by the pass kernels
+  int64_t bytes_A_copied;          // bytes of A copied host -> device
 
   int esz() const { return prm.dtype == BRSVD_DTYPE_F64 ? 8 : 4; }
   template <typename T = float> T* Pm(int i) { return (T*)(arena + lay.Pm[i]); }
@@ -78,6 +82,7 @@ int validate(const brsvd_params* p) {
   if (p->pass_mode != BRSVD_PASSES_SEPARATE && p->pass_mode != BRSVD_PASSES_FUSED) return BRSVD_ERR_ARG;
   if (p->dtype != BRSVD_DTYPE_F32 && p->dtype != BRSVD_DTYPE_F64) return BRSVD_ERR_ARG;
   if (p->timing_level != 0 && p->timing_level != 1) return BRSVD_ERR_ARG;
+  if (p->workspace && ((uintptr_t)p->workspace) % kAlign != 0) return BRSVD_ERR_ARG;
   return BRSVD_OK;
 }
 
@@ -143,6 +148,8 @@ int resolve_block(const brsvd_params& p, int64_t* b_out) {
   const bool host = p.a_location == BRSVD_A_HOST_PINNED;
   int64_t b = p.row_block > 0 ? std::min<int64_t>(p.row_block, p.m) : 0;
   uint64_t budget = p.device_budget_bytes;
+  if (p.workspace) budget = budget ? std::min<uint64_t>(budget, p.workspace_bytes) : p.workspace_bytes;
+  if (p.workspace && budget == 0) return BRSVD_ERR_BUDGET;
   if (b == 0) {
     if (!host) {
       b = p.m;
@@ -163,7 +170,7 @@ int resolve_block(const brsvd_params& p, int64_t* b_out) {
       b = std::min<int64_t>(lo * 256, p.m);
     }
   }
-  if (p.device_budget_bytes && make_layout(p, b).total > p.device_budget_bytes) return BRSVD_ERR_BUDGET;
+  if ((p.device_budget_bytes || p.workspace) && make_layout(p, b).total > budget) return BRSVD_ERR_BUDGET;
   *b_out = b;
   return BRSVD_OK;
 }
@@ -176,7 +183,7 @@ struct Region {
   Region(brsvd_handle h_, int cat_, hipStream_t s_) : h(h_), cat(cat_), s(s_), i0(-1) {
     if (!h->timing || h->ev_used + 2 > h->ev.size()) return;
     // timing_level 1: only the pass kernels, the copies and the whole call are timed
-    if (h->prm.timing_level == 1 && cat != CAT_TOTAL && cat != CAT_COPY) return;
+    if (h->prm.timing_level == 1 && cat != CAT_TOTAL && cat != CAT_COPY && cat != CAT_UPD) return;
     i0 = (int)h->ev_used;
     h->ev_used += 2;
     (void)hipEventRecord(h->ev[i0], s);
@@ -188,15 +195,20 @@ struct Region {
   }
 };
 
-// A pair of events from the pool for tight per-kernel timing; registered under `cat`.
-bool kernel_events(brsvd_handle h, int cat, KernelEvents* ke) {
+// Accounts for one pass-kernel launch that reads `rows` rows of A, and hands out events from the pool
+// for tight per-kernel timing: one pair registered under `cat`, one under CAT_SUM for the split sums.
+bool kernel_events(brsvd_handle h, int cat, int64_t rows, KernelEvents* ke) {
   h->launches[cat]++;
-  if (!h->timing || h->ev_used + 2 > h->ev.size()) return false;
+  h->bytes_A_kernels += rows * h->prm.n * h->esz();
+  if (!h->timing || h->ev_used + 4 > h->ev.size()) return false;
   int i0 = (int)h->ev_used;
-  h->ev_used += 2;
+  h->ev_used += 4;
   ke->start = h->ev[i0];
   ke->stop = h->ev[i0 + 1];
+  ke->sum_start = h->ev[i0 + 2];
+  ke->sum_stop = h->ev[i0 + 3];
   h->regions[cat].push_back({i0, i0 + 1});
+  h->regions[CAT_SUM].push_back({i0 + 2, i0 + 3});
   return true;
 }
 
@@ -235,6 +247,7 @@ struct Streamer {
     const size_t esz = (size_t)h->esz();
     const char* src = A + (int64_t)i * h->b * lda * esz;
     const int64_t rows = rows_of(i), n = h->prm.n;
+    h->bytes_A_copied += rows * n * (int64_t)esz;
     Region r(h, CAT_COPY, h->copy);
     if (lda == n) {
       BRSVD_HIP_TRY(hipMemcpyAsync(dst, src, (size_t)rows * n * esz, hipMemcpyHostToDevice, h->copy));
@@ -267,7 +280,7 @@ int pass_an(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Y) {
   void* scr = h->arena + h->lay.gemm_scratch;
   if (!h->host_a) {
     KernelEvents ke;
-    bool t = kernel_events(h, CAT_AN, &ke);
+    bool t = kernel_events(h, CAT_AN, m, &ke);
     return gemm_an(A, lda, m, n, X, Lp, Y, Lp, Lp, scr, h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr);
   }
   Streamer st(h, A, lda);
@@ -275,7 +288,7 @@ int pass_an(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Y) {
     const T* blk;
     BRSVD_TRY(st.acquire(i, &blk));
     KernelEvents ke;
-    bool t = kernel_events(h, CAT_AN, &ke);
+    bool t = kernel_events(h, CAT_AN, st.rows_of(i), &ke);
     BRSVD_TRY(gemm_an(blk, n, st.rows_of(i), n, X, Lp, Y + (int64_t)i * h->b * Lp, Lp, Lp, scr,
                       h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr));
     BRSVD_TRY(st.release(i));
@@ -290,7 +303,7 @@ int pass_at(brsvd_handle h, const T* A, int64_t lda, const T* Q, T* Z) {
   void* scr = h->arena + h->lay.gemm_scratch;
   if (!h->host_a) {
     KernelEvents ke;
-    bool t = kernel_events(h, CAT_AT, &ke);
+    bool t = kernel_events(h, CAT_AT, m, &ke);
     // device-resident A: one launch over all rows; the row range is cut into equal sub-ranges whose partial
     // panels are added in row order (the row blocks matter only when A is streamed block by block)
     return gemm_at(A, lda, m, n, Q, Lp, Z, false, m, scr, h->lay.gemm_scratch_bytes, h->compute,
@@ -301,7 +314,7 @@ int pass_at(brsvd_handle h, const T* A, int64_t lda, const T* Q, T* Z) {
     const T* blk;
     BRSVD_TRY(st.acquire(i, &blk));
     KernelEvents ke;
-    bool t = kernel_events(h, CAT_AT, &ke);
+    bool t = kernel_events(h, CAT_AT, st.rows_of(i), &ke);
     BRSVD_TRY(gemm_at(blk, n, st.rows_of(i), n, Q + (int64_t)i * h->b * Lp, Lp, Z, i > 0, st.rows_of(i), scr,
                       h->lay.gemm_scratch_bytes, h->compute, t ? &ke : nullptr));
     BRSVD_TRY(st.release(i));
@@ -326,10 +339,10 @@ int pass_fused(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Tm_, T* Z
     BRSVD_TRY(st.acquire(i, &blk));
     T* Ti = Tm_ + (int64_t)i * h->b * Lp;
     KernelEvents ke;
-    bool t = kernel_events(h, CAT_AN, &ke);
+    bool t = kernel_events(h, CAT_AN, st.rows_of(i), &ke);
     BRSVD_TRY(gemm_an(blk, n, st.rows_of(i), n, X, Lp, Ti, Lp, Lp, scr, h->lay.gemm_scratch_bytes, h->compute,
                       t ? &ke : nullptr));
-    t = kernel_events(h, CAT_AT, &ke);
+    t = kernel_events(h, CAT_AT, st.rows_of(i), &ke);
     BRSVD_TRY(gemm_at(blk, n, st.rows_of(i), n, Ti, Lp, Z, i > 0, st.rows_of(i), scr, h->lay.gemm_scratch_bytes,
                       h->compute, t ? &ke : nullptr));
     BRSVD_TRY(st.release(i));
@@ -457,7 +470,7 @@ int enqueue_alg2(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, const T
     if (h->host_a) { BRSVD_TRY(st.acquire(i, &blk)); ldb = n; }
     auto at = [&](const T* Qp, T* Z, bool accumulate) {
       KernelEvents ke;
-      bool t = kernel_events(h, CAT_AT, &ke);
+      bool t = kernel_events(h, CAT_AT, rows, &ke);
       return gemm_at(blk, ldb, rows, n, Qp, Lp, Z, accumulate, rows, scr, scr_bytes, cs, t ? &ke : nullptr);
     };
     if (q == 0) {
@@ -466,7 +479,7 @@ int enqueue_alg2(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, const T
       BRSVD_TRY(at(OmI, Pn1, false));
       for (int t = 0; t < q; ++t) {
         KernelEvents ke;
-        bool tm = kernel_events(h, CAT_AN, &ke);
+        bool tm = kernel_events(h, CAT_AN, rows, &ke);
         BRSVD_TRY(gemm_an(blk, ldb, rows, n, Pn1, Lp, TI, Lp, Lp, scr, scr_bytes, cs, tm ? &ke : nullptr));
         const bool last = t == q - 1;
         BRSVD_TRY(at(TI, last ? Yn : Pn1, last && i > 0));
@@ -508,13 +521,10 @@ int enqueue_alg2(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, const T
   return BRSVD_OK;
 }
 
-int passes_per_run(brsvd_handle h) {
-  return h->prm.pass_mode == BRSVD_PASSES_FUSED ? h->prm.q + 1 : 2 * h->prm.q + 2;
-}
-
 void reset_timing(brsvd_handle h, bool on) {
   h->timing = on;
   h->ev_used = 0;
+  h->bytes_A_kernels = h->bytes_A_copied = 0;
   for (int c = 0; c < CAT_COUNT; ++c) { h->regions[c].clear(); h->launches[c] = 0; }
 }
 
@@ -527,7 +537,9 @@ double sum_regions(brsvd_handle h, int cat) {
   return s;
 }
 
-void fill_stats(brsvd_handle h, brsvd_stats* st, int passes, int fallbacks) {
+// Reads of A are counted where they happen: a host-resident A is read over the host link by the block
+// copies (the kernels then read the staged blocks), a device-resident A by the pass kernels themselves.
+void fill_stats(brsvd_handle h, brsvd_stats* st, int fallbacks) {
   std::memset(st, 0, sizeof(*st));
   st->total_seconds = sum_regions(h, CAT_TOTAL);
   st->gemm_an_seconds = sum_regions(h, CAT_AN);
@@ -539,8 +551,12 @@ void fill_stats(brsvd_handle h, brsvd_stats* st, int passes, int fallbacks) {
   st->elementwise_seconds = sum_regions(h, CAT_ELEM);
   st->gemm_an_launches = h->launches[CAT_AN];
   st->gemm_at_launches = h->launches[CAT_AT];
-  st->passes_over_A = passes;
-  st->bytes_A_streamed = (int64_t)passes * h->esz() * h->prm.m * h->prm.n;
+  st->split_sum_seconds = sum_regions(h, CAT_SUM);
+  st->rpca_update_seconds = sum_regions(h, CAT_UPD);
+  st->rpca_update_launches = h->launches[CAT_UPD];
+  st->bytes_A_streamed = h->host_a ? h->bytes_A_copied : h->bytes_A_kernels;
+  st->bytes_A_read_by_kernels = h->bytes_A_kernels;
+  st->passes_over_A = st->bytes_A_streamed / ((int64_t)h->esz() * h->prm.m * h->prm.n);
   st->orth_fallbacks = fallbacks;
   st->jacobi_sweeps = h->host_flags[1];
   st->row_block = (int32_t)h->b;
@@ -556,10 +572,14 @@ void add_stats(brsvd_stats* acc, const brsvd_stats& s) {
   acc->lift_seconds += s.lift_seconds;
   acc->copy_seconds += s.copy_seconds;
   acc->elementwise_seconds += s.elementwise_seconds;
+  acc->split_sum_seconds += s.split_sum_seconds;
+  acc->rpca_update_seconds += s.rpca_update_seconds;
+  acc->rpca_update_launches += s.rpca_update_launches;
   acc->gemm_an_launches += s.gemm_an_launches;
   acc->gemm_at_launches += s.gemm_at_launches;
   acc->passes_over_A += s.passes_over_A;
   acc->bytes_A_streamed += s.bytes_A_streamed;
+  acc->bytes_A_read_by_kernels += s.bytes_A_read_by_kernels;
   acc->orth_fallbacks += s.orth_fallbacks;
   acc->jacobi_sweeps = s.jacobi_sweeps;
   acc->row_block = s.row_block;
@@ -578,7 +598,16 @@ int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
       // the staging buffers start out free
       for (int i = 0; i < 2; ++i) BRSVD_HIP_TRY(hipEventRecord(h->drained[i], h->compute));
     }
-    BRSVD_TRY(enqueue(method));
+    {
+      // an error part-way leaves kernels and copies queued that still touch the caller's buffers and the
+      // staging blocks: drain both streams before handing the status back
+      const int st = enqueue(method);
+      if (st != BRSVD_OK) {
+        (void)hipStreamSynchronize(h->compute);
+        if (h->host_a) (void)hipStreamSynchronize(h->copy);
+        return st;
+      }
+    }
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags, dflags, sizeof(int), hipMemcpyDeviceToHost, h->compute));
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags + 1, dflags + 4, 2 * sizeof(int), hipMemcpyDeviceToHost,
                                  h->compute));
@@ -612,7 +641,7 @@ int run_with_stats(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U
   }
   if (stats) {
     (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, passes_per_run(h) * (1 + fallbacks), fallbacks);
+    fill_stats(h, stats, fallbacks);
   }
   return status;
 }
@@ -631,7 +660,7 @@ int run_alg2_with_stats(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, 
   }
   if (stats) {
     (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, 2 * (1 + fallbacks), fallbacks);
+    fill_stats(h, stats, fallbacks);
   }
   return status;
 }
@@ -688,11 +717,11 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   double* scal = h->at<double>(h->lay.scal);
   brsvd_stats acc;
   std::memset(&acc, 0, sizeof(acc));
-  auto flush_stats = [&](int passes, int fallbacks) {
+  auto flush_stats = [&](int fallbacks) {
     if (!stats) return;
     (void)hipStreamSynchronize(cs);
     brsvd_stats one;
-    fill_stats(h, &one, passes, fallbacks);
+    fill_stats(h, &one, fallbacks);
     add_stats(&acc, one);
     reset_timing(h, true);
   };
@@ -707,7 +736,6 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   BRSVD_HIP_TRY(hipStreamSynchronize(cs));
   const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
   if (!(normF > 0.0)) return BRSVD_ERR_ARG;
-  const int passes1 = passes_per_run(h);
   if (!(norm2_M > 0.0)) {
     int fb = 0;
     {
@@ -717,7 +745,7 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
     T s0 = T(0);
     BRSVD_HIP_TRY(hipMemcpy(&s0, Sw, sizeof(T), hipMemcpyDeviceToHost));
     norm2_M = (double)s0;
-    flush_stats(passes1 * (1 + fb), fb);
+    flush_stats(fb);
     if (!(norm2_M > 0.0)) return BRSVD_ERR_ARG;
   }
   const double J = std::max(norm2_M, max_abs / (double)lambda);
@@ -737,15 +765,19 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
       BRSVD_TRY(run_sync<T>(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
       {
         Region r(h, CAT_ELEM, cs);
-        BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part,
-                                 scal + 2, cs));
+        {
+          Region u(h, CAT_UPD, cs);
+          h->launches[CAT_UPD]++;
+          BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part, cs));
+        }
+        BRSVD_TRY(rpca_residual_sum(part, m, n, scal + 2, cs));
       }
       BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
       BRSVD_HIP_TRY(hipStreamSynchronize(cs));
     }
     const double res = std::sqrt(h->host_scal[2]) / normF;
     if (residuals) residuals[it] = res;
-    flush_stats(passes1 * (1 + fb), fb);
+    flush_stats(fb);
     ++it;
     if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
     mu = mu_next;
@@ -756,7 +788,7 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
     BRSVD_TRY(rpca_lowrank<T>(Uw, Sw, Vtw, m, n, l, (T)mu_last, L, cs));
   }
   BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-  flush_stats(0, 0);
+  flush_stats(0);
   if (iters_done) *iters_done = it;
   if (stats) *stats = acc;
   return BRSVD_OK;
@@ -882,9 +914,7 @@ int brsvd_workspace_bytes(const brsvd_params* params, uint64_t* bytes_out) {
   return BRSVD_OK;
 }
 
-int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
-  if (!handle_out) return BRSVD_ERR_ARG;
-  *handle_out = nullptr;
+static int create_impl(const brsvd_params* params, brsvd_handle* handle_out) {
   BRSVD_TRY(validate(params));
   int64_t b;
   BRSVD_TRY(resolve_block(*params, &b));
@@ -905,10 +935,15 @@ int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
   h->host_scal = nullptr;
   h->ev_used = 0;
   h->timing = false;
+  h->own_arena = params->workspace == nullptr;
   for (int i = 0; i < 2; ++i) { h->filled[i] = nullptr; h->drained[i] = nullptr; }
   int status = BRSVD_OK;
   do {
-    if (hipMalloc((void**)&h->arena, h->lay.total) != hipSuccess) { status = BRSVD_ERR_ALLOC; break; }
+    if (h->own_arena) {
+      if (hipMalloc((void**)&h->arena, h->lay.total) != hipSuccess) { status = BRSVD_ERR_ALLOC; break; }
+    } else {
+      h->arena = (char*)params->workspace;      // resolve_block has checked that it is large enough
+    }
     if (hipMemset(h->arena + h->lay.gram_part, 0, (size_t)h->lay.gram_chunks * h->Lp * h->Lp * 8) != hipSuccess) {
       status = BRSVD_ERR_HIP; break;
     }
@@ -927,8 +962,12 @@ int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
       }
       if (!ok) { status = BRSVD_ERR_HIP; break; }
     }
-    const size_t pool = 64 + (size_t)h->nblocks * 8 * (2 * params->q + 2);
-    h->ev.resize(pool, nullptr);
+    // per block and pass at most two products (4 events each) and one copy (2 events)
+    const size_t pool = 64 + (size_t)h->nblocks * 12 * (2 * params->q + 2);
+    try {
+      h->ev.resize(pool, nullptr);
+      for (int c = 0; c < CAT_COUNT; ++c) h->regions[c].reserve(pool / 2);   // no growth while a run records
+    } catch (...) { status = BRSVD_ERR_ALLOC; break; }
     bool ok = true;
     for (size_t i = 0; i < pool && ok; ++i) ok = hipEventCreate(&h->ev[i]) == hipSuccess;
     if (!ok) { status = BRSVD_ERR_HIP; break; }
@@ -939,6 +978,16 @@ int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
   }
   *handle_out = h;
   return BRSVD_OK;
+}
+
+int brsvd_create(const brsvd_params* params, brsvd_handle* handle_out) {
+  if (!handle_out) return BRSVD_ERR_ARG;
+  *handle_out = nullptr;
+  try {
+    return create_impl(params, handle_out);
+  } catch (...) {            // nothing may propagate across the C boundary
+    return BRSVD_ERR_ALLOC;
+  }
 }
 
 int brsvd_destroy(brsvd_handle h) {
@@ -952,7 +1001,7 @@ int brsvd_destroy(brsvd_handle h) {
   if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
   if (h->host_flags) (void)hipHostFree(h->host_flags);
   if (h->host_scal) (void)hipHostFree(h->host_scal);
-  if (h->arena) (void)hipFree(h->arena);
+  if (h->arena && h->own_arena) (void)hipFree(h->arena);
   delete h;
   return BRSVD_OK;
 }
@@ -988,7 +1037,13 @@ int brsvd_gemm_plan(int32_t which, int64_t rows, int64_t n, int32_t l, int64_t b
   const int esz = dtype == BRSVD_DTYPE_F64 ? 8 : 4;
   if (which == 0) gemm_an_plan_describe(rows, n, padded_l(l), esz, out12);
   else if (which == 1) gemm_at_plan_describe(rows, n, padded_l(l), block_rows, esz, out12);
-  else return BRSVD_ERR_ARG;
+  else if (which == 2) {
+    const uint64_t an = gemm_an_scratch_bytes(rows, n, padded_l(l), esz);
+    const uint64_t at = gemm_at_scratch_bytes(rows, n, padded_l(l), block_rows, esz);
+    for (int i = 0; i < 12; ++i) out12[i] = 0;
+    out12[0] = (int32_t)(an & 0x7fffffff); out12[1] = (int32_t)(an >> 31);
+    out12[2] = (int32_t)(at & 0x7fffffff); out12[3] = (int32_t)(at >> 31);
+  } else return BRSVD_ERR_ARG;
   return BRSVD_OK;
 }
 
@@ -1078,38 +1133,57 @@ int brsvd_gemm_at_f64(const double* A, int64_t lda, int64_t rows, int64_t n, con
   return step_gemm_at<double>(A, lda, rows, n, Q, l, Z, accumulate, scratch, scratch_bytes, stream);
 }
 
+// Scratch of brsvd_orth: two padded panels, the Gram partial sums, five l x l fp64 factors, the inverse
+// factor in the panels' type, flags, the split-sum scratch of the apply product and the TSQR work area.
+struct OrthScratch {
+  uint64_t panel, sq8, sq4, gs, tb, total;
+  int chunks;
+};
+static OrthScratch orth_scratch_layout(int64_t rows, int Lp) {
+  OrthScratch o;
+  o.panel = align_up((uint64_t)rows * Lp * 4);
+  o.sq8 = align_up((uint64_t)Lp * Lp * 8);
+  o.sq4 = align_up((uint64_t)Lp * Lp * 4);
+  o.chunks = (int)orth_gram_slots(rows, Lp);
+  o.gs = align_up(gemm_an_scratch_bytes(rows, Lp, Lp));
+  o.tb = align_up(tsqr_work_bytes(rows, Lp));
+  o.total = 2 * o.panel + (uint64_t)o.chunks * o.sq8 + 5 * o.sq8 + o.sq4 + 256 + o.gs + o.tb;
+  return o;
+}
+
+uint64_t brsvd_orth_scratch_bytes(int64_t rows, int32_t l) {
+  if (rows < 1 || l < 1 || l > kMaxL) return 0;
+  return orth_scratch_layout(rows, padded_l(l)).total;
+}
+
 int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int32_t* fallback_taken,
-               void* stream) {
+               void* scratch, uint64_t scratch_bytes, void* stream) {
   if (!P || rows < 1 || l < 1 || l > kMaxL || rows < l) return BRSVD_ERR_ARG;
   if (method < BRSVD_ORTH_AUTO || method > BRSVD_ORTH_TSQR) return BRSVD_ERR_ARG;
+  if (!scratch || ((uintptr_t)scratch) % kAlign != 0) return BRSVD_ERR_ARG;
   if (fallback_taken) *fallback_taken = 0;
   const int Lp = padded_l(l);
   hipStream_t s = (hipStream_t)stream;
-  const uint64_t panel = align_up((uint64_t)rows * Lp * 4);
-  const uint64_t sq8 = align_up((uint64_t)Lp * Lp * 8), sq4 = align_up((uint64_t)Lp * Lp * 4);
-  const int chunks = (int)orth_gram_slots(rows, Lp);
-  const uint64_t gs = align_up(gemm_an_scratch_bytes(rows, Lp, Lp));
-  const uint64_t tb = align_up(tsqr_work_bytes(rows, Lp));
-  const uint64_t total = 2 * panel + (uint64_t)chunks * sq8 + 5 * sq8 + sq4 + 256 + gs + tb;
-  char* buf = nullptr;
-  if (hipMalloc((void**)&buf, total) != hipSuccess) return BRSVD_ERR_ALLOC;
+  const OrthScratch o = orth_scratch_layout(rows, Lp);
+  if (scratch_bytes < o.total) return BRSVD_ERR_BUDGET;
+  char* buf = (char*)scratch;
   int status = BRSVD_OK;
   do {
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { char* p = buf + off; off += bytes; return p; };
-    float* P0 = (float*)take(panel);
-    float* P1 = (float*)take(panel);
+    float* P0 = (float*)take(o.panel);
+    float* P1 = (float*)take(o.panel);
     OrthWork w;
-    w.gram_part = (double*)take((uint64_t)chunks * sq8);
-    w.gram_chunks_max = chunks;
-    w.G = (double*)take(sq8); w.R[0] = (double*)take(sq8); w.R[1] = (double*)take(sq8);
-    w.Xinv = (double*)take(sq8);
-    double* Rtot = (double*)take(sq8);
-    w.Rinv = (float*)take(sq4);
+    w.gram_part = (double*)take((uint64_t)o.chunks * o.sq8);
+    w.gram_chunks_max = o.chunks;
+    w.G = (double*)take(o.sq8); w.R[0] = (double*)take(o.sq8); w.R[1] = (double*)take(o.sq8);
+    w.Xinv = (double*)take(o.sq8);
+    double* Rtot = (double*)take(o.sq8);
+    w.Rinv = (float*)take(o.sq4);
     w.flags = (int*)take(256);
-    w.gemm_scratch = take(gs); w.gemm_scratch_bytes = gs;
-    w.tsqr_work = take(tb); w.tsqr_bytes = tb;
-    if (hipMemsetAsync(buf, 0, total, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
+    w.gemm_scratch = take(o.gs); w.gemm_scratch_bytes = o.gs;
+    w.tsqr_work = take(o.tb); w.tsqr_bytes = o.tb;
+    if (hipMemsetAsync(buf, 0, o.total, s) != hipSuccess) { status = BRSVD_ERR_HIP; break; }
     int m_now = method;
     for (int attempt = 0; attempt < 2; ++attempt) {
       float* res = nullptr;
@@ -1134,17 +1208,20 @@ int brsvd_orth(float* P, int64_t rows, int32_t l, int32_t method, double* R, int
     }
   } while (0);
   (void)hipStreamSynchronize(s);
-  (void)hipFree(buf);
   return status;
 }
 
-int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps, void* stream) {
+uint64_t brsvd_small_svd_scratch_bytes(int32_t l) {
+  if (l < 1 || l > kMaxL) return 0;
+  return small_svd_scratch_bytes(padded_l(l));
+}
+
+int brsvd_small_svd(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps, void* scratch,
+                    uint64_t scratch_bytes, void* stream) {
   if (!R || !S || !Ur || !Vr || l < 1 || l > kMaxL) return BRSVD_ERR_ARG;
-  char* buf = nullptr;
-  if (hipMalloc((void**)&buf, small_svd_scratch_bytes(padded_l(l))) != hipSuccess) return BRSVD_ERR_ALLOC;
-  const int status = small_svd_on_scratch(R, l, S, Ur, Vr, sweeps, buf, (hipStream_t)stream);
-  (void)hipFree(buf);
-  return status;
+  if (!scratch || ((uintptr_t)scratch) % kAlign != 0) return BRSVD_ERR_ARG;
+  if (scratch_bytes < small_svd_scratch_bytes(padded_l(l))) return BRSVD_ERR_BUDGET;
+  return small_svd_on_scratch(R, l, S, Ur, Vr, sweeps, (char*)scratch, (hipStream_t)stream);
 }
 
 int brsvd_small_svd_static(const double* R, int32_t l, double* S, double* Ur, double* Vr, int32_t* sweeps,

@@ -226,7 +226,9 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
 #undef STORE_X
 #undef LOAD_A
 
-  T* Yo = partial ? Part + (int64_t)slot * split_stride : Y;
+  // partial panels hold only the rows of the leftover tiles, i.e. rows from sh.whole tiles on
+  const int part_row0 = sh.whole * (WAVES * MT * 16);
+  T* Yo = partial ? Part + (int64_t)slot * split_stride - (int64_t)part_row0 * ldp : Y;
   const int64_t ldo = partial ? ldp : ldy;
   const int nc = partial ? NT * 16 : ncols;
 #pragma unroll
@@ -320,9 +322,10 @@ k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
     int64_t row = min((rbase) + s * 4 + g, rows_total - 1);                        \
     const T* p = A + row * lda;                                                \
     if (VEC) {                                                                     \
-      dst[s] = *(const vecT*)(p + col[0]);                                         \
+      dst[s] = __builtin_nontemporal_load((const vecT*)(p + col[0]));              \
     } else {                                                                       \
-      _Pragma("unroll") for (int j = 0; j < MT; ++j) dst[s][j] = p[col[j]];        \
+      _Pragma("unroll") for (int j = 0; j < MT; ++j)                               \
+        dst[s][j] = __builtin_nontemporal_load(p + col[j]);                        \
     }                                                                              \
   }
 
@@ -502,10 +505,7 @@ static int wg_slots(int lds_bytes, int wg_per_cu_regs) {
 // partial output panel (written and re-read) relative to the bytes of A the launch reads;
 // units = indivisible pieces of the contraction range; traffic_weight in (0, 1] discounts that
 // traffic when the launch is bound by MFMA rather than by HBM.
-static int pick_splits(int64_t tiles, int slots, int64_t units, double out_over_in, double traffic_weight,
-                       const char* env_name) {
-  const char* e = getenv(env_name);
-  if (e && atoi(e) > 0) return (int)std::min<int64_t>(atoi(e), units);
+static int pick_splits(int64_t tiles, int slots, int64_t units, double out_over_in, double traffic_weight) {
   int best = 1;
   double best_score = -1.0;
   const int smax = (int)std::min<int64_t>(units, 4096);   // long split sums are reduced in two levels
@@ -567,10 +567,7 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   const int wg_regs = esz == 8 ? 2 : (c.waves == 8 ? 1 : 2);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
-  const char* e = getenv("BRSVD_AN_SPLITS");
-  if (e && atoi(e) > 0) {
-    sh.whole = 0; sh.lt = T; sh.f = (int)std::min<int64_t>(atoi(e), C);
-  } else if (C >= 16 && T < 8 * S) {
+  if (C >= 16 && T < 8 * S) {
     sh.whole = T / S * S;
     sh.lt = T - sh.whole;
     if (sh.lt > 0) {
@@ -590,10 +587,15 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   return p;
 }
 
+// Rows that take part in a split sum: those of the leftover tiles.
+static int64_t an_partial_rows(const AnPlan& p, int64_t rows) {
+  return p.nsplit > 0 ? rows - (int64_t)p.sh.whole * p.tile_rows : 0;
+}
+
 uint64_t gemm_an_scratch_bytes(int64_t rows, int64_t K, int Lp, int esz) {
   NGroups ng = column_groups(Lp, esz);
   AnPlan p = an_plan(rows, K, ng.nt, esz);
-  return (uint64_t)p.nsplit * rows * Lp * esz;
+  return (uint64_t)p.nsplit * an_partial_rows(p, rows) * Lp * esz;
 }
 
 // The launch plans as plain numbers, for host-side checks of their invariants.
@@ -716,7 +718,8 @@ static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* 
   NGroups ng = column_groups(Lp, esz);
   AnPlan p = an_plan(rows, K, ng.nt, esz);
   const bool vec = vec_ok(A, lda, K);
-  if (scratch_bytes < (uint64_t)p.nsplit * rows * Lp * esz) return BRSVD_ERR_BUDGET;
+  const int64_t prows = an_partial_rows(p, rows);
+  if (scratch_bytes < (uint64_t)p.nsplit * prows * Lp * esz) return BRSVD_ERR_BUDGET;
   if (verbose())
     fprintf(stderr, "[brsvd] gemm_an f%d rows=%ld K=%ld Lp=%d: %d whole tiles + %d leftover tiles x %d splits + tail of %d "
             "chunks (%d per workgroup), %d chunks per tile, %d workgroups, vec=%d\n", esz * 8, (long)rows, (long)K, Lp,
@@ -729,15 +732,18 @@ static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* 
     if (nt <= 0) break;
     int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group (may be <= 0)
     BRSVD_TRY(launch_an<T>(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr,
-                           Lp, rows * Lp, p, stream));
+                           Lp, prows * Lp, p, stream));
   }
-  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
+  if (ev) {
+    BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
+    BRSVD_HIP_TRY(hipEventRecord(ev->sum_start, stream));
+  }
   if (p.nsplit > 0) {
     // rows of the leftover tiles: their partial panels, in split order
-    const int64_t r0 = (int64_t)p.sh.whole * p.tile_rows;
-    BRSVD_TRY(reduce_splits<T>(part + r0 * Lp, p.nsplit, rows * Lp, rows - r0, ncols, Lp, Y + r0 * ldy, ldy, false,
-                               stream));
+    const int64_t r0 = rows - prows;
+    BRSVD_TRY(reduce_splits<T>(part, p.nsplit, prows * Lp, prows, ncols, Lp, Y + r0 * ldy, ldy, false, stream));
   }
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->sum_stop, stream));
   return BRSVD_OK;
 }
 int gemm_an(const float* A, int64_t lda, int64_t rows, int64_t K, const float* X, int Lp, float* Y, int64_t ldy,
@@ -781,7 +787,7 @@ static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows, int e
   const int lds_bytes = 2 * kAtKC * at_ld(nt, esz) * esz;
   // one partial panel (n x Lp) per split, against block_rows x n of A read per block
   const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, p.waves == kAtWaves ? 1 : 8), max_sub,
-                               (double)(nt * 16) / (double)block_rows, traffic_weight(nt), "BRSVD_AT_SPLITS");
+                               (double)(nt * 16) / (double)block_rows, traffic_weight(nt));
   int64_t rps = ceil_div(block_rows, want);
   rps = ceil_div(rps, kAtKC) * kAtKC;
   p.rows_per_sub = (int)rps;
@@ -888,8 +894,13 @@ static int gemm_at_t(const T* A, int64_t lda, int64_t rows, int64_t n, const T* 
     if (nt <= 0) break;
     BRSVD_TRY(launch_at<T>(nt, vec, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
   }
-  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
-  return reduce_splits<T>(part, p.nsplit, n * Lp, n, Lp, Lp, Z, Lp, accumulate, stream);
+  if (ev) {
+    BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));
+    BRSVD_HIP_TRY(hipEventRecord(ev->sum_start, stream));
+  }
+  BRSVD_TRY(reduce_splits<T>(part, p.nsplit, n * Lp, n, Lp, Lp, Z, Lp, accumulate, stream));
+  if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->sum_stop, stream));
+  return BRSVD_OK;
 }
 int gemm_at(const float* A, int64_t lda, int64_t rows, int64_t n, const float* Q, int Lp, float* Z, bool accumulate,
             int64_t block_rows, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {

@@ -237,7 +237,7 @@ int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hi
 
 template <typename T>
 int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
-                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, double* resid2_out, hipStream_t stream) {
+                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, hipStream_t stream) {
   const int cw = rpca_col_tile(n);
   dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
@@ -249,9 +249,14 @@ int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, in
   else if (cw == 128) BRSVD_RPCA_UPDATE(128);
   else BRSVD_RPCA_UPDATE(64);
 #undef BRSVD_RPCA_UPDATE
-  // residual: the per-workgroup partial sums, in two levels when there are many (first-level sums go
-  // behind the partials)
-  const int nparts = (int)(grid.x * grid.y);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
+// *resid2_out = sum of the per-workgroup partial sums rpca_update left in `part`, in two levels when
+// there are many (first-level sums go behind the partials); fixed order.
+int rpca_residual_sum(double* part, int64_t m, int64_t n, double* resid2_out, hipStream_t stream) {
+  const int nparts = (int)(ceil_div(n, rpca_col_tile(n)) * ceil_div(m, kRpcaTR));
   if (nparts > 8192) {
     const int groups = 64, per = (int)ceil_div(nparts, groups);
     hipLaunchKernelGGL(k_sum_partials, dim3(groups), dim3(256), 0, stream, part, nparts, per, part + nparts);
@@ -288,7 +293,7 @@ int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream) {
   template int rpca_norms<T>(const T*, int64_t, double*, double*, hipStream_t);                                     \
   template int rpca_init<T>(const T*, int64_t, T, T, T*, T*, T*, hipStream_t);                                      \
   template int rpca_update<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, T, T*, T*, T*,   \
-                              T*, double*, double*, hipStream_t);                                                   \
+                              T*, double*, hipStream_t);                                                            \
   template int rpca_lowrank<T>(const T*, const T*, const T*, int64_t, int64_t, int, T, T*, hipStream_t);            \
   template int scale_rsqrt<T>(T*, int64_t, const double*, hipStream_t);
 BRSVD_RPCA_INSTANTIATE(float)

@@ -18,7 +18,8 @@ def test_more_than_one_gpu_is_refused():
 
 @pytest.mark.gpu
 def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
-    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--config", "C1", "--steps", "3", "--warmup", "1"],
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "C1", "--steps", "3", "--warmup", "1",
+                        "--sub", "C5"],
                        capture_output=True, text=True, timeout=110)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
@@ -36,3 +37,9 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
     assert d["value"] > 0 and d["ms_per_step"] > 0
     assert d["parity"]["sigma_topk_max_rel"] < 1e-4
+    assert d["config"]["workload"].startswith("C1") and rf["kernel"] in ("gemm_an", "gemm_at")
+    # sub-record of the robust-PCA configuration: per-iteration time and the HBM fraction of its three kernels
+    c5 = d["sub_records"]["C5"]
+    assert c5["ms_per_iteration"] > 0 and c5["final_residual"] < 1e-5 and c5["L_vs_planted"] < 1e-3
+    for kname in ("gemm_an", "gemm_at", "rpca_update"):
+        assert 0 < c5[kname]["hbm_frac"] < 1 and c5[kname]["avg_launch_us"] > 0

@@ -12,12 +12,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "brsvd.h")).read()
-    declared = set(re.findall(r"\b(brsvd_[a-z_0-9]+)\s*\(", hdr))
-    assert declared == set(B.EXPORTS)
     L = B.lib()
-    for name in declared:
-        assert getattr(L, name) is not None
+    for header, exports in (("brsvd.h", B.EXPORTS), ("brsvd_steps.h", B.STEP_EXPORTS)):
+        hdr = open(os.path.join(ROOT, "include", header)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)          # declarations only, not the comments
+        declared = set(re.findall(r"\b(brsvd_[a-z_0-9]+)\s*\(", hdr))
+        assert declared == set(exports), header
+        for name in declared:
+            assert getattr(L, name) is not None
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["brsvd.h", "brsvd_steps.h"]
 
 
 def test_product_path_does_not_import_oracle():
@@ -65,8 +68,19 @@ def test_null_arguments_rejected():
     assert L.brsvd_destroy(None) == B.BRSVD_OK
     assert L.brsvd_gemm_an(None, 0, 0, 0, None, 0, None, None, 0, None) == B.BRSVD_ERR_ARG
     assert L.brsvd_gemm_at(None, 0, 0, 0, None, 0, None, 0, None, 0, None) == B.BRSVD_ERR_ARG
-    assert L.brsvd_orth(None, 0, 0, 0, None, None, None) == B.BRSVD_ERR_ARG
-    assert L.brsvd_small_svd(None, 0, None, None, None, None, None) == B.BRSVD_ERR_ARG
+    assert L.brsvd_orth(None, 0, 0, 0, None, None, None, 0, None) == B.BRSVD_ERR_ARG
+    assert L.brsvd_small_svd(None, 0, None, None, None, None, None, 0, None) == B.BRSVD_ERR_ARG
+    assert L.brsvd_small_svd_static(None, 0, None, None, None, None, None) == B.BRSVD_ERR_ARG
+    # sizes beyond the scratch the no-allocation call carries, and scratch that is missing, misaligned or short:
+    # all rejected on the host, before any GPU call
+    one = C.c_void_p(256)
+    assert L.brsvd_small_svd_static(one, 513, one, one, one, None, None) == B.BRSVD_ERR_BUDGET
+    assert L.brsvd_small_svd(one, 8, one, one, one, None, None, 1 << 20, None) == B.BRSVD_ERR_ARG
+    assert L.brsvd_small_svd(one, 8, one, one, one, None, C.c_void_p(264), 1 << 20, None) == B.BRSVD_ERR_ARG
+    assert L.brsvd_small_svd(one, 8, one, one, one, None, one, 16, None) == B.BRSVD_ERR_BUDGET
+    assert L.brsvd_orth(one, 100, 8, 0, None, None, one, 16, None) == B.BRSVD_ERR_BUDGET
+    assert L.brsvd_small_svd_scratch_bytes(8) >= 2 * 16 * 16 * 8 and L.brsvd_small_svd_scratch_bytes(0) == 0
+    assert L.brsvd_orth_scratch_bytes(100, 8) >= 2 * 100 * 16 * 4 and L.brsvd_orth_scratch_bytes(100, 600) == 0
 
 
 def test_workspace_accounting_and_budget():
@@ -84,3 +98,14 @@ def test_workspace_accounting_and_budget():
     assert host >= 2 * (2000 + 1000) * 32 * 4 + 2 * 512 * 1000 * 4
     assert B.brsvd_gemm_scratch_bytes(512, 1000, 30) > 0
     assert B.brsvd_gemm_scratch_bytes(0, 1000, 30) == 0
+    # a caller's workspace bounds the working set exactly as the budget does; it must be 256-byte aligned
+    h = C.c_void_p()
+    p = _p()
+    p.workspace, p.workspace_bytes = 4096, small - 1
+    assert B.lib().brsvd_create(C.byref(p), C.byref(h)) == B.BRSVD_ERR_BUDGET and not h
+    p.workspace, p.workspace_bytes = 4100, small
+    assert B.lib().brsvd_create(C.byref(p), C.byref(h)) == B.BRSVD_ERR_ARG and not h
+    # the split-sum scratch of A X covers the leftover row tiles only: C3's in-core working set stays near its
+    # four panels (2 x 100000 x 272 + 2 x 50000 x 272 floats = 163 MB) instead of carrying 2 GB of scratch
+    c3 = B.brsvd_workspace_bytes(_p(m=100000, n=50000, k=256, p=16, q=1, row_block=8192))
+    assert c3 < 1.7e9        # of which about 1 GB are the partial panels of the split A^T Q launch

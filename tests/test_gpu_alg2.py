@@ -58,7 +58,9 @@ def test_alg2_matches_oracle(name, m, n, b, q):
         B.brsvd_destroy(h)
     f, _, _ = _figures(A.numpy(), Om.numpy(), cfg, b, U, S, Vt)
     note(f"[alg2 {name} {m}x{n} b={b} q={q}] " + " ".join(f"{k_}={v:.3e}" for k_, v in f.items()))
-    assert st["passes_over_A"] == 2 and st["orth_fallbacks"] == 0
+    # A lives in device memory: the kernels read every block 2q+1 times in the first sweep and once in the second;
+    # only a host-resident A is read (over the host link) twice whatever q is
+    assert st["passes_over_A"] == 2 * q + 2 and st["orth_fallbacks"] == 0
     assert st["gemm_at_launches"] == st["n_blocks"] * (q + 1) and st["gemm_an_launches"] == st["n_blocks"] * q + 1
     assert f["sigma_rel"] <= SIGMA_RTOL
     assert f["orthU"] <= ORTH_TOL and f["orthV"] <= ORTH_TOL
@@ -93,6 +95,7 @@ def test_alg2_on_device_omega_and_streaming():
     finally:
         B.brsvd_destroy(h)
     assert sth["passes_over_A"] == 2 and sth["copy_seconds"] > 0
+    assert sth["bytes_A_streamed"] == 2 * 4 * m * n and sth["bytes_A_read_by_kernels"] == (2 * cfg.q + 2) * 4 * m * n
     k = cfg.k
     assert float(torch.max(torch.abs(S - Sh)[:k] / S[:k])) <= 1e-5
     R1 = (U[:, :k].double() * S[:k].double()) @ Vt[:k].double()
@@ -175,6 +178,6 @@ def test_alg2_seeded_random_shapes():
             B.brsvd_destroy(h)
         f, _, _ = _figures(A.numpy(), Om, cfg, b, U, S, Vt)
         note(f"[alg2 rand{case}] " + " ".join(f"{k_}={v:.3e}" for k_, v in f.items()))
-        assert st["passes_over_A"] == 2 * (1 + st["orth_fallbacks"])
+        assert st["passes_over_A"] == (2 * q + 2) * (1 + st["orth_fallbacks"])
         assert f["sigma_rel"] <= SIGMA_RTOL and f["orthU"] <= ORTH_TOL and f["orthV"] <= ORTH_TOL
         assert abs(f["err_gpu"] - f["err_oracle"]) <= RECON_RTOL * f["err_oracle"]

@@ -104,7 +104,8 @@ def test_seeded_random_shapes_against_oracle():
         U, S, Vt, st = _run(cfg, A.pin_memory() if host else A.to(dev), Om.to(dev),
                             a_location=B.BRSVD_A_HOST_PINNED if host else B.BRSVD_A_DEVICE,
                             pass_mode=B.BRSVD_PASSES_FUSED if fused else B.BRSVD_PASSES_SEPARATE)
-        assert st["passes_over_A"] == (q + 1 if fused else 2 * q + 2) * (1 + st["orth_fallbacks"])
+        assert st["passes_over_A"] == (q + 1 if fused and host else 2 * q + 2) * (1 + st["orth_fallbacks"])
+        assert st["bytes_A_read_by_kernels"] == (2 * q + 2) * (1 + st["orth_fallbacks"]) * 4 * m * n
         check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b if b else m, U, S, Vt, f"rand{case}")
 
 
@@ -164,6 +165,39 @@ def test_caller_streams():
     assert outs[1][3]["copy_seconds"] > 0 and outs[1][3]["n_blocks"] == 4
 
 
+def test_caller_owned_workspace():
+    """A handle built on a device buffer of the caller (no allocation in brsvd_create) gives the same results bit
+    for bit as one that allocates its own; too small a buffer is refused; the buffer survives brsvd_destroy."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C1"]
+    A, Om = cfg.make_A(), cfg.make_Omega()
+    Ad, Od = A.to(dev), Om.to(dev)
+    U0, S0, Vt0, _ = _run(cfg, Ad, Od)
+    for host in (False, True):
+        loc = B.BRSVD_A_HOST_PINNED if host else B.BRSVD_A_DEVICE
+        need = B.brsvd_workspace_bytes(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, a_location=loc))
+        ws = torch.empty(need + 4096, dtype=torch.uint8, device=dev)
+        ws.fill_(0xAB)                                  # whatever the buffer held before must not matter
+        h = B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, a_location=loc,
+                                         workspace=ws))
+        try:
+            U1, S1, Vt1, st = B.brsvd_run(h, A.pin_memory() if host else Ad, Od)
+        finally:
+            B.brsvd_destroy(h)
+        torch.cuda.synchronize()
+        assert torch.all(ws[need:] == 0xAB)             # nothing written beyond the declared working set
+        if host:
+            rel = ((S1[:cfg.k] - S0[:cfg.k]).abs() / S0[:cfg.k]).max().item()
+            assert rel < 2e-5                           # block-wise launches sum in another order than one launch
+        else:
+            assert torch.equal(S0, S1) and torch.equal(U0, U1) and torch.equal(Vt0, Vt1)
+        check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, cfg.row_block, U1, S1, Vt1, f"workspace host={host}")
+        with pytest.raises(B.BrsvdError) as ei:
+            B.brsvd_create(B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block, a_location=loc,
+                                         workspace=ws[:need - 256]))
+        assert ei.value.status == B.BRSVD_ERR_BUDGET
+
+
 def test_timing_levels():
     """timing_level 1 times the pass kernels and the whole call only; the results do not depend on it."""
     dev = need_gpu()
@@ -199,7 +233,7 @@ def test_forced_tsqr_matches_oracle():
 @pytest.mark.parametrize("name,m,n,b,q", [("C2", 3000, 2500, 700, 2), ("C3", 4000, 3000, 1024, 1),
                                            ("C1", 2000, 1000, 512, 2), ("C1", 1500, 800, 333, 0)])
 def test_fused_passes_match_oracle(name, m, n, b, q):
-    """q+1 reads of A instead of 2q+2: both products of a power step from one resident block, projection
+    """Fused pass mode: both products of a power step without an orthonormalisation in between, projection
     recovered as C^T R^-1.  Same range(Y) in exact arithmetic, so the same oracle applies."""
     dev = need_gpu()
     cfg = synth.CONFIGS[name].scaled(m, n, b)
@@ -207,7 +241,9 @@ def test_fused_passes_match_oracle(name, m, n, b, q):
     A = cfg.make_A()
     Om = cfg.make_Omega()
     U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), pass_mode=B.BRSVD_PASSES_FUSED)
-    assert st["passes_over_A"] == q + 1 and st["bytes_A_streamed"] == (q + 1) * 4 * m * n
+    # A lives in device memory here: each of the two product kernels of a fused pass reads it, and that is what
+    # the statistics count; only a host-resident A is read q+1 times (over the host link)
+    assert st["passes_over_A"] == 2 * q + 2 and st["bytes_A_streamed"] == (2 * q + 2) * 4 * m * n
     assert st["gemm_an_launches"] == q + 1 and st["gemm_at_launches"] == q + 1
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, q, b, U, S, Vt, f"{cfg.name}-fused-q{q}")
 
@@ -221,6 +257,7 @@ def test_fused_passes_host_resident_and_tsqr():
     Ap.copy_(A)
     U, S, Vt, st = _run(cfg, Ap, Om.to(dev), a_location=B.BRSVD_A_HOST_PINNED, pass_mode=B.BRSVD_PASSES_FUSED)
     assert st["passes_over_A"] == 2 and st["n_blocks"] == 4 and st["gemm_an_launches"] == 8
+    assert st["bytes_A_streamed"] == 2 * 4 * cfg.m * cfg.n and st["bytes_A_read_by_kernels"] == 4 * 4 * cfg.m * cfg.n
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 900, U, S, Vt, "C4-host-fused")
     U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), orth=B.BRSVD_ORTH_TSQR, pass_mode=B.BRSVD_PASSES_FUSED)
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, cfg.q, 900, U, S, Vt, "C4-fused-tsqr")

@@ -56,10 +56,13 @@ def _check_an(rows, K, l, dtype):
             assert a1 == b0                       # contiguous, no overlap
         slots = [s for _, _, s in ranges]
         assert slots == [None] or slots == list(range(len(slots))) and len(slots) == nsplit
-    # scratch the library asks for holds nsplit partial panels (step-level figure includes two padded panels)
+    # scratch of the split sums: nsplit partial panels of the rows of the leftover tiles only (not of all rows)
+    leftover_rows = rows - whole * tile_rows if nsplit else 0
+    sizes = B.brsvd_gemm_plan(2, rows, K, l, 0, dtype)
+    an_bytes = sizes[0] + (sizes[1] << 31)
+    assert an_bytes == nsplit * leftover_rows * Lp * esz
     panel = -(-max(rows, K) * Lp * esz // 256) * 256
-    need = nsplit * rows * Lp * esz
-    assert B.brsvd_gemm_scratch_bytes(rows, K, l, f64=esz == 8) >= 2 * panel + need
+    assert B.brsvd_gemm_scratch_bytes(rows, K, l, f64=esz == 8) >= 2 * panel + an_bytes
 
 
 @pytest.mark.parametrize("rows,K,l", [(20000, 20000, 110), (100000, 50000, 272), (76800, 2000, 20), (2073600, 100, 20),
