@@ -158,8 +158,11 @@ def shrink(x: np.ndarray, eps: float) -> np.ndarray:
 
 
 def rpca_ialm(M, Omegas, k: int, p: int, q: int, iters: int, lam: float, mu0: float, rho: float,
-              row_block: int = 0):
+              row_block: int = 0, norm2: float | None = None):
     """Alg. 3 with a fixed number of iterations.
+
+    norm2: the value of ||M||_2 for the multiplier initialisation when the caller already has it (the dense
+    2-norm of a large M takes longer than the iterations); None = computed here by LAPACK.
 
     Readings: S_0 = 0 (the listing initialises "E_0"); mu_i everywhere mu appears; the
     multiplier starts at Y_0 = M / max(||M||_2, ||M||_max / lam) where ||M||_max is the largest
@@ -169,7 +172,7 @@ def rpca_ialm(M, Omegas, k: int, p: int, q: int, iters: int, lam: float, mu0: fl
     """
     M = np.asarray(M, dtype=np.float64)
     normM = np.linalg.norm(M)
-    J = max(np.linalg.norm(M, 2), np.max(np.abs(M)) / lam)
+    J = max(np.linalg.norm(M, 2) if norm2 is None else float(norm2), np.max(np.abs(M)) / lam)
     Y = M / J
     S = np.zeros_like(M)
     L = np.zeros_like(M)

@@ -12,9 +12,11 @@ EPS32 = float(np.finfo(np.float32).eps)
 SIGMA_RTOL = 1e-4        # top-k singular values, relative
 ORTH_TOL = 1e-5          # ||U^T U - I||_2
 RECON_RTOL = 1e-2        # reconstruction error within 1 % of the oracle's
-RECON_FLOOR = 1e-6       # ... once it is above the fp32 rounding level of the reconstruction itself (the paper
-                         # reports 1e-7 for single precision on exactly representable inputs): an fp64 oracle
-                         # error of 1e-15 cannot be matched to 1 % by fp32 factors
+RECON_FLOOR = 1e-6       # absolute allowance, applied ONLY where the oracle's own error is below RECON_FLOOR_BELOW:
+RECON_FLOOR_BELOW = 1e-5  # the fp32 rounding level of the reconstruction itself is about 1e-7 ... 1e-6 (the paper reports
+                         # 1e-7 for single precision on exactly representable inputs), so an fp64 oracle error of 1e-15
+                         # (l = min(m, n), or exactly rank-k inputs) cannot be matched to 1 % by fp32 factors.  Everywhere
+                         # else the stated 1 % applies as written.
 
 
 def need_gpu():
@@ -50,6 +52,57 @@ def check_against_oracle(A_host, Om_host, k, p, q, b, U, S, Vt, tag=""):
     assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0), "sigma must be descending and non-negative"
     assert out["sigma_rel"] <= SIGMA_RTOL, out
     assert out["orthU"] <= ORTH_TOL and out["orthV"] <= ORTH_TOL, out
-    assert abs(out["err_gpu"] - out["err_oracle"]) <= RECON_RTOL * out["err_oracle"] + RECON_FLOOR, out
-    assert abs(out["err_gpu_l"] - out["err_oracle_l"]) <= RECON_RTOL * out["err_oracle_l"] + RECON_FLOOR, out
+    assert recon_close(out["err_gpu"], out["err_oracle"]), out
+    assert recon_close(out["err_gpu_l"], out["err_oracle_l"]), out
+    return out
+
+
+def recon_close(err_gpu: float, err_oracle: float) -> bool:
+    """Reconstruction error within 1 % of the oracle's; the absolute floor only below the fp32 rounding level."""
+    floor = RECON_FLOOR if err_oracle < RECON_FLOOR_BELOW else 0.0
+    return abs(err_gpu - err_oracle) <= RECON_RTOL * err_oracle + floor
+
+
+def recon_error_fp64_gpu(A_rows, m, U, s, Vt, k=None, step=4096):
+    """||A - U_k diag(s_k) V_k^T||_F / ||A||_F evaluated in fp64 on the GPU, block by block -- the checker for the
+    configurations whose A takes the host minutes per evaluation; the same definition as the oracle's recon_error
+    (pinned against it in test_fp64_gpu_checker_equals_oracle_metric).  A_rows(r0, r1) returns rows of A as a CUDA
+    tensor; U, s, Vt: anything torch.as_tensor accepts (fp64 on the device after conversion)."""
+    dev = torch.device("cuda:0")
+    U = torch.as_tensor(U).to(dev, torch.float64)
+    s = torch.as_tensor(s).to(dev, torch.float64)
+    Vt = torch.as_tensor(Vt).to(dev, torch.float64)
+    if k is not None:
+        U, s, Vt = U[:, :k], s[:k], Vt[:k]
+    SV = s[:, None] * Vt
+    num = 0.0
+    den = 0.0
+    for r0 in range(0, m, step):
+        blk = A_rows(r0, min(m, r0 + step)).double()
+        den += float((blk * blk).sum())
+        blk = blk - U[r0:r0 + step] @ SV
+        num += float((blk * blk).sum())
+    return float(np.sqrt(num / den))
+
+
+def check_full_size_against_oracle(A_host, A_rows, Om_host, cfg, U, S, Vt, tag):
+    """Oracle parity at a configuration's stated size: the complete fp64 oracle walks A_host (numpy fp32, row blocks);
+    sigma, orthogonality and the reconstruction errors (rank k and rank l, both sides through recon_error_fp64_gpu)
+    are held to the same tolerances as the small cases."""
+    import time
+    t0 = time.time()
+    Uo, so, Vto = O.brsvd(A_host, Om_host, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block)
+    t_or = time.time() - t0
+    k = cfg.k
+    sg = S.double().cpu().numpy()
+    out = {"sigma_rel": float(np.max(np.abs(sg[:k] - so[:k]) / so[:k])),
+           "orthU": O.orth_defect(U.double().cpu().numpy()), "orthV": O.orth_defect(Vt.double().cpu().numpy().T)}
+    for name, kk in (("", k), ("_l", None)):
+        out["err_gpu" + name] = recon_error_fp64_gpu(A_rows, cfg.m, U, S, Vt, k=kk)
+        out["err_oracle" + name] = recon_error_fp64_gpu(A_rows, cfg.m, Uo, so, Vto, k=kk)
+    note(f"[parity {tag}] " + " ".join(f"{k_}={v:.6e}" for k_, v in out.items()) + f" oracle_seconds={t_or:.1f}")
+    assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0)
+    assert out["sigma_rel"] <= SIGMA_RTOL, out
+    assert out["orthU"] <= ORTH_TOL and out["orthV"] <= ORTH_TOL, out
+    assert recon_close(out["err_gpu"], out["err_oracle"]) and recon_close(out["err_gpu_l"], out["err_oracle_l"]), out
     return out

@@ -203,6 +203,32 @@ def test_hmt_bound_on_C1_shape():
     assert rel(s[:k], sA[:k]) < 1e-2
 
 
+def test_hmt_spectral_bound_on_C1_shape():
+    """Spectral-norm companion of the bound above (Halko, Martinsson and Tropp, the analysis the paper builds on,
+    q = 0): E||A - Q Q^T A||_2 <= (1 + sqrt(k/(p-1))) sigma_{k+1} + (e sqrt(k+p)/p) (sum_{j>k} sigma_j^2)^(1/2), and its
+    simplified form [1 + 4 sqrt(k+p)/(p-1) sqrt(min(m,n))] sigma_{k+1}.  A - U S V^T with all l triplets is
+    A - Q Q^T A.  Slack 2 per draw (one Omega is a sample, not the expectation); the mean of three draws with 1.2."""
+    cfg = synth.CONFIGS["C1"]
+    A = cfg.make_A().numpy().astype(np.float64)
+    sA = np.linalg.svd(A, compute_uv=False)
+    k, p = cfg.k, cfg.p
+    tail = np.sqrt(np.sum(sA[k:] ** 2))
+    sharp = (1.0 + np.sqrt(k / (p - 1.0))) * sA[k] + np.e * np.sqrt(k + p) / p * tail
+    simple = (1.0 + 4.0 * np.sqrt(k + p) / (p - 1.0) * np.sqrt(min(A.shape))) * sA[k]
+    errs = []
+    for t in range(3):
+        Om = cfg.make_Omega(it=t).numpy()
+        U, s, Vt = O.brsvd(A, Om, k, p, 0, row_block=cfg.row_block)
+        e2 = np.linalg.norm(A - (U * s) @ Vt, 2)
+        errs.append(e2)
+        assert e2 >= sA[k + p] * (1 - 1e-9)                  # no rank-l approximation beats sigma_{l+1}
+        assert e2 <= 2.0 * sharp and e2 <= 2.0 * simple
+    assert np.mean(errs) <= 1.2 * sharp
+    # with the configuration's power iterations the spectral error comes down towards sigma_{l+1}
+    U, s, Vt = O.brsvd(A, cfg.make_Omega().numpy(), k, p, cfg.q, row_block=cfg.row_block)
+    assert np.linalg.norm(A - (U * s) @ Vt, 2) <= errs[0] * (1 + 1e-9)
+
+
 # ---- shrinkage operator, closed form from the paper's definition ---------------------------
 
 def test_shrink_golden():

@@ -61,6 +61,19 @@ def test_rpca_matches_dense_svd_iteration():
     assert np.linalg.norm(S - Sd) / np.linalg.norm(Sd) < 1e-3
 
 
+def test_rpca_supplied_norm2_is_the_same_iteration():
+    """norm2 handed in (as the full-size GPU test does) instead of computed inside: identical results for the exact
+    value; a 1 % error of it only rescales the multiplier's start and leaves the decomposition within 1e-3."""
+    cfg, D, L0, S0, Om = _problem(300, 120)
+    lam = 1.0 / np.sqrt(300)
+    n2 = float(np.linalg.norm(D, 2))
+    a = O.rpca_ialm(D, Om, cfg.k, cfg.p, cfg.q, 12, lam, 1.25 / n2, 1.5, row_block=128)
+    b = O.rpca_ialm(D, Om, cfg.k, cfg.p, cfg.q, 12, lam, 1.25 / n2, 1.5, row_block=128, norm2=n2)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    c = O.rpca_ialm(D, Om, cfg.k, cfg.p, cfg.q, 12, lam, 1.25 / n2, 1.5, row_block=128, norm2=1.01 * n2)
+    assert np.linalg.norm(c[0] - a[0]) <= 1e-3 * np.linalg.norm(a[0])
+
+
 def test_rpca_tol_stopping_rule():
     """Alg. 3's break: the loop stops at the FIRST iteration whose residual is below tol; with a
     tolerance that is never met it is the fixed-iteration loop (different code, same iterates)."""
