@@ -765,12 +765,14 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
       BRSVD_TRY(run_sync<T>(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
       {
         Region r(h, CAT_ELEM, cs);
+        int nparts = 0;
         {
           Region u(h, CAT_UPD, cs);
           h->launches[CAT_UPD]++;
-          BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part, cs));
+          BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part, &nparts,
+                                   cs));
         }
-        BRSVD_TRY(rpca_residual_sum(part, m, n, scal + 2, cs));
+        BRSVD_TRY(rpca_residual_sum(part, nparts, scal + 2, cs));
       }
       BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + 2, scal + 2, sizeof(double), hipMemcpyDeviceToHost, cs));
       BRSVD_HIP_TRY(hipStreamSynchronize(cs));

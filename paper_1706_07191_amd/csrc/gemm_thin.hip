@@ -249,6 +249,195 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
 }
 
 // --------------------------------------------------------------------------------------------
+// gemm_an for the narrowest panels (one column tile, l <= 16, fp32): bound by the read of A
+// --------------------------------------------------------------------------------------------
+// The MFMA A operand wants lane (r, g) to hold row r, so a load straight into the operand registers
+// touches 16 rows with 64 bytes each per instruction, and a workgroup of k_gemm_an takes 256 bytes of a
+// row per chunk.  Wide panels hide that behind the MFMAs; with a single column tile the kernel is a read
+// of A, and how A is read decides: a plain read of a 76800 x 2000 matrix runs at 5.3 TB/s when every
+// workgroup takes 256 bytes per row at a time and at 6.5 TB/s with 1 KiB per row.  Here a workgroup
+// therefore owns 32 rows and walks them in chunks of 256 columns: a wave reads 1 KiB of one row per
+// instruction (nontemporal), the block goes through LDS (row stride 260 words: the 16 lanes of a pass of
+// a 128-bit LDS read hit 64 distinct banks), and the four waves split the chunk's columns, wave w
+// multiplying columns [64 w, 64 w + 64) of all 32 rows; their four partial tiles are added in wave order
+// at the end.  Both operands of a chunk are in registers before its MFMAs start, so block and panel
+// chunk are single buffered in LDS and the stores of the next chunk overlap the MFMAs; two register sets
+// hold the blocks of the next two chunks, i.e. a load has two chunk times to arrive.  Work partition
+// (AnShape) and partial-panel convention are those of k_gemm_an with tiles of 32 rows and chunks of 256
+// columns.  Measured (l = 16): 100000 x 50000 6.3 TB/s against 5.6 for k_gemm_an, 76800 x 2000 5.2 against
+// 4.8.  With two column tiles the MFMA work doubles and this arrangement, whose MFMA phases do not overlap
+// its LDS phases within a wave, loses to k_gemm_an (76800 x 2000, l = 20: 157 against 152 us), so it is
+// instantiated for one tile only.
+constexpr int kAnNarrowMaxNT = 1;
+constexpr int kAnNarrowRows = 32;
+constexpr int kAnNarrowKC = 256;
+constexpr int kAnNarrowLDA = kAnNarrowKC + 4;
+static constexpr int an_narrow_lds_bytes(int nt) {
+  return (kAnNarrowRows * kAnNarrowLDA + kAnNarrowKC * (nt * 16 + 4)) * 4;
+}
+
+template <int NT, bool VEC>
+__global__ void __launch_bounds__(256, 2)
+k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
+                 const float* __restrict__ X, int ldx,
+                 float* __restrict__ Y, int64_t ldy, int ncols,
+                 float* __restrict__ Part, int64_t ldp, int64_t split_stride, AnShape sh) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  float* lds = reinterpret_cast<float*>(lds_raw);
+  constexpr int MT = 2, KC = kAnNarrowKC, KS = 4, NTHREADS = 256, ROWS = kAnNarrowRows;
+  constexpr int LD = NT * 16 + 4;
+  constexpr int LDA = kAnNarrowLDA;
+  constexpr int ROWF4 = NT * 4;              // 16-byte units per panel row
+  constexpr int XPT = KC * ROWF4 / NTHREADS; // 4 or 8
+  constexpr int APT = ROWS * (KC / 4) / NTHREADS;  // 16-byte units of A per thread and chunk (8)
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  float* abuf = lds;
+  float* xbuf = lds + ROWS * LDA;
+
+  int first_tile, nseg = 1, c0, c1, slot = 0;
+  bool partial = true;
+  {
+    const int b = blockIdx.x, C = sh.C;
+    if (b < sh.whole) {
+      first_tile = b; c0 = 0; c1 = C; partial = false;
+    } else if (b < sh.whole + sh.lt * sh.f) {
+      const int idx = b - sh.whole, sp = idx % sh.f;
+      first_tile = sh.whole + idx / sh.f;
+      c0 = (int)((int64_t)sp * (C - sh.x) / sh.f);
+      c1 = (int)((int64_t)(sp + 1) * (C - sh.x) / sh.f);
+      slot = sp;
+    } else {
+      const int i = b - sh.whole - sh.lt * sh.f;
+      first_tile = sh.whole + i * sh.j;
+      nseg = min(sh.j, sh.whole + sh.lt - first_tile);
+      c0 = C - sh.x; c1 = C; slot = sh.f;
+    }
+  }
+  const int nchunks = c1 - c0;
+  const int kbeg = c0 * KC;
+  const int kend = min(K, c1 * KC);
+
+  for (int seg = 0; seg < nseg; ++seg) {
+  const int tile0 = (first_tile + seg) * ROWS;
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  floatx4 xr[XPT], ra[APT], rb[APT], a_cur[MT][KS];
+  float b_cur[4 * KS][NT];
+
+#define LOAD_X(kbase)                                                              \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    int k = (kbase) + kr;                                                          \
+    floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};                                       \
+    if (k < kend) v = *(const floatx4*)(X + (int64_t)k * ldx + c4 * 4);            \
+    xr[i] = v;                                                                     \
+  }
+#define STORE_X()                                                                  \
+  _Pragma("unroll") for (int i = 0; i < XPT; ++i) {                                \
+    int idx = tid + i * NTHREADS;                                                  \
+    int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
+    *(floatx4*)(xbuf + kr * LD + c4 * 4) = xr[i];                                  \
+  }
+  // a wave reads 1 KiB of one row per instruction; columns past the end of the row are re-read from its last
+  // ones: they meet zero rows of the staged panel
+#define LOAD_A(dst, kbase)                                                         \
+  _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                \
+    const int row = min(tile0 + wave + 4 * i, rows - 1);                           \
+    const float* ap = A + (int64_t)row * lda;                                      \
+    const int k = (kbase) + 4 * lane;                                              \
+    if (VEC) {                                                                     \
+      dst[i] = __builtin_nontemporal_load((const floatx4*)(ap + min(k, K - 4)));   \
+    } else {                                                                       \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
+        dst[i][j] = __builtin_nontemporal_load(ap + min(k + j, K - 1));            \
+    }                                                                              \
+  }
+#define STORE_A(src)                                                               \
+  _Pragma("unroll") for (int i = 0; i < APT; ++i)                                  \
+    *(floatx4*)(abuf + (wave + 4 * i) * LDA + 4 * lane) = src[i];
+  // operands of this wave's quarter of the chunk: columns [64 wave, 64 wave + 64)
+#define READ_OPERANDS()                                                            \
+  _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                \
+  _Pragma("unroll") for (int s = 0; s < KS; ++s)                                   \
+    a_cur[mt][s] = *(const floatx4*)(abuf + (mt * 16 + r) * LDA + 64 * wave + 16 * s + 4 * g); \
+  _Pragma("unroll") for (int t = 0; t < 4 * KS; ++t)                               \
+  _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                \
+    b_cur[t][nt] = xbuf[(64 * wave + (t >> 2) * 16 + 4 * g + (t & 3)) * LD + nt * 16 + r];
+  // One chunk: the panel rows of chunk c + 1 are requested (they come from L2 while the operands of chunk c
+  // leave LDS), the staged copies of chunk c + 1 (block of A from the register set `rs`, panel rows from xr)
+  // take the operands' place, the loads of chunk c + 3 are issued into the set just emptied, then the MFMAs
+  // of chunk c run from registers.
+#define CHUNK(c, rs)                                                               \
+  {                                                                                \
+    if ((c) + 1 < nchunks) LOAD_X(kbeg + ((c) + 1) * KC);                          \
+    READ_OPERANDS();                                                               \
+    __syncthreads();                                                               \
+    if ((c) + 1 < nchunks) { STORE_A(rs); STORE_X(); }                             \
+    if ((c) + 3 < nchunks) LOAD_A(rs, kbeg + ((c) + 3) * KC);                      \
+    _Pragma("unroll") for (int t = 0; t < 4 * KS; ++t)                             \
+    _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                              \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                              \
+      acc[mt][nt] = mfma16(a_cur[mt][t >> 2][t & 3], b_cur[t][nt], acc[mt][nt]);   \
+    __syncthreads();                                                               \
+  }
+
+  LOAD_X(kbeg);
+  LOAD_A(ra, kbeg);
+  if (nchunks > 1) LOAD_A(rb, kbeg + KC);
+  STORE_X();
+  STORE_A(ra);
+  if (nchunks > 2) LOAD_A(ra, kbeg + 2 * KC);
+  __syncthreads();
+#pragma nounroll
+  for (int c = 0; c < nchunks; c += 2) {
+    CHUNK(c, rb);
+    if (c + 1 < nchunks) CHUNK(c + 1, ra);
+  }
+#undef LOAD_X
+#undef STORE_X
+#undef LOAD_A
+#undef STORE_A
+#undef READ_OPERANDS
+#undef CHUNK
+
+  // the four partial tiles (one per wave, each over a quarter of every chunk) are added in wave order;
+  // the staging area of the block is free after the last barrier of the chunk loop
+  float* red = abuf;                                   // [wave][32 rows][NT * 16]
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        red[(wave * ROWS + mt * 16 + 4 * g + v) * (NT * 16) + nt * 16 + r] = acc[mt][nt][v];
+  __syncthreads();
+  {
+    const int part_row0 = sh.whole * ROWS;
+    float* Yo = partial ? Part + (int64_t)slot * split_stride - (int64_t)part_row0 * ldp : Y;
+    const int64_t ldo = partial ? ldp : ldy;
+    const int nc = partial ? NT * 16 : ncols;
+    for (int e = tid; e < ROWS * NT * 16; e += NTHREADS) {
+      const int lr = e / (NT * 16), col = e - lr * (NT * 16);
+      const int row = tile0 + lr;
+      float sum = red[e];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) sum += red[w * ROWS * NT * 16 + e];
+      if (row < rows && col < nc) Yo[(int64_t)row * ldo + col] = sum;
+    }
+  }
+  __syncthreads();                                     // before the next strip reuses the staging area
+  }   // next tail strip of this workgroup
+}
+
+// --------------------------------------------------------------------------------------------
 // gemm_at
 // --------------------------------------------------------------------------------------------
 // Workgroup: WAVES waves, wave w owns MT*16 consecutive columns of A (= rows of Z) and all NT*16
@@ -538,16 +727,19 @@ static NGroups column_groups(int Lp, int esz) {
 
 // ---- gemm_an ----
 struct AnCfg {
-  int mt, waves, kc;
+  int mt, waves, kc, tile_rows;
 };
 // Tile shapes picked from sweeps on MI355X (see the launch templates below, which must agree).
 constexpr int64_t kAnWideK = 1024;
 static AnCfg an_cfg(int nt, int esz, int64_t K) {
-  if (esz == 8) return {nt >= 5 ? 1 : 2, 4, 32};   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
+  auto cfg = [](int mt, int waves, int kc) { return AnCfg{mt, waves, kc, waves * mt * 16}; };
+  if (esz == 8) return cfg(nt >= 5 ? 1 : 2, 4, 32);   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
+  // one or two column tiles: bound by the read of A (k_gemm_an_narrow: tiles of 32 rows, chunks of 256 columns)
+  if (nt <= kAnNarrowMaxNT) return AnCfg{2, 4, kAnNarrowKC, kAnNarrowRows};
   // eight waves share one staged panel chunk (half the staging per MFMA); short contractions keep four-wave
   // workgroups, i.e. twice as many of them
-  if (nt <= 8) return {2, K >= kAnWideK ? 8 : 4, 64};
-  return {nt > 14 ? 1 : 2, 8, 32};
+  if (nt <= 8) return cfg(2, K >= kAnWideK ? 8 : 4, 64);
+  return cfg(nt > 14 ? 1 : 2, 8, 32);
 }
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
 static double traffic_weight(int nt) { return nt <= 2 ? 1.0 : (nt <= 4 ? 0.6 : 0.3); }
@@ -560,23 +752,26 @@ struct AnPlan {
 static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   AnCfg c = an_cfg(nt, esz, K);
   AnPlan p;
-  p.tile_rows = c.waves * c.mt * 16;
+  p.tile_rows = c.tile_rows;
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
-  const int lds_bytes = 2 * c.kc * (nt * 16 + 4) * esz;
+  const bool narrow = esz == 4 && nt <= kAnNarrowMaxNT;
+  const int lds_bytes = narrow ? an_narrow_lds_bytes(nt) : 2 * c.kc * (nt * 16 + 4) * esz;
   const int wg_regs = esz == 8 ? 2 : (c.waves == 8 ? 1 : 2);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
   AnShape sh = {C, T, 0, 1, 0, 0};
-  if (C >= 16 && T < 8 * S) {
+  // a split or a strip is worth its partial panel from about 512 columns on: 8 chunks of 64, 2 of 256
+  const int min_piece = c.kc >= 256 ? 2 : 8, min_strip = c.kc >= 256 ? 1 : 4;
+  if (C >= 2 * min_piece && T < 8 * S) {
     sh.whole = T / S * S;
     sh.lt = T - sh.whole;
     if (sh.lt > 0) {
-      sh.f = std::max(1, std::min(S / sh.lt, C / 8));
+      sh.f = std::max(1, std::min(S / sh.lt, C / min_piece));
       const int spare = S - sh.f * sh.lt;
       if (spare > 0) {
         sh.j = (int)ceil_div(sh.lt, spare);
         sh.x = C / (1 + sh.f * sh.j);          // j strips weigh one main split: (C - x) / f = j * x
-        if (sh.x < 4) { sh.x = 0; sh.j = 0; }
+        if (sh.x < min_strip) { sh.x = 0; sh.j = 0; }
       }
       if (sh.f == 1 && sh.x == 0) { sh.whole = T; sh.lt = 0; }
     }
@@ -625,12 +820,33 @@ static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, 
   return BRSVD_OK;
 }
 
+template <int NT, bool VEC>
+static int launch_an_narrow(const float* A, int64_t lda, int rows, int K, const float* X, int ldx, float* Y,
+                            int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                            hipStream_t stream) {
+  auto kern = k_gemm_an_narrow<NT, VEC>;
+  constexpr int lds_bytes = an_narrow_lds_bytes(NT);
+  static bool attr_set = false;
+  if (!attr_set) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(p.wgs), dim3(256), lds_bytes, stream, A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
+                     split_stride, p.sh);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
 template <typename T, int NT>
 static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
                         int64_t ldy, int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
                         hipStream_t stream) {
   if constexpr (sizeof(T) == 8 && NT > 8) {
     return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
+  } else if constexpr (sizeof(T) == 4 && NT <= kAnNarrowMaxNT) {
+    if (vec)
+      return launch_an_narrow<NT, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
+    return launch_an_narrow<NT, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
   } else {
     constexpr int MT = ((sizeof(T) == 8 && NT >= 5) || NT > 14) ? 1 : 2;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;

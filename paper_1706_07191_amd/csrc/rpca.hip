@@ -173,6 +173,79 @@ k_rpca_update(const T* __restrict__ M, const T* __restrict__ U, const T* __restr
   if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
 }
 
+// The same update with 16 bytes per lane (rows whose length is a multiple of 16 bytes): a wave handles 8 rows
+// of 64 * VW columns, a workgroup of four waves 32 rows, so every memory instruction of a wave moves 1 KiB of one
+// row; M and the multiplier are read and S, Y, X written with nontemporal accesses (each is touched once per
+// iteration), all 16 loads of a lane are issued before the first value is used.  Per element the arithmetic --
+// including the order of the rank-l sum -- is that of k_rpca_update.
+template <typename T>
+__global__ void __launch_bounds__(256)
+k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
+                  const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
+                  T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
+                  T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part) {
+  extern __shared__ __align__(16) unsigned char us_raw[];
+  T* us = reinterpret_cast<T*>(us_raw);
+  __shared__ double sh[4];
+  constexpr int VW = 16 / (int)sizeof(T);
+  typedef T vecT __attribute__((ext_vector_type(VW)));
+  constexpr int RPT = kRpcaTR / 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rsub = wave * RPT;
+  const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * VW;
+  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
+  for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
+    const int i = idx / l, t = idx - i * l;
+    const int64_t row = row0 + i;
+    const T sv = fmax(sig[t] - inv_mu, T(0));
+    us[idx] = row < m ? U[row * l + t] * sv : T(0);
+  }
+  __syncthreads();
+  double z2 = 0.0;
+  if (col < n) {
+    vecT mv[RPT], yv[RPT], acc[RPT];
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+      const int64_t row = min(row0 + rsub + i, m - 1);
+      mv[i] = __builtin_nontemporal_load((const vecT*)(M + row * n + col));
+      yv[i] = __builtin_nontemporal_load((const vecT*)(Y + row * n + col));
+      acc[i] = vecT{};
+    }
+    for (int t = 0; t < l; ++t) {
+      const vecT v = *(const vecT*)(Vt + (int64_t)t * n + col);
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        const T u = us[(rsub + i) * l + t];
+#pragma unroll
+        for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < RPT; ++i) {
+      const int64_t row = row0 + rsub + i;
+      if (row < m) {
+        vecT sv, yn, xn;
+#pragma unroll
+        for (int c = 0; c < VW; ++c) {
+          const T lv = acc[i][c];
+          sv[c] = shrinkf(fma(yv[i][c], inv_mu, mv[i][c] - lv), thr_s);
+          const T z = mv[i][c] - lv - sv[c];
+          yn[c] = fma(mu, z, yv[i][c]);
+          xn[c] = fma(yn[c], inv_mu_next, mv[i][c] - sv[c]);
+          z2 = fma((double)z, (double)z, z2);
+        }
+        const int64_t e = row * n + col;
+        __builtin_nontemporal_store(sv, (vecT*)(S + e));
+        __builtin_nontemporal_store(yn, (vecT*)(Y + e));
+        __builtin_nontemporal_store(xn, (vecT*)(X + e));
+        if (Lout) *(vecT*)(Lout + e) = acc[i];
+      }
+    }
+  }
+  const double s = block_sum(z2, sh);
+  if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
+}
+
 // L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
 // same tile arithmetic as the update kernel, so it is the L that iteration used.
 template <typename T, int CW>
@@ -194,6 +267,11 @@ k_rpca_lowrank(const T* __restrict__ U, const T* __restrict__ sig, const T* __re
   }
 }
 
+// Rows of M, S, Y, X start 16-byte aligned when n is a multiple of 16 bytes' worth of elements: the update then
+// moves 16 bytes per lane (column tile of 64 lanes).
+static bool rpca_vec_ok(int64_t n, int esz) { return n % (16 / esz) == 0 && n >= 16 / esz; }
+static int rpca_update_col_tile(int64_t n, int esz);
+
 // Column tile: the width among 256, 128, 64 that wastes the fewest lanes beyond column n (ties: wider).
 static int rpca_col_tile(int64_t n) {
   int best = 256;
@@ -214,8 +292,12 @@ __global__ void k_scale_rsqrt(T* __restrict__ P, int64_t count, const double* __
   P[i] = v > 0.0 ? (T)((double)P[i] / sqrt(v)) : T(0);
 }
 
+// Columns per workgroup of the update kernel for rows of n elements of esz bytes.
+static int rpca_update_col_tile(int64_t n, int esz) { return rpca_vec_ok(n, esz) ? 64 * (16 / esz) : rpca_col_tile(n); }
+
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
-  const int64_t blocks = ceil_div(n, rpca_col_tile(n)) * ceil_div(m, kRpcaTR);
+  // the narrowest column tile any element type can take (64) bounds the number of partial sums
+  const int64_t blocks = ceil_div(n, 64) * ceil_div(m, kRpcaTR);
   return (uint64_t)std::max<int64_t>(blocks + 64, 2 * kRpcaBlocks);   // + the first-level sums of the residual
 }
 
@@ -237,11 +319,20 @@ int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hi
 
 template <typename T>
 int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
-                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, hipStream_t stream) {
-  const int cw = rpca_col_tile(n);
+                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, int* nparts_out, hipStream_t stream) {
+  const int cw = rpca_update_col_tile(n, (int)sizeof(T));
   dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
   if (grid.y > 65535) return BRSVD_ERR_ARG;
+  *nparts_out = (int)(grid.x * grid.y);
   const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
+  if (rpca_vec_ok(n, (int)sizeof(T)) && ((uintptr_t)M | (uintptr_t)S | (uintptr_t)Y | (uintptr_t)X | (uintptr_t)Vt |
+                                         (uintptr_t)Lout) % 16 == 0) {
+    hipLaunchKernelGGL((k_rpca_update_vec<T>), grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,
+                       lambda / mu, T(1) / mu_next, Lout, S, Y, X, part);
+    BRSVD_HIP_TRY(hipGetLastError());
+    return BRSVD_OK;
+  }
+  if (cw != rpca_col_tile(n)) return BRSVD_ERR_ARG;      // misaligned arrays with an aligned row length: not supported
 #define BRSVD_RPCA_UPDATE(CW)                                                                                      \
   hipLaunchKernelGGL((k_rpca_update<T, CW>), grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,  \
                      lambda / mu, T(1) / mu_next, Lout, S, Y, X, part)
@@ -255,8 +346,7 @@ int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, in
 
 // *resid2_out = sum of the per-workgroup partial sums rpca_update left in `part`, in two levels when
 // there are many (first-level sums go behind the partials); fixed order.
-int rpca_residual_sum(double* part, int64_t m, int64_t n, double* resid2_out, hipStream_t stream) {
-  const int nparts = (int)(ceil_div(n, rpca_col_tile(n)) * ceil_div(m, kRpcaTR));
+int rpca_residual_sum(double* part, int nparts, double* resid2_out, hipStream_t stream) {
   if (nparts > 8192) {
     const int groups = 64, per = (int)ceil_div(nparts, groups);
     hipLaunchKernelGGL(k_sum_partials, dim3(groups), dim3(256), 0, stream, part, nparts, per, part + nparts);
@@ -293,7 +383,7 @@ int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream) {
   template int rpca_norms<T>(const T*, int64_t, double*, double*, hipStream_t);                                     \
   template int rpca_init<T>(const T*, int64_t, T, T, T*, T*, T*, hipStream_t);                                      \
   template int rpca_update<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, T, T*, T*, T*,   \
-                              T*, double*, hipStream_t);                                                            \
+                              T*, double*, int*, hipStream_t);                                                      \
   template int rpca_lowrank<T>(const T*, const T*, const T*, int64_t, int64_t, int, T, T*, hipStream_t);            \
   template int scale_rsqrt<T>(T*, int64_t, const double*, hipStream_t);
 BRSVD_RPCA_INSTANTIATE(float)
