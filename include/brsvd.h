@@ -45,7 +45,11 @@ enum { BRSVD_ORTH_AUTO = 0, BRSVD_ORTH_CHOLQR2 = 1, BRSVD_ORTH_TSQR = 2 };
  * host-resident A crosses the host link q+1 times -- the paper's "only twice" for q = 1 -- at the
  * price of one skipped re-orthonormalisation per pass (panels of condition up to (s_1/s_l)^2).  For a
  * device-resident A the two products are two kernels that each read A from device memory, so FUSED
- * saves orthonormalisations there, not reads. */
+ * saves orthonormalisations there, not reads.  The fused projection multiplies the rounding noise of
+ * C^T by (s_1/s_l)^2, so it only holds the accuracy of the separate mode while s_l/s_1 stays well above
+ * the square root of the machine epsilon; the library checks this on the triangular factor R of the
+ * sketch and, when min |R_ii| / max |R_ii| is below 3e-4 (fp32) or 3e-8 (fp64), repeats the run with
+ * separate passes (stats.fused_fallbacks). */
 enum { BRSVD_PASSES_SEPARATE = 0, BRSVD_PASSES_FUSED = 1 };
 /* Element type of A, Omega and the results.  F32: brsvd_run and everything else.  F64 (the precision
  * the paper measures in, Sec. 4 "Experiments"): the *_f64 entry points -- the same path on the fp64
@@ -108,6 +112,9 @@ typedef struct {
   int64_t rpca_update_launches;
   int64_t bytes_A_read_by_kernels; /* bytes of A, or of its staged blocks, read from device memory by the
                                       product kernels (equals bytes_A_streamed for a device-resident A) */
+  int32_t fused_fallbacks;     /* reruns with separate passes after a fused run whose sketch was too ill
+                                  conditioned for the fused projection (see BRSVD_PASSES_FUSED)          */
+  int32_t reserved_;
 } brsvd_stats;
 
 /* Device bytes a handle needs for these parameters (panels, partial-sum scratch, small factors, and

@@ -52,7 +52,8 @@ class brsvd_stats(C.Structure):
                 ("orth_fallbacks", C.c_int32), ("jacobi_sweeps", C.c_int32),
                 ("row_block", C.c_int32), ("n_blocks", C.c_int32),
                 ("split_sum_seconds", C.c_double), ("rpca_update_seconds", C.c_double),
-                ("rpca_update_launches", C.c_int64), ("bytes_A_read_by_kernels", C.c_int64)]
+                ("rpca_update_launches", C.c_int64), ("bytes_A_read_by_kernels", C.c_int64),
+                ("fused_fallbacks", C.c_int32), ("reserved_", C.c_int32)]
 
     def as_dict(self):
         return {f: getattr(self, f) for f, _ in self._fields_}

@@ -351,8 +351,13 @@ int pass_fused(brsvd_handle h, const T* A, int64_t lda, const T* X, T* Tm_, T* Z
 }
 
 // The whole factorisation, enqueued asynchronously on the handle's streams.
+// Index (in doubles) into the handle's device scalars of the diagonal ratio of the factor of the sketch that a
+// fused run leaves for the host (the slots before it belong to the robust-PCA loop and the power method).
+constexpr int kScalFusedRatio = 7;
+
 template <typename T>
-int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int method) {
+int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int method,
+                  bool fused) {
   const int l = h->l, Lp = h->Lp, q = h->prm.q;
   const int64_t m = h->prm.m, n = h->prm.n;
   hipStream_t cs = h->compute;
@@ -367,7 +372,7 @@ int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U,
   T* res;
 
   BRSVD_TRY(pad_panel(Omega, n, l, Xn, Lp, cs));
-  if (h->prm.pass_mode == BRSVD_PASSES_FUSED) {
+  if (fused) {
     // q passes Z = A^T (A X), X <- orth(Z), then one pass Y = A X, C^T = A^T Y; with Y = Q R the
     // projection is B^T = A^T Q = C^T R^-1, so R^-1 is applied to both panels.
     for (int it = 0; it < q; ++it) {
@@ -380,7 +385,12 @@ int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U,
     {
       Region r(h, CAT_ORTH, cs);
       ow.comp = Tn; ow.comp_tmp = Xn; ow.comp_rows = n;
-      BRSVD_TRY(orth_panel<T>(Ym, Tm, m, l, Lp, method, true, ow, nullptr, &res, cs));
+      // the factor R of Y = Q R is kept (in the buffer the thin QR of B^T overwrites below) for its diagonal:
+      // the host reads min |R_ii| / max |R_ii| at the end of the run and decides whether B^T = C^T R^-1 can be
+      // trusted in this precision
+      double* Ry = h->at<double>(h->lay.Rtot);
+      BRSVD_TRY(orth_panel<T>(Ym, Tm, m, l, Lp, method, true, ow, Ry, &res, cs));
+      BRSVD_TRY(diag_ratio(Ry, l, Lp, h->at<double>(h->lay.scal) + kScalFusedRatio, cs));
       if (res != Ym) std::swap(Ym, Tm);
       Xn = ow.comp; Tn = ow.comp_tmp;     // B^T and a free n x Lp buffer
       ow.comp = ow.comp_tmp = nullptr; ow.comp_rows = 0;
@@ -539,7 +549,7 @@ double sum_regions(brsvd_handle h, int cat) {
 
 // Reads of A are counted where they happen: a host-resident A is read over the host link by the block
 // copies (the kernels then read the staged blocks), a device-resident A by the pass kernels themselves.
-void fill_stats(brsvd_handle h, brsvd_stats* st, int fallbacks) {
+void fill_stats(brsvd_handle h, brsvd_stats* st, int fallbacks, int fused_fallbacks) {
   std::memset(st, 0, sizeof(*st));
   st->total_seconds = sum_regions(h, CAT_TOTAL);
   st->gemm_an_seconds = sum_regions(h, CAT_AN);
@@ -558,6 +568,7 @@ void fill_stats(brsvd_handle h, brsvd_stats* st, int fallbacks) {
   st->bytes_A_read_by_kernels = h->bytes_A_kernels;
   st->passes_over_A = st->bytes_A_streamed / ((int64_t)h->esz() * h->prm.m * h->prm.n);
   st->orth_fallbacks = fallbacks;
+  st->fused_fallbacks = fused_fallbacks;
   st->jacobi_sweeps = h->host_flags[1];
   st->row_block = (int32_t)h->b;
   st->n_blocks = h->nblocks;
@@ -581,18 +592,31 @@ void add_stats(brsvd_stats* acc, const brsvd_stats& s) {
   acc->bytes_A_streamed += s.bytes_A_streamed;
   acc->bytes_A_read_by_kernels += s.bytes_A_read_by_kernels;
   acc->orth_fallbacks += s.orth_fallbacks;
+  acc->fused_fallbacks += s.fused_fallbacks;
   acc->jacobi_sweeps = s.jacobi_sweeps;
   acc->row_block = s.row_block;
   acc->n_blocks = s.n_blocks;
 }
 
-// Runs one factorisation to completion (synchronises), handling the optimistic CholeskyQR route:
-// the breakdown flag is only inspected at the end, and AUTO then repeats the run with TSQR.
+// Below this ratio min |R_ii| / max |R_ii| of the sketch's triangular factor the fused pass mode is not
+// trusted: its projection B^T = C^T R^-1 amplifies the rounding noise of C^T (relative eps) by the square of
+// the ratio's inverse, so once ratio^2 nears eps the trailing triplets are noise -- and noise that comes out
+// LARGE, which would displace real singular values.  Measured in fp32 (k = 40, p = 10, q = 1, geometric
+// spectra): sigma_l / sigma_1 = 1.7e-4 still gives 4e-5 relative accuracy, 8.7e-5 gives errors of order one.
+inline double fused_ratio_floor(int dtype) { return dtype == BRSVD_DTYPE_F64 ? 3e-8 : 3e-4; }
+
+// Runs one factorisation to completion (synchronises), handling two optimistic choices whose failure is
+// only visible at the end: the CholeskyQR route (breakdown flag; AUTO then repeats the run with TSQR) and
+// the fused pass mode (diagonal ratio of the sketch's factor below fused_ratio_floor: the run is repeated
+// with separate passes, which re-orthonormalise after every product and have no such limit).
+// enqueue(method, fused) queues one attempt; fused_possible = the caller asked for the fused mode.
 template <typename Enqueue>
-int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
+int run_sync_with(brsvd_handle h, bool fused_possible, int* fallbacks, int* fused_fallbacks, Enqueue enqueue) {
   int method = h->prm.orth_method;
+  bool fused = fused_possible;
   int* dflags = h->at<int>(h->lay.flags);
-  for (int attempt = 0; attempt < 2; ++attempt) {
+  double* dratio = h->at<double>(h->lay.scal) + kScalFusedRatio;
+  for (int attempt = 0; attempt < 3; ++attempt) {
     BRSVD_HIP_TRY(hipMemsetAsync(dflags, 0, 64, h->compute));
     if (h->host_a) {
       // the staging buffers start out free
@@ -601,7 +625,7 @@ int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
     {
       // an error part-way leaves kernels and copies queued that still touch the caller's buffers and the
       // staging blocks: drain both streams before handing the status back
-      const int st = enqueue(method);
+      const int st = enqueue(method, fused);
       if (st != BRSVD_OK) {
         (void)hipStreamSynchronize(h->compute);
         if (h->host_a) (void)hipStreamSynchronize(h->copy);
@@ -611,22 +635,33 @@ int run_sync_with(brsvd_handle h, int* fallbacks, Enqueue enqueue) {
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags, dflags, sizeof(int), hipMemcpyDeviceToHost, h->compute));
     BRSVD_HIP_TRY(hipMemcpyAsync(h->host_flags + 1, dflags + 4, 2 * sizeof(int), hipMemcpyDeviceToHost,
                                  h->compute));
+    if (fused)
+      BRSVD_HIP_TRY(hipMemcpyAsync(h->host_scal + kScalFusedRatio, dratio, sizeof(double), hipMemcpyDeviceToHost,
+                                   h->compute));
     BRSVD_HIP_TRY(hipStreamSynchronize(h->compute));
     if (h->host_a) BRSVD_HIP_TRY(hipStreamSynchronize(h->copy));
-    if (h->host_flags[0] == 0) {
-      if (h->host_flags[2] == 0) return BRSVD_ERR_SVD_NOCONV;
-      return BRSVD_OK;
+    if (h->host_flags[0] != 0) {
+      if (method != BRSVD_ORTH_AUTO) return BRSVD_ERR_ORTH_BREAKDOWN;
+      method = BRSVD_ORTH_TSQR;
+      if (fallbacks) ++*fallbacks;
+      continue;
     }
-    if (method != BRSVD_ORTH_AUTO) return BRSVD_ERR_ORTH_BREAKDOWN;
-    method = BRSVD_ORTH_TSQR;
-    if (fallbacks) ++*fallbacks;
+    if (fused && !(h->host_scal[kScalFusedRatio] >= fused_ratio_floor(h->prm.dtype))) {
+      fused = false;
+      if (fused_fallbacks) ++*fused_fallbacks;
+      continue;
+    }
+    if (h->host_flags[2] == 0) return BRSVD_ERR_SVD_NOCONV;
+    return BRSVD_OK;
   }
   return BRSVD_ERR_ORTH_BREAKDOWN;
 }
 
 template <typename T>
-int run_sync(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int* fallbacks) {
-  return run_sync_with(h, fallbacks, [&](int method) { return enqueue_brsvd<T>(h, A, lda, Omega, U, S, Vt, method); });
+int run_sync(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U, T* S, T* Vt, int* fallbacks,
+             int* fused_fallbacks) {
+  return run_sync_with(h, h->prm.pass_mode == BRSVD_PASSES_FUSED, fallbacks, fused_fallbacks,
+                       [&](int method, bool fused) { return enqueue_brsvd<T>(h, A, lda, Omega, U, S, Vt, method, fused); });
 }
 
 template <typename T>
@@ -634,14 +669,14 @@ int run_with_stats(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U
   if (!A || !Omega || !U || !S || !Vt) return BRSVD_ERR_ARG;
   if (lda < h->prm.n) return BRSVD_ERR_ARG;
   reset_timing(h, stats != nullptr);
-  int fallbacks = 0, status;
+  int fallbacks = 0, fused_fallbacks = 0, status;
   {
     Region total(h, CAT_TOTAL, h->compute);
-    status = run_sync<T>(h, A, lda, Omega, U, S, Vt, &fallbacks);
+    status = run_sync<T>(h, A, lda, Omega, U, S, Vt, &fallbacks, &fused_fallbacks);
   }
   if (stats) {
     (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, fallbacks);
+    fill_stats(h, stats, fallbacks, fused_fallbacks);
   }
   return status;
 }
@@ -655,12 +690,13 @@ int run_alg2_with_stats(brsvd_handle h, const T* A, int64_t lda, uint64_t seed, 
   int fallbacks = 0, status;
   {
     Region total(h, CAT_TOTAL, h->compute);
-    status = run_sync_with(h, &fallbacks,
-                           [&](int method) { return enqueue_alg2<T>(h, A, lda, seed, Omega, U, S, Vt, method); });
+    status = run_sync_with(h, false, &fallbacks, nullptr, [&](int method, bool) {
+      return enqueue_alg2<T>(h, A, lda, seed, Omega, U, S, Vt, method);
+    });
   }
   if (stats) {
     (void)hipStreamSynchronize(h->compute);
-    fill_stats(h, stats, fallbacks);
+    fill_stats(h, stats, fallbacks, 0);
   }
   return status;
 }
@@ -717,11 +753,11 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   double* scal = h->at<double>(h->lay.scal);
   brsvd_stats acc;
   std::memset(&acc, 0, sizeof(acc));
-  auto flush_stats = [&](int fallbacks) {
+  auto flush_stats = [&](int fallbacks, int fused_fallbacks) {
     if (!stats) return;
     (void)hipStreamSynchronize(cs);
     brsvd_stats one;
-    fill_stats(h, &one, fallbacks);
+    fill_stats(h, &one, fallbacks, fused_fallbacks);
     add_stats(&acc, one);
     reset_timing(h, true);
   };
@@ -737,15 +773,15 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   const double max_abs = h->host_scal[0], normF = std::sqrt(h->host_scal[1]);
   if (!(normF > 0.0)) return BRSVD_ERR_ARG;
   if (!(norm2_M > 0.0)) {
-    int fb = 0;
+    int fb = 0, ffb = 0;
     {
       Region total(h, CAT_TOTAL, cs);
-      BRSVD_TRY(run_sync<T>(h, M, n, Omegas, Uw, Sw, Vtw, &fb));
+      BRSVD_TRY(run_sync<T>(h, M, n, Omegas, Uw, Sw, Vtw, &fb, &ffb));
     }
     T s0 = T(0);
     BRSVD_HIP_TRY(hipMemcpy(&s0, Sw, sizeof(T), hipMemcpyDeviceToHost));
     norm2_M = (double)s0;
-    flush_stats(fb);
+    flush_stats(fb, ffb);
     if (!(norm2_M > 0.0)) return BRSVD_ERR_ARG;
   }
   const double J = std::max(norm2_M, max_abs / (double)lambda);
@@ -757,12 +793,12 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   int it = 0;
   double mu_last = mu;
   while (it < max_iters) {
-    int fb = 0;
+    int fb = 0, ffb = 0;
     const double mu_next = mu * (double)rho;
     mu_last = mu;
     {
       Region total(h, CAT_TOTAL, cs);
-      BRSVD_TRY(run_sync<T>(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb));
+      BRSVD_TRY(run_sync<T>(h, X, n, Omegas + (int64_t)it * n * l, Uw, Sw, Vtw, &fb, &ffb));
       {
         Region r(h, CAT_ELEM, cs);
         int nparts = 0;
@@ -779,7 +815,7 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
     }
     const double res = std::sqrt(h->host_scal[2]) / normF;
     if (residuals) residuals[it] = res;
-    flush_stats(fb);
+    flush_stats(fb, ffb);
     ++it;
     if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
     mu = mu_next;
@@ -790,7 +826,7 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
     BRSVD_TRY(rpca_lowrank<T>(Uw, Sw, Vtw, m, n, l, (T)mu_last, L, cs));
   }
   BRSVD_HIP_TRY(hipStreamSynchronize(cs));
-  flush_stats(0);
+  flush_stats(0, 0);
   if (iters_done) *iters_done = it;
   if (stats) *stats = acc;
   return BRSVD_OK;

@@ -117,6 +117,8 @@ template <typename T>
 int tsqr_panel(T* P, T* tmp, int64_t rows, int l, int Lp, OrthWorkT<T>& w, double* Rtot, T** result,
                hipStream_t stream);
 int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream);
+// *out (device) = min |R_ii| / max |R_ii| of the l x l triangular factor R (stride Lp)
+int diag_ratio(const double* R, int l, int Lp, double* out, hipStream_t stream);
 
 // ---- small SVD (small_svd.hip) -------------------------------------------------------------
 struct SvdWork {

@@ -522,6 +522,30 @@ int apply_to_companion(OrthWorkT<T>& w, int Lp, hipStream_t stream) {
   return BRSVD_OK;
 }
 
+// *out = min_i |R_ii| / max_i |R_ii| of an l x l triangular factor (stride Lp): how far the last column
+// of the factored panel sits below the first.  One wave.
+__global__ void __launch_bounds__(64)
+k_diag_ratio(const double* __restrict__ R, int l, int Lp, double* __restrict__ out) {
+  double lo = INFINITY, hi = 0.0;
+  for (int i = threadIdx.x; i < l; i += 64) {
+    const double d = fabs(R[(int64_t)i * Lp + i]);
+    lo = fmin(lo, d);
+    hi = fmax(hi, d);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    lo = fmin(lo, __shfl_xor(lo, off, 64));
+    hi = fmax(hi, __shfl_xor(hi, off, 64));
+  }
+  if (threadIdx.x == 0) *out = hi > 0.0 ? lo / hi : 0.0;
+}
+
+int diag_ratio(const double* R, int l, int Lp, double* out, hipStream_t stream) {
+  hipLaunchKernelGGL(k_diag_ratio, dim3(1), dim3(64), 0, stream, R, l, Lp, out);
+  BRSVD_HIP_TRY(hipGetLastError());
+  return BRSVD_OK;
+}
+
 int triu_mul(const double* R2, const double* R1, int l, int Lp, double* Rtot, hipStream_t stream) {
   hipLaunchKernelGGL(k_triu_mul, dim3((unsigned)ceil_div((int64_t)l * l, 256)), dim3(256), 0, stream, R2, R1, l, Lp,
                      Rtot);

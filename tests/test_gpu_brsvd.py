@@ -104,6 +104,7 @@ def test_seeded_random_shapes_against_oracle():
         U, S, Vt, st = _run(cfg, A.pin_memory() if host else A.to(dev), Om.to(dev),
                             a_location=B.BRSVD_A_HOST_PINNED if host else B.BRSVD_A_DEVICE,
                             pass_mode=B.BRSVD_PASSES_FUSED if fused else B.BRSVD_PASSES_SEPARATE)
+        assert st["fused_fallbacks"] == 0                # sigma_l / sigma_1 >= 0.09: far above the fused mode's floor
         assert st["passes_over_A"] == (q + 1 if fused and host else 2 * q + 2) * (1 + st["orth_fallbacks"])
         assert st["bytes_A_read_by_kernels"] == (2 * q + 2) * (1 + st["orth_fallbacks"]) * 4 * m * n
         check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b if b else m, U, S, Vt, f"rand{case}")
@@ -246,6 +247,32 @@ def test_fused_passes_match_oracle(name, m, n, b, q):
     assert st["passes_over_A"] == 2 * q + 2 and st["bytes_A_streamed"] == (2 * q + 2) * 4 * m * n
     assert st["gemm_an_launches"] == q + 1 and st["gemm_at_launches"] == q + 1
     check_against_oracle(A.numpy(), Om.numpy(), cfg.k, cfg.p, q, b, U, S, Vt, f"{cfg.name}-fused-q{q}")
+
+
+@pytest.mark.parametrize("depth,expect_fallback", [(2e-2, False), (5e-3, False), (1e-3, True), (3e-4, True)])
+def test_fused_mode_accuracy_limit_and_guard(depth, expect_fallback):
+    """What the fused pass mode guarantees in fp32.  Its projection B^T = C^T R^-1 multiplies the rounding noise of
+    C^T by (sigma_1 / sigma_l)^2, so it keeps the 1e-4 tolerance only while sigma_l / sigma_1 stays above about the
+    square root of the machine epsilon; past that the unguarded scheme returns trailing values that are wrong by
+    factors (measured: 0.5 relative at sigma_k / sigma_1 = 1e-3, 7 at 3e-4), and too LARGE, so they would displace
+    real ones.  The library therefore checks the diagonal of the sketch's triangular factor and repeats such a run
+    with separate passes.  Pinned here on exactly known geometric spectra from sigma_1 = 1 down to sigma_k = depth
+    (tail 0.3 depth 0.9^j): above the floor the fused run stands and meets the tolerance; below it the fallback is
+    taken, is counted, and the result meets the tolerance again.  The separate mode meets it throughout."""
+    dev = need_gpu()
+    m, n, k, p, q, b = 3000, 2000, 40, 10, 1, 1024
+    s = torch.cat([torch.logspace(0, np.log10(depth), k, dtype=torch.float64),
+                   depth * 0.3 * 0.9 ** torch.arange(1, 61, dtype=torch.float64)])
+    A = synth.exact_spectrum_matrix(m, n, s, seed=4711, dtype=torch.float32)
+    Om = synth.gaussian(n, k + p, 4712)
+    cfg = synth.Config("depth", m, n, k, p, q, b, 100, lambda i: i, 0.0, 4711)
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev))
+    assert st["fused_fallbacks"] == 0 and st["passes_over_A"] == 2 * q + 2
+    check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"depth {depth:g} separate")
+    U, S, Vt, st = _run(cfg, A.to(dev), Om.to(dev), pass_mode=B.BRSVD_PASSES_FUSED)
+    assert st["fused_fallbacks"] == (1 if expect_fallback else 0)
+    assert st["passes_over_A"] == (2 * q + 2) * (2 if expect_fallback else 1)
+    check_against_oracle(A.numpy(), Om.numpy(), k, p, q, b, U, S, Vt, f"depth {depth:g} fused")
 
 
 def test_fused_passes_host_resident_and_tsqr():

@@ -70,9 +70,11 @@ def test_rpca_planted_recovery_matches_oracle():
 
 
 def test_rpca_on_a_fused_pass_handle():
-    """The ALM loop on a handle created with the fused pass mode (one re-orthonormalisation per power step): same decomposition.
-    The inner SVDs are less accurate there in fp32 (one re-orthonormalisation fewer per pass), which shows as
-    a residual floor of about 1e-5 instead of 1e-6 after 30 iterations."""
+    """The ALM loop on a handle created with the fused pass mode.  The iterates are a rank-5 matrix plus noise
+    sketched with l = 20 columns; once the sparse part has been peeled off, the sketch's trailing columns are noise,
+    far below the conditioning the fused projection tolerates in fp32, and the library's guard repeats those inner SVDs
+    with separate passes (about half of the 30 here): same decomposition and residual floor as on a separate-pass
+    handle, at the price of the discarded fused attempts."""
     dev = need_gpu()
     cfg, D, L0, S0, Om = _case(1200, 320)
     m, n = D.shape
@@ -83,10 +85,11 @@ def test_rpca_on_a_fused_pass_handle():
         L, S, res, st = B.brsvd_rpca_ialm(h, D.to(dev), Om.to(dev), 30, lam, 1.25 / n2, 1.5, norm2_M=n2)
     finally:
         B.brsvd_destroy(h)
-    assert st["passes_over_A"] == 30 * (2 * cfg.q + 2) and res[-1] < 5e-5
+    assert 5 <= st["fused_fallbacks"] <= 30
+    assert st["passes_over_A"] == (30 + st["fused_fallbacks"]) * (2 * cfg.q + 2) and res[-1] < 1e-5
     Lg = L.double().cpu().numpy()
     assert np.linalg.norm(Lg - L0.numpy()) <= 5e-3 * np.linalg.norm(L0.numpy())
-    assert float(torch.linalg.norm(D.to(dev) - L - S) / torch.linalg.norm(D.to(dev))) < 5e-5
+    assert float(torch.linalg.norm(D.to(dev) - L - S) / torch.linalg.norm(D.to(dev))) < 1e-5
 
 
 def test_rpca_argument_errors():
