@@ -734,11 +734,13 @@ constexpr int64_t kAnWideK = 1024;
 static AnCfg an_cfg(int nt, int esz, int64_t K) {
   auto cfg = [](int mt, int waves, int kc) { return AnCfg{mt, waves, kc, waves * mt * 16}; };
   if (esz == 8) return cfg(nt >= 5 ? 1 : 2, 4, 32);   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
-  // one or two column tiles: bound by the read of A (k_gemm_an_narrow: tiles of 32 rows, chunks of 256 columns)
+  // one column tile: bound by the read of A (k_gemm_an_narrow: tiles of 32 rows, chunks of 256 columns)
   if (nt <= kAnNarrowMaxNT) return AnCfg{2, 4, kAnNarrowKC, kAnNarrowRows};
   // eight waves share one staged panel chunk (half the staging per MFMA); short contractions keep four-wave
-  // workgroups, i.e. twice as many of them
-  if (nt <= 8) return cfg(2, K >= kAnWideK ? 8 : 4, 64);
+  // workgroups, i.e. twice as many of them, and so do panels of two column tiles, which are close to the read
+  // bound: more, smaller workgroups per CU overlap their load waits better (76800 x 2000, l = 20: 152 -> 135 us;
+  // 100000 x 50000, l = 32: 4.5 -> 5.3 TB/s)
+  if (nt <= 8) return cfg(2, (K >= kAnWideK && nt > 2) ? 8 : 4, 64);
   return cfg(nt > 14 ? 1 : 2, 8, 32);
 }
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
@@ -851,7 +853,7 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
     constexpr int MT = ((sizeof(T) == 8 && NT >= 5) || NT > 14) ? 1 : 2;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
     if constexpr (sizeof(T) == 4 && NT <= 8) {
-      if (K >= kAnWideK) {
+      if (K >= kAnWideK && NT > 2) {
         if (vec)
           return launch_an_inst<T, NT, MT, 8, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
                                                         split_stride, p, stream);
