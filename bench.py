@@ -16,6 +16,8 @@ under "sub_records" -- the other named configurations:
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1|C2|C3] [--sub C2,C5,C4|none]
                   [--only C4|C5] [--no-cpu-baseline] [--fused] [--dtype f32|f64] [--copy-calibration] [--peaks]
+  python bench.py --sweep gemm|shapes|rpca [--shape MxN ...] [--l L ...] [--family tall|square] [--gb G ...]
+                  [--iters I] [--tol T] [--dtype f32|f64]      (kernel, shape and robust-PCA sweeps; JSON lines)
 """
 from __future__ import annotations
 
@@ -283,6 +285,139 @@ def measured_peaks(B, torch):
     return out
 
 
+# ---- sweeps (not part of the default run; every line of output is one JSON object) ----------------------------
+def _time_ms(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def sweep_gemm(B, torch, args):
+    """The two pass kernels alone (HIP events inside the library around the product kernels of one BRSVD with q = 1):
+    microseconds, Tflop/s and GB/s of the algorithmic bytes 4mn + 4(m+n)l.  l <= 32 is the HBM-bound side of the ridge."""
+    dev = torch.device("cuda:0")
+    for shape in args.shape or ["20000x20000", "100000x50000"]:
+        m, n = (int(x) for x in shape.lower().split("x"))
+        A = torch.randn(m, n, device=dev)
+        for l in args.l or [8, 16, 32, 64, 110, 272]:
+            Om = torch.randn(n, l, device=dev)
+            h = B.brsvd_create(B.make_params(m, n, l, 0, 1, row_block=0, timing_level=1))
+            best = None
+            try:
+                for _ in range(4):
+                    _, _, _, st = B.brsvd_run(h, A, Om)
+                    t = st["gemm_an_seconds"] + st["gemm_at_seconds"]
+                    if best is None or t < best["gemm_an_seconds"] + best["gemm_at_seconds"]:
+                        best = st
+            finally:
+                B.brsvd_destroy(h)
+            rec = {"m": m, "n": n, "l": l}
+            for name in ("gemm_an", "gemm_at"):
+                f = kernel_figures(m, n, l, 4, best[f"{name}_seconds"], best[f"{name}_launches"], PEAK_MFMA_F32_TFLOPS)
+                rec[name] = {"us": round(f["avg_launch_ms"] * 1e3, 1), "GBps": round(f["hbm_GBps"]), "hbm_frac": round(f["hbm_frac"], 3),
+                             "TFLOPs": round(f["mfma_TFLOPs"], 1), "mfma_frac": round(f["mfma_frac"], 3)}
+            print(json.dumps(rec), flush=True)
+        del A
+
+
+def sweep_shapes(B, torch, args):
+    """Whole rank-k BRSVDs over growing inputs at the two aspect ratios of the paper's Fig. 2 (tall-skinny m:n:k =
+    1024:32:1, square 256:256:1; rank-k Gaussian-product inputs as in Sec. 4, p = 10, q = 1): seconds, Tflop/s with the
+    flop count of the paper's Table 1 terms written out, and the share of each phase."""
+    dev = torch.device("cuda:0")
+    fams = {"tall": (1024, 32), "square": (256, 256)}
+    f64 = args.dtype == "f64"
+    tdt, esz = (torch.float64, 8) if f64 else (torch.float32, 4)
+    p, q = 10, 1
+    for fam in args.family or ["tall", "square"]:
+        rm, rn = fams[fam]
+        for gb in args.gb or [0.25, 1, 4, 16]:
+            k = max(2, int(round((gb * 1e9 / esz / (rm * rn)) ** 0.5)))
+            m, n, l = rm * k, rn * k, k + p
+            if l > min(m, n, 512):
+                print(json.dumps({"family": fam, "gb": gb, "skipped": f"l = {l} exceeds min(m, n, 512)"}), flush=True)
+                continue
+            g = torch.Generator(device=dev)
+            g.manual_seed(1000 + k)
+            A = torch.empty(m, n, device=dev, dtype=tdt)
+            G2 = torch.randn(k, n, device=dev, generator=g, dtype=tdt)
+            step = max(1, (1 << 27) // max(n, 1))
+            for r0 in range(0, m, step):
+                r1 = min(m, r0 + step)
+                A[r0:r1] = torch.randn(r1 - r0, k, device=dev, generator=g, dtype=tdt) @ G2
+            Om = torch.randn(n, l, device=dev, dtype=tdt)
+            h = B.brsvd_create(B.make_params(m, n, k, p, q, row_block=0, dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32))
+            try:
+                B.brsvd_run(h, A, Om, want_stats=False)
+                best = None
+                for _ in range(3):
+                    U, S, Vt, st = B.brsvd_run(h, A, Om)
+                    if best is None or st["total_seconds"] < best["total_seconds"]:
+                        best = st
+            finally:
+                B.brsvd_destroy(h)
+            sweeps = (q + 1) + q + 4           # one CholeskyQR sweep per intermediate panel, two per output basis
+            flops = 2.0 * m * n * l * (2 * q + 2) + 2.0 * (m + n) * l * l * (sweeps + 1)
+            t = best["total_seconds"]
+            err = float(torch.linalg.norm(A[:4096] - (U[:4096] * S) @ Vt) / torch.linalg.norm(A[:4096]))
+            print(json.dumps({"family": fam, "dtype": args.dtype, "m": m, "n": n, "k": k, "p": p, "q": q,
+                              "bytes_A_GB": round(float(esz) * m * n / 1e9, 3), "seconds": round(t, 6),
+                              "tflops": round(flops / t / 1e12, 2), "A_GBps": round(best["bytes_A_streamed"] / t / 1e9, 1),
+                              "share": {key[:-8]: round(best[key] / t, 3) for key in
+                                        ("gemm_an_seconds", "gemm_at_seconds", "orth_seconds", "svd_seconds", "lift_seconds")},
+                              "orth_fallbacks": best["orth_fallbacks"], "rel_error_first_4096_rows": err}), flush=True)
+            del A, Om, U, S, Vt
+
+
+def sweep_rpca(B, torch, np, synth, args):
+    """Alg. 3 with its stopping rule (k = p = 10, q = 1) on synthetic rank-5 + 5 % sparse matrices of the shapes of the
+    paper's Table 2 (and configuration 5): iterations, seconds, per-iteration milliseconds of the phases and the GB/s of
+    the pass and update kernels."""
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS["C5"]
+    f64 = args.dtype == "f64"
+    esz = 8 if f64 else 4
+    for shape in args.shape or ["76800x2000", "2073600x100", "32256x2383"]:
+        m, n = (int(x) for x in shape.lower().split("x"))
+        D, L0, S0 = synth.make_rpca(cfg, device=dev, m=m, n=n)
+        Om = synth.rpca_omegas(cfg, n, args.iters, device=dev)
+        lam = 1.0 / np.sqrt(max(m, n))
+        x0 = synth.gaussian(n, 1, cfg.seed + 5, device=dev).reshape(-1).contiguous()
+        if f64:
+            D, L0, S0, Om, x0 = D.double(), L0.double(), S0.double(), Om.double(), x0.double()
+        h = B.brsvd_create(B.make_params(m, n, cfg.k, cfg.p, cfg.q, row_block=min(m, 65536),
+                                         dtype=B.BRSVD_DTYPE_F64 if f64 else B.BRSVD_DTYPE_F32))
+        try:
+            n2 = B.brsvd_norm2_power(h, D, x0, 20)
+            L, S = torch.empty_like(D), torch.empty_like(D)
+            work = torch.empty(2 * m * n, device=dev, dtype=D.dtype)
+            for _ in range(2):
+                L, S, res, done, st = B.brsvd_rpca_ialm_tol(h, D, Om, args.iters, args.tol, lam, 1.25 / n2, 1.5,
+                                                            norm2_M=n2, L=L, S=S, work=work)
+        finally:
+            B.brsvd_destroy(h)
+        by = float(esz) * m * n
+        an = st["gemm_an_seconds"] / max(st["gemm_an_launches"], 1)
+        at = st["gemm_at_seconds"] / max(st["gemm_at_launches"], 1)
+        up = st["rpca_update_seconds"] / max(st["rpca_update_launches"], 1)
+        print(json.dumps({"m": m, "n": n, "dtype": args.dtype, "iterations": done, "tol": args.tol, "residual": res[-1],
+                          "seconds": round(st["total_seconds"], 6),
+                          "ms_per_iteration": {key[:-8]: round(st[key] / done * 1e3, 4) for key in
+                                               ("total_seconds", "gemm_an_seconds", "gemm_at_seconds", "split_sum_seconds",
+                                                "orth_seconds", "svd_seconds", "lift_seconds", "elementwise_seconds")},
+                          "gemm_an_GBps": round(by / an / 1e9, 1), "gemm_at_GBps": round(by / at / 1e9, 1),
+                          "rpca_update_GBps": round(5.0 * by / up / 1e9, 1),
+                          "L_vs_planted": float(torch.linalg.norm(L - L0) / torch.linalg.norm(L0)),
+                          "S_vs_planted": float(torch.linalg.norm(S - S0) / torch.linalg.norm(S0))}), flush=True)
+        del D, L0, S0, Om, L, S, work
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -302,6 +437,15 @@ def main() -> int:
                     help="also run one plain 1 GiB device copy (outside the timed region) so that a rocprofv3 "
                          "--pmc run has a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE with")
     ap.add_argument("--peaks", action="store_true", help="add the measured streaming-read and fp32 MFMA peaks of this device")
+    ap.add_argument("--sweep", default=None, choices=["gemm", "shapes", "rpca"],
+                    help="instead of the benchmark line: the pass kernels over shapes and widths (gemm), whole BRSVDs at the "
+                         "aspect ratios of the paper's Fig. 2 (shapes), or Alg. 3 at the shapes of its Table 2 (rpca)")
+    ap.add_argument("--shape", nargs="+", default=None, help="sweeps gemm, rpca: MxN ...")
+    ap.add_argument("--l", nargs="+", type=int, default=None, help="sweep gemm: sketch widths")
+    ap.add_argument("--family", nargs="+", default=None, choices=["tall", "square"], help="sweep shapes")
+    ap.add_argument("--gb", nargs="+", type=float, default=None, help="sweep shapes: input sizes in GB")
+    ap.add_argument("--iters", type=int, default=30, help="sweep rpca: iteration cap")
+    ap.add_argument("--tol", type=float, default=1e-7, help="sweep rpca: stopping tolerance")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no multi-GPU sharding or collectives); "
@@ -318,6 +462,15 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     B.lib()   # fail loudly when the HIP library is missing
+
+    if args.sweep:
+        if args.sweep == "gemm":
+            sweep_gemm(B, torch, args)
+        elif args.sweep == "shapes":
+            sweep_shapes(B, torch, args)
+        else:
+            sweep_rpca(B, torch, np, synth, args)
+        return 0
 
     if args.only:
         if args.copy_calibration:

@@ -3,12 +3,13 @@
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  Written from the paper, not from the
 HIP code; shares nothing with it.
 
-What it computes (Alg. 1; Sec. 2 Eqs. (1)-(2); the two-sweep block structure of Alg. 2):
+What it computes (Alg. 1; the sketch y = A omega and the power-iteration formula of Sec. 2; the two-sweep
+block structure of Alg. 2):
     l = k + p
-    Y = A Omega                      sketch                     (Alg. 1 step 2 with q = 0, Eq. (1))
+    Y = A Omega                      sketch                     (Alg. 1 step 2 with q = 0; Sec. 2, y = A omega)
     Q = orth(Y)                                                 (Alg. 1 step 3)
-    q times:  Z = A^T Q, W = orth(Z);  Y = A W, Q = orth(Y)     (power iteration, Eq. (2); factors
-                                                                 applied right to left, Eq. (4))
+    q times:  Z = A^T Q, W = orth(Z);  Y = A W, Q = orth(Y)     (power iteration of Sec. 2; factors applied
+                                                                 right to left, Sec. 3 "Implementation details")
     B = Q^T A                                                   (Alg. 1 step 4 / Alg. 2 second sweep)
     B = Ut Sigma V^T  (dense SVD)                               (Alg. 1 step 5)
     U = Q Ut                                                    (Alg. 1 step 6)
@@ -153,7 +154,7 @@ def recon_error(A, U, s, Vt, k: int | None = None, row_block: int = 4096) -> flo
 # --------------------------------------------------------------------------------------
 
 def shrink(x: np.ndarray, eps: float) -> np.ndarray:
-    """Shrinkage (soft-threshold) operator of Sec. 4: x-eps if x>eps, x+eps if x<-eps, else 0."""
+    """Shrinkage (soft-threshold) operator of Sec. 5 (defined before Alg. 3): x-eps if x>eps, x+eps if x<-eps, else 0."""
     return np.where(x > eps, x - eps, np.where(x < -eps, x + eps, 0.0))
 
 
@@ -247,7 +248,7 @@ def brsvd_alg2(A, Omega, k: int, p: int, q: int, row_block: int = 0):
     column block of the transposed input, so Alg. 2 is applied to A^T (its "m" is our n):
         Y (n x l) = sum over blocks I of (A_I^T A_I)^q A_I^T Omega_I      (first sweep; Omega_I = the
                                                                            block's rows of Omega, m x l;
-                                                                           factors applied right to left, Eq. (4))
+                                                                           factors applied right to left, Sec. 3 "Implementation details")
         Q = orth(Y)                                                       (n x l)
         B(:, I) = Q^T A_I^T  for every block                              (second sweep; B is l x m)
         B = Ut Sigma Vp^T,  Up = Q Ut                                     (SVD of B and the lift)

@@ -450,7 +450,7 @@ int enqueue_brsvd(brsvd_handle h, const T* A, int64_t lda, const T* Omega, T* U,
 // The block-local scheme as Alg. 2 prints it, for a row-major A walked in row blocks (= column blocks of
 // A^T, so the roles of m and n are those of the transposed problem):
 //   first sweep    Y (n x l) += (A_I^T A_I)^q A_I^T Omega_I per resident block, factors applied right to
-//                  left (Eq. (4)); Omega_I is drawn on the device while the block is being copied
+//                  left (Sec. 3 "Implementation details"); Omega_I is drawn on the device while the block is being copied
 //   Q = orth(Y)
 //   second sweep   C_I = A_I Q  (C = B^T, m x l)
 //   C = W_C R, R = Ur diag(s) Vr^T   =>   A ~ (W_C Ur) diag(s) (Q Vr)^T

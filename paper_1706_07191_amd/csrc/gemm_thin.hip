@@ -2,7 +2,8 @@
 // v_mfma_f32_16x16x4_f32 and, from the same templates, fp64 on v_mfma_f64_16x16x4_f64.
 //
 //   gemm_an:  Y_I = A_I * X        sketch Y = A*Omega and the power step Y = A*W
-//                                  (Alg. 1 step 2, Alg. 2 line 4, Eq. (4) right-to-left order)
+//                                  (Alg. 1 step 2, Alg. 2 line 4; factors applied right to left,
+//                                  Sec. 3 "Implementation details")
 //   gemm_at:  Z  += A_I^T * Q_I    power half step Z = A^T*Q and the projection B^T = A^T*Q
 //                                  (Alg. 1 step 4, Alg. 2 line 9)
 //

@@ -1,4 +1,5 @@
-// Robust PCA by the inexact augmented Lagrange multiplier method (Alg. 3, Eq. (3)):
+// Robust PCA by the inexact augmented Lagrange multiplier method (Alg. 3 and the
+// low-rank + sparse decomposition problem of Sec. 5):
 // the elementwise kernels around the randomized SVD.  All of them are single sweeps over
 // m x n fp32 arrays (HBM-bound); the rank-l product L = U diag(shrunk sigma) V^T is
 // recomputed inside the fused update instead of being stored and re-read.
@@ -173,28 +174,30 @@ k_rpca_update(const T* __restrict__ M, const T* __restrict__ U, const T* __restr
   if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
 }
 
-// The same update with 16 bytes per lane (rows whose length is a multiple of 16 bytes): a wave handles 8 rows
-// of 64 * VW columns, a workgroup of four waves 32 rows, so every memory instruction of a wave moves 1 KiB of one
-// row; M and the multiplier are read and S, Y, X written with nontemporal accesses (each is touched once per
-// iteration), all 16 loads of a lane are issued before the first value is used.  Per element the arithmetic --
+// The same update with 16 bytes per lane (rows whose length is a multiple of 16 bytes): a wave handles
+// 32 / WAVES rows of 64 * VW columns, a workgroup 32 rows, so every memory instruction of a wave moves 1 KiB of
+// one row; M and the multiplier are read and S, Y, X written with nontemporal accesses (each is touched once per
+// iteration), all loads of a lane are issued before the first value is used.  Eight waves of four rows each
+// measured best on 76800 x 2000 (581 us; four waves of eight rows 606 us, sixteen of two 619 us; the scalar
+// kernel 664 us; a plain kernel with the same two reads and three writes per element reaches 5.4 TB/s = 570 us).  Per element the arithmetic --
 // including the order of the rank-l sum -- is that of k_rpca_update.
-template <typename T>
-__global__ void __launch_bounds__(256)
+template <typename T, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64)
 k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
                   const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
                   T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
                   T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part) {
   extern __shared__ __align__(16) unsigned char us_raw[];
   T* us = reinterpret_cast<T*>(us_raw);
-  __shared__ double sh[4];
+  __shared__ double sh[WAVES];
   constexpr int VW = 16 / (int)sizeof(T);
   typedef T vecT __attribute__((ext_vector_type(VW)));
-  constexpr int RPT = kRpcaTR / 4;
+  constexpr int RPT = kRpcaTR / WAVES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rsub = wave * RPT;
   const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * VW;
   const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
+  for (int idx = tid; idx < kRpcaTR * l; idx += WAVES * 64) {
     const int i = idx / l, t = idx - i * l;
     const int64_t row = row0 + i;
     const T sv = fmax(sig[t] - inv_mu, T(0));
@@ -327,7 +330,7 @@ int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, in
   const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
   if (rpca_vec_ok(n, (int)sizeof(T)) && ((uintptr_t)M | (uintptr_t)S | (uintptr_t)Y | (uintptr_t)X | (uintptr_t)Vt |
                                          (uintptr_t)Lout) % 16 == 0) {
-    hipLaunchKernelGGL((k_rpca_update_vec<T>), grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,
+    hipLaunchKernelGGL((k_rpca_update_vec<T, 8>), grid, dim3(512), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,
                        lambda / mu, T(1) / mu_next, Lout, S, Y, X, part);
     BRSVD_HIP_TRY(hipGetLastError());
     return BRSVD_OK;

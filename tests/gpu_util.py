@@ -1,6 +1,4 @@
 """Helpers for the GPU parity tests (not collected by pytest)."""
-import os
-
 import numpy as np
 import torch
 
@@ -25,12 +23,8 @@ def need_gpu():
 
 
 def note(line: str):
-    """Prints a measurement line and appends it to parity.log in the run's output folder, if there is one."""
+    """Prints a measurement line (shown with pytest -s, and in the report of a failing test)."""
     print(line, flush=True)
-    log_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(log_dir):
-        with open(os.path.join(log_dir, "parity.log"), "a") as f:
-            f.write(line + "\n")
 
 
 def check_against_oracle(A_host, Om_host, k, p, q, b, U, S, Vt, tag=""):

@@ -238,7 +238,7 @@ def test_rpca_video_shape_scaled_vs_oracle():
     finally:
         B.brsvd_destroy(h)
     note(f"[rpca-video] iterations gpu={done} oracle={ito} residual gpu={res[-1]:.3e} oracle={reso[-1]:.3e}")
-    # the paper itself reports the count moving by one between its CPU and GPU runs (Sec. 4, Table 2)
+    # the paper itself reports the count moving by one between its CPU and GPU runs (Sec. 5, Table 2)
     assert abs(done - ito) <= 1 and res[-1] < 1e-5
     Lg, Sg = L.double().cpu().numpy(), S.double().cpu().numpy()
     assert np.linalg.norm(Lg - Lo) <= 2e-3 * np.linalg.norm(Lo)

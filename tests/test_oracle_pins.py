@@ -168,7 +168,7 @@ def test_q0_projector_closed_form():
 
 
 def test_q1_projector_closed_form():
-    """With q = 1 the range is that of A A^T A Omega (Eq. (2)); catches a dropped or
+    """With q = 1 the range is that of A A^T A Omega (the power-iteration formula of Sec. 2); catches a dropped or
     transposed factor in the power iteration."""
     A = small_problem()
     Om = synth.gaussian(40, 10, 18).numpy()
