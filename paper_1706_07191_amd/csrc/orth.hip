@@ -469,7 +469,10 @@ static int gram(const T* P, int64_t rows, int Lp, OrthWorkT<T>& w, hipStream_t s
   BRSVD_HIP_TRY(hipGetLastError());
   const int64_t count = (int64_t)Lp * Lp;
   const unsigned bx = (unsigned)ceil_div(count, 256);
-  if (chunks > kGramFan) {
+  // small factors (up to 64 x 64) are summed in one level up to 256 chunks: a thread's serial sum is short against a
+  // second launch on the latency-bound chain Gram -> Cholesky -> apply
+  const int fan = count <= 4096 ? 4 * kGramFan : kGramFan;
+  if (chunks > fan) {
     const int groups = (int)ceil_div(chunks, kGramFan);
     double* lvl1 = w.gram_part + (int64_t)chunks * count;
     hipLaunchKernelGGL(k_reduce_groups, dim3(bx, groups), dim3(256), 0, stream, w.gram_part, chunks, kGramFan, count,
