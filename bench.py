@@ -38,8 +38,17 @@ C4_ROWS = 160000              # the GPU machine pins at most about 64 GB of host mem
 # HBM bytes per launch of the pass kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each
 # scaled by a plain 1 GiB copy in the same run.  Hardware counters cannot be read from inside the timed run, so
 # these are offline figures; `traffic_source` in the JSON names the summary they come from.
-OFFLINE_HBM_TRAFFIC = {}
-OFFLINE_HBM_TRAFFIC_SOURCE = {}
+OFFLINE_HBM_TRAFFIC = {
+    "C3:gemm_an": 2.23400e10, "C3:gemm_at": 2.41287e10,
+    "C2:gemm_an": 1.72469e9, "C2:gemm_at": 1.85194e9,
+    "C5:gemm_an": 6.804e8, "C5:gemm_at": 7.035e8, "C5:rpca_update": 3.2021e9,
+}
+OFFLINE_HBM_TRAFFIC_SOURCE = {
+    "C3:gemm_an": "profiles/gemm_thin_C3_hbm_traffic.md", "C3:gemm_at": "profiles/gemm_thin_C3_hbm_traffic.md",
+    "C2:gemm_an": "profiles/gemm_thin_C2_hbm_traffic.md", "C2:gemm_at": "profiles/gemm_thin_C2_hbm_traffic.md",
+    "C5:gemm_an": "profiles/gemm_thin_C5_hbm_traffic.md", "C5:gemm_at": "profiles/gemm_thin_C5_hbm_traffic.md",
+    "C5:rpca_update": "profiles/gemm_thin_C5_hbm_traffic.md",
+}
 
 
 def log(msg: str) -> None:
@@ -205,10 +214,14 @@ def sub_c5(B, torch, np, synth, reps=3):
                        f"{st['passes_over_A'] // iters} passes over the iterate per iteration",
            "ms_per_iteration": st["total_seconds"] / iters * 1e3, "ms_total": st["total_seconds"] * 1e3,
            "bound": "hbm",
-           "gemm_an": {"avg_launch_us": an["avg_launch_ms"] * 1e3, "hbm_GBps": an["hbm_GBps"], "hbm_frac": an["hbm_frac"]},
-           "gemm_at": {"avg_launch_us": at["avg_launch_ms"] * 1e3, "hbm_GBps": at["hbm_GBps"], "hbm_frac": at["hbm_frac"]},
+           "gemm_an": {"avg_launch_us": an["avg_launch_ms"] * 1e3, "hbm_GBps": an["hbm_GBps"], "hbm_frac": an["hbm_frac"],
+                       "algorithmic_bytes": an["algorithmic_bytes"], "traffic": OFFLINE_HBM_TRAFFIC.get("C5:gemm_an")},
+           "gemm_at": {"avg_launch_us": at["avg_launch_ms"] * 1e3, "hbm_GBps": at["hbm_GBps"], "hbm_frac": at["hbm_frac"],
+                       "algorithmic_bytes": at["algorithmic_bytes"], "traffic": OFFLINE_HBM_TRAFFIC.get("C5:gemm_at")},
            "rpca_update": {"avg_launch_us": upd * 1e6, "hbm_GBps": upd_bytes / upd / 1e9,
-                           "hbm_frac": upd_bytes / upd / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": upd_bytes},
+                           "hbm_frac": upd_bytes / upd / 1e9 / PEAK_HBM_GBS, "algorithmic_bytes": upd_bytes,
+                           "traffic": OFFLINE_HBM_TRAFFIC.get("C5:rpca_update")},
+           "traffic_source": OFFLINE_HBM_TRAFFIC_SOURCE.get("C5:gemm_an"),
            "ms_per_iteration_by_phase": {key[:-8]: st[key] / iters * 1e3 for key in
                                          ("gemm_an_seconds", "gemm_at_seconds", "split_sum_seconds", "rpca_update_seconds")},
            "final_residual": res[-1],

@@ -124,6 +124,17 @@ __device__ void publish(const double* W, int ld, int l, int Lp, double* Wg, doub
     }
 }
 
+// Sum over the 64 lanes of a wave, result in every lane: the four row sums are read as scalars and added.
+__device__ __forceinline__ double lane_value(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave64_sum(double v) {
+  v = row16_sum(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+
 // Sum over groups of 8 lanes (half a DPP row), result in every lane of the group.
 __device__ __forceinline__ double row8_sum(double v) {
   v += dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
@@ -283,13 +294,17 @@ __global__ void k_jacobi_init(const double* __restrict__ R, int ldr, int l, int 
 }
 
 // outer < 0: diagonal launch (workgroup p owns blocks 2p and 2p+1); otherwise round `outer` of the
-// round robin over nblk2 (even) blocks.  256 threads = 16 row pairs x 16 lanes; EPL = ceil(l / 16).
+// round robin over nblk2 (even) blocks.  1024 threads = 16 row pairs, one wave per pair (a wave of 64 lanes per
+// pair keeps four waves on every SIMD of the CU, which hides the LDS and cross-lane latencies that a quarter wave per
+// pair left exposed: 5.3 -> about 1 us per step at l = 272); EPL = ceil(l / 64).
+constexpr int kJBLanes = 64;
+constexpr int kJBThreads = kJB * kJBLanes;
 template <int EPL>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kJBThreads)
 k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, double tol, double settled,
                int* __restrict__ rotated) {
   extern __shared__ double sh[];               // 2 * kJB rows of l doubles: block I, then block J
-  const int tid = threadIdx.x, pi = tid >> 4, rl = tid & 15;
+  const int tid = threadIdx.x, pi = tid / kJBLanes, rl = tid % kJBLanes;
   int I, J;
   if (outer < 0) { I = 2 * blockIdx.x; J = I + 1; }
   else rr_pair(blockIdx.x, outer, nblk2, I, J);
@@ -297,7 +312,7 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
   if (rI >= l) return;                                  // uniform over the workgroup
   const int nI = min(kJB, l - rI), nJ = max(0, min(kJB, l - rJ));
   if (outer >= 0 && nJ == 0) return;                    // the padding block of an odd block count
-  for (int idx = tid; idx < 2 * kJB * l; idx += 256) {
+  for (int idx = tid; idx < 2 * kJB * l; idx += kJBThreads) {
     const int rr = idx / l, c = idx - rr * l;
     const bool live = rr < kJB ? rr < nI : rr - kJB < nJ;
     const int grow = rr < kJB ? rI + rr : rJ + rr - kJB;
@@ -317,13 +332,13 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       double x[EPL], y[EPL], al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        const int col = rl + 16 * e;
+        const int col = rl + kJBLanes * e;
         const bool in = valid && col < l;
         x[e] = in ? wa[col] : 0.0;
         y[e] = in ? wb[col] : 0.0;
         al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
       }
-      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      al = wave64_sum(al); be = wave64_sum(be); ga = wave64_sum(ga);
       double c, s;
       bool big;
       const bool rot = rotation(al, be, ga, tol2, settled2, c, s, big) && valid;
@@ -331,7 +346,7 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       if (rot) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-          const int col = rl + 16 * e;
+          const int col = rl + kJBLanes * e;
           if (col < l) { wa[col] = c * x[e] - s * y[e]; wb[col] = s * x[e] + c * y[e]; }
         }
       }
@@ -342,7 +357,7 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
     double* wa = sh + pi * l;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
-      const int col = rl + 16 * e;
+      const int col = rl + kJBLanes * e;
       x[e] = (pi < nI && col < l) ? wa[col] : 0.0;
     }
     for (int step = 0; step < kJB; ++step) {
@@ -352,11 +367,11 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       double y[EPL], al = 0.0, be = 0.0, ga = 0.0;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        const int col = rl + 16 * e;
+        const int col = rl + kJBLanes * e;
         y[e] = (valid && col < l) ? wb[col] : 0.0;
         al = fma(x[e], x[e], al); be = fma(y[e], y[e], be); ga = fma(x[e], y[e], ga);
       }
-      al = row16_sum(al); be = row16_sum(be); ga = row16_sum(ga);
+      al = wave64_sum(al); be = wave64_sum(be); ga = wave64_sum(ga);
       double c, s;
       bool big;
       const bool rot = rotation(al, be, ga, tol2, settled2, c, s, big) && valid;
@@ -364,7 +379,7 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
       if (rot) {
 #pragma unroll
         for (int e = 0; e < EPL; ++e) {
-          const int col = rl + 16 * e;
+          const int col = rl + kJBLanes * e;
           const double xn = c * x[e] - s * y[e];
           if (col < l) wb[col] = s * x[e] + c * y[e];
           x[e] = xn;
@@ -375,13 +390,13 @@ k_jacobi_block(double* __restrict__ W, int l, int Lp, int nblk2, int outer, doub
     if (pi < nI) {
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        const int col = rl + 16 * e;
+        const int col = rl + kJBLanes * e;
         if (col < l) wa[col] = x[e];
       }
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < 2 * kJB * l; idx += 256) {
+  for (int idx = tid; idx < 2 * kJB * l; idx += kJBThreads) {
     const int rr = idx / l, c = idx - rr * l;
     const bool live = rr < kJB ? rr < nI : rr - kJB < nJ;
     const int grow = rr < kJB ? rI + rr : rJ + rr - kJB;
@@ -466,16 +481,15 @@ static int launch_jacobi_block_inst(double* W, int l, int Lp, int nblk2, int out
                                       2 * kJB * kMaxL * (int)sizeof(double)));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(nblk2 / 2), dim3(256), (size_t)2 * kJB * l * sizeof(double), stream, W, l, Lp, nblk2,
+  hipLaunchKernelGGL(kern, dim3(nblk2 / 2), dim3(kJBThreads), (size_t)2 * kJB * l * sizeof(double), stream, W, l, Lp, nblk2,
                      outer, tol, settled, rotated);
   return BRSVD_OK;
 }
 static int launch_jacobi_block(double* W, int l, int Lp, int nblk2, int outer, double tol, double settled, int* rotated,
                                hipStream_t stream) {
-  if (l <= 192) return launch_jacobi_block_inst<12>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
-  if (l <= 272) return launch_jacobi_block_inst<17>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
-  if (l <= 384) return launch_jacobi_block_inst<24>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
-  return launch_jacobi_block_inst<32>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
+  if (l <= 192) return launch_jacobi_block_inst<3>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
+  if (l <= 320) return launch_jacobi_block_inst<5>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
+  return launch_jacobi_block_inst<8>(W, l, Lp, nblk2, outer, tol, settled, rotated, stream);
 }
 
 template <typename TO>
