@@ -39,6 +39,7 @@ __device__ __forceinline__ doublex4 mfma16(double a, double b, doublex4 c) {
 template <typename T> struct El;
 template <> struct El<float> {
   typedef floatx4 v4;
+  typedef floatx4 v4u __attribute__((aligned(4)));     // four consecutive elements at any element address
   typedef floatx4 u16;
   static constexpr int kPerU16 = 4;
   static constexpr int kBankMod = 64;      // row strides are padded against 64 banks of 4 bytes
@@ -46,11 +47,21 @@ template <> struct El<float> {
 };
 template <> struct El<double> {
   typedef doublex4 v4;
+  typedef doublex4 v4u __attribute__((aligned(8)));
   typedef double u16 __attribute__((ext_vector_type(2)));
   static constexpr int kPerU16 = 2;
   static constexpr int kBankMod = 32;
   __device__ static __forceinline__ int acc_row(int g, int v) { return g + 4 * v; }
 };
+
+// Streaming (nontemporal) load where STREAM, plain load otherwise.  Rows that do not start on 16-byte boundaries
+// share their first and last cache lines with the neighbouring accesses; a streaming load does not keep a line
+// for the neighbour, so such rows are read with plain loads.
+template <bool STREAM, typename V>
+__device__ __forceinline__ V load_a(const V* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(p);
+  else return *p;
+}
 
 // Identity the compiler cannot see through: the result is a new value living in VGPRs.  Used to
 // hand the prefetched block of A over to the MFMA stream, so that (a) the wait for the prefetch
@@ -80,7 +91,7 @@ struct AnShape {
   int C, whole, lt, f, x, j;
 };
 
-template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
+template <typename T, int NT, int MT, int WAVES, int KC, bool RAGGED>
 __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
           const T* __restrict__ X, int ldx,
@@ -89,6 +100,7 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
   extern __shared__ __align__(16) unsigned char lds_raw[];
   T* lds = reinterpret_cast<T*>(lds_raw);
   typedef typename El<T>::v4 vec4;
+  typedef typename El<T>::v4u vec4u;
   typedef typename El<T>::u16 unit16;
   constexpr int EPU = El<T>::kPerU16;
   constexpr int NTHREADS = WAVES * 64;
@@ -125,6 +137,8 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
   const int nchunks = c1 - c0;
   const int kbeg = c0 * KC;
   const int kend = min(K, c1 * KC);
+  const int K4 = K & ~3;
+  const bool ragged = RAGGED && (K4 != K || K < 4);   // RAGGED = false: the launcher has checked K % 4 == 0, K >= 4
 
   for (int seg = 0; seg < nseg; ++seg) {
   const int row0 = (first_tile + seg) * (WAVES * MT * 16) + wave * (MT * 16);
@@ -160,16 +174,23 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
     if (idx < F4) *(unit16*)((buf) + kr * LD + c4 * EPU) = xr[i];                  \
   }
+  // A lane takes four consecutive k of its row with one load (rows may start at any element address).  Groups
+  // past the end of a row whose length is a multiple of four are clamped to the last group: they meet zero
+  // rows of the staged panel.  A row length that is not a multiple of four leaves a group that straddles the
+  // end of the row; the chunk that holds it (one per row) is loaded element by element instead.
 #define LOAD_A(dst, kbase)                                                         \
-  _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                \
-  _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                 \
-    int k = (kbase) + s * 16 + 4 * g;                                              \
-    if (VEC) {                                                                     \
-      k = min(k, K - 4);                                                           \
-      dst[mt][s] = *(const vec4*)(ap[mt] + k);                                  \
-    } else {                                                                       \
+  if (ragged && (kbase) + KC > K4) {                                               \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                              \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                               \
+      const int k = (kbase) + s * 16 + 4 * g;                                      \
       _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
         dst[mt][s][j] = ap[mt][min(k + j, K - 1)];                                 \
+    }                                                                              \
+  } else {                                                                         \
+    _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                              \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                               \
+      const int k = min((kbase) + s * 16 + 4 * g, K - 4);                          \
+      dst[mt][s] = *(const vec4u*)(ap[mt] + k);                                    \
     }                                                                              \
   }
 
@@ -270,6 +291,7 @@ k_gemm_an(const T* __restrict__ A, int64_t lda, int rows, int K,
 // its LDS phases within a wave, loses to k_gemm_an (76800 x 2000, l = 20: 157 against 152 us), so it is
 // instantiated for one tile only.
 constexpr int kAnNarrowMaxNT = 1;
+constexpr int kAnNarrowMinK = 512;   // shorter rows leave most of a 256-column chunk empty: k_gemm_an takes them
 constexpr int kAnNarrowRows = 32;
 constexpr int kAnNarrowKC = 256;
 constexpr int kAnNarrowLDA = kAnNarrowKC + 4;
@@ -277,7 +299,7 @@ static constexpr int an_narrow_lds_bytes(int nt) {
   return (kAnNarrowRows * kAnNarrowLDA + kAnNarrowKC * (nt * 16 + 4)) * 4;
 }
 
-template <int NT, bool VEC>
+template <int NT, bool RAGGED>
 __global__ void __launch_bounds__(256, 2)
 k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
                  const float* __restrict__ X, int ldx,
@@ -319,6 +341,9 @@ k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
   const int nchunks = c1 - c0;
   const int kbeg = c0 * KC;
   const int kend = min(K, c1 * KC);
+  const int K4 = K & ~3;
+  const bool ragged = RAGGED && (K4 != K || K < 4);
+  typedef floatx4 floatx4u __attribute__((aligned(4)));
 
   for (int seg = 0; seg < nseg; ++seg) {
   const int tile0 = (first_tile + seg) * ROWS;
@@ -347,18 +372,19 @@ k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
     int kr = idx / ROWF4, c4 = idx - kr * ROWF4;                                   \
     *(floatx4*)(xbuf + kr * LD + c4 * 4) = xr[i];                                  \
   }
-  // a wave reads 1 KiB of one row per instruction; columns past the end of the row are re-read from its last
-  // ones: they meet zero rows of the staged panel
+  // a wave reads 1 KiB of one row per instruction (rows may start at any element address); columns past the
+  // end of the row are re-read from its last ones: they meet zero rows of the staged panel.  The one chunk of
+  // a row whose length is not a multiple of four that holds the straddling group is loaded element by element.
 #define LOAD_A(dst, kbase)                                                         \
   _Pragma("unroll") for (int i = 0; i < APT; ++i) {                                \
     const int row = min(tile0 + wave + 4 * i, rows - 1);                           \
     const float* ap = A + (int64_t)row * lda;                                      \
     const int k = (kbase) + 4 * lane;                                              \
-    if (VEC) {                                                                     \
-      dst[i] = __builtin_nontemporal_load((const floatx4*)(ap + min(k, K - 4)));   \
-    } else {                                                                       \
+    if (ragged && (kbase) + KC > K4) {                                             \
       _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
-        dst[i][j] = __builtin_nontemporal_load(ap + min(k + j, K - 1));            \
+        dst[i][j] = ap[min(k + j, K - 1)];                                         \
+    } else {                                                                       \
+      dst[i] = load_a<!RAGGED>((const floatx4u*)(ap + min(k, K - 4)));             \
     }                                                                              \
   }
 #define STORE_A(src)                                                               \
@@ -445,7 +471,7 @@ k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
 // panel columns; blockIdx.x = column tile, blockIdx.y = (row block, sub-range) of the contraction.
 // A lane loads MT consecutive columns of one row; component j of that load is the A operand of
 // m-tile j, which therefore holds the interleaved columns {cw + MT*i + j : i = 0..15}.
-template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
+template <typename T, int NT, int MT, int WAVES, int KC, bool RAGGED>
 __global__ void __launch_bounds__(WAVES * 64)
 k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
           const T* __restrict__ Q, int ldq,
@@ -464,6 +490,7 @@ k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
   constexpr int F4 = KC * ROWF4;
   constexpr int XPT = (F4 + NTHREADS - 1) / NTHREADS;
   typedef T vecT __attribute__((ext_vector_type(MT)));
+  typedef vecT vecTu __attribute__((aligned(sizeof(T))));   // MT consecutive columns at any element address
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, g = lane >> 4;
@@ -475,13 +502,15 @@ k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
   rend = min(rend, rows_total);
   const int nchunks = rbeg < rend ? (int)((rend - rbeg + KC - 1) / KC) : 0;
 
+  // A lane takes its MT consecutive columns with one load; groups past column n are clamped to the last group
+  // (their rows of Z are not stored).  When n is not a multiple of MT one group straddles the end of the rows:
+  // the workgroup that owns it (the last column tile) loads element by element instead.
+  const int n_whole = n - n % MT;
+  const bool by_element = RAGGED && (n_whole != n || n < MT) && (int)(blockIdx.x + 1) * (WAVES * MT * 16) > n_whole;
   int col[MT];
-  if (VEC) {
-    col[0] = min(cw + MT * r, n - MT);
-  } else {
 #pragma unroll
-    for (int j = 0; j < MT; ++j) col[j] = min(cw + MT * r + j, n - 1);
-  }
+  for (int j = 0; j < MT; ++j) col[j] = min(cw + MT * r + j, n - 1);
+  if (!by_element) col[0] = min(cw + MT * r, n - MT);
 
   vec4 acc[MT][NT];
 #pragma unroll
@@ -511,11 +540,11 @@ k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
   _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                 \
     int64_t row = min((rbase) + s * 4 + g, rows_total - 1);                        \
     const T* p = A + row * lda;                                                \
-    if (VEC) {                                                                     \
-      dst[s] = __builtin_nontemporal_load((const vecT*)(p + col[0]));              \
-    } else {                                                                       \
+    if (by_element) {                                                              \
       _Pragma("unroll") for (int j = 0; j < MT; ++j)                               \
-        dst[s][j] = __builtin_nontemporal_load(p + col[j]);                        \
+        dst[s][j] = p[col[j]];                                                     \
+    } else {                                                                       \
+      dst[s] = load_a<!RAGGED>((const vecTu*)(p + col[0]));                        \
     }                                                                              \
   }
 
@@ -736,7 +765,7 @@ static AnCfg an_cfg(int nt, int esz, int64_t K) {
   auto cfg = [](int mt, int waves, int kc) { return AnCfg{mt, waves, kc, waves * mt * 16}; };
   if (esz == 8) return cfg(nt >= 5 ? 1 : 2, 4, 32);   // wide fp64 panels: one m-tile per wave keeps two waves per SIMD
   // one column tile: bound by the read of A (k_gemm_an_narrow: tiles of 32 rows, chunks of 256 columns)
-  if (nt <= kAnNarrowMaxNT) return AnCfg{2, 4, kAnNarrowKC, kAnNarrowRows};
+  if (nt <= kAnNarrowMaxNT && K >= kAnNarrowMinK) return AnCfg{2, 4, kAnNarrowKC, kAnNarrowRows};
   // eight waves share one staged panel chunk (half the staging per MFMA); short contractions keep four-wave
   // workgroups, i.e. twice as many of them, and so do panels of two column tiles, which are close to the read
   // bound: more, smaller workgroups per CU overlap their load waits better (76800 x 2000, l = 20: 152 -> 135 us;
@@ -758,7 +787,7 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   p.tile_rows = c.tile_rows;
   p.row_tiles = (int)ceil_div(rows, p.tile_rows);
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
-  const bool narrow = esz == 4 && nt <= kAnNarrowMaxNT;
+  const bool narrow = esz == 4 && nt <= kAnNarrowMaxNT && K >= kAnNarrowMinK;
   const int lds_bytes = narrow ? an_narrow_lds_bytes(nt) : 2 * c.kc * (nt * 16 + 4) * esz;
   const int wg_regs = esz == 8 ? 2 : (c.waves == 8 ? 1 : 2);   // workgroups per CU the registers allow
   const int S = wg_slots(lds_bytes, wg_regs);
@@ -805,11 +834,11 @@ void gemm_an_plan_describe(int64_t rows, int64_t K, int Lp, int esz, int32_t out
   for (int i = 0; i < 12; ++i) out[i] = v[i];
 }
 
-template <typename T, int NT, int MT, int WAVES, int KC, bool VEC>
-static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y, int64_t ldy,
+template <typename T, int NT, int MT, int WAVES, int KC, bool RAGGED>
+static int launch_an_inst_r(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y, int64_t ldy,
                           int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
                           hipStream_t stream) {
-  auto kern = k_gemm_an<T, NT, MT, WAVES, KC, VEC>;
+  auto kern = k_gemm_an<T, NT, MT, WAVES, KC, RAGGED>;
   constexpr int lds_bytes = 2 * KC * (NT * 16 + 4) * (int)sizeof(T);
   static bool attr_set = false;
   if (!attr_set) {
@@ -823,11 +852,31 @@ static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, 
   return BRSVD_OK;
 }
 
-template <int NT, bool VEC>
-static int launch_an_narrow(const float* A, int64_t lda, int rows, int K, const float* X, int ldx, float* Y,
+// Rows that start on 16-byte boundaries and hold a whole number of a lane's element groups take the kernels
+// compiled without the element-by-element path for the group that straddles a row's end (and, where A is
+// streamed, with nontemporal loads); any other layout takes the RAGGED instance.
+template <typename T>
+static bool rows_aligned(const T* A, int64_t lda, int64_t len, int group) {
+  constexpr int per16 = 16 / (int)sizeof(T);
+  return len % group == 0 && len >= group && lda % per16 == 0 && ((uintptr_t)A) % 16 == 0;
+}
+
+template <typename T, int NT, int MT, int WAVES, int KC>
+static int launch_an_inst(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y, int64_t ldy,
+                          int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                          hipStream_t stream) {
+  if (rows_aligned(A, lda, K, 4))
+    return launch_an_inst_r<T, NT, MT, WAVES, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
+                                                         p, stream);
+  return launch_an_inst_r<T, NT, MT, WAVES, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
+                                                      stream);
+}
+
+template <int NT, bool RAGGED>
+static int launch_an_narrow_r(const float* A, int64_t lda, int rows, int K, const float* X, int ldx, float* Y,
                             int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
                             hipStream_t stream) {
-  auto kern = k_gemm_an_narrow<NT, VEC>;
+  auto kern = k_gemm_an_narrow<NT, RAGGED>;
   constexpr int lds_bytes = an_narrow_lds_bytes(NT);
   static bool attr_set = false;
   if (!attr_set) {
@@ -840,34 +889,35 @@ static int launch_an_narrow(const float* A, int64_t lda, int rows, int K, const 
   return BRSVD_OK;
 }
 
+template <int NT>
+static int launch_an_narrow(const float* A, int64_t lda, int rows, int K, const float* X, int ldx, float* Y,
+                            int64_t ldy, int ncols, float* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
+                            hipStream_t stream) {
+  if (rows_aligned(A, lda, K, 4))
+    return launch_an_narrow_r<NT, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
+  return launch_an_narrow_r<NT, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
+}
+
 template <typename T, int NT>
-static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
+static int launch_an_nt(const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
                         int64_t ldy, int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
                         hipStream_t stream) {
   if constexpr (sizeof(T) == 8 && NT > 8) {
     return BRSVD_ERR_ARG;                     // never planned: column_groups keeps fp64 launches at 8 n-tiles
-  } else if constexpr (sizeof(T) == 4 && NT <= kAnNarrowMaxNT) {
-    if (vec)
-      return launch_an_narrow<NT, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
-    return launch_an_narrow<NT, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
   } else {
+    if constexpr (sizeof(T) == 4 && NT <= kAnNarrowMaxNT) {
+      if (K >= kAnNarrowMinK)
+        return launch_an_narrow<NT>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
+    }
     constexpr int MT = ((sizeof(T) == 8 && NT >= 5) || NT > 14) ? 1 : 2;
     constexpr int KC = (sizeof(T) == 8 || NT > 8) ? 32 : 64;
     if constexpr (sizeof(T) == 4 && NT <= 8) {
-      if (K >= kAnWideK && NT > 2) {
-        if (vec)
-          return launch_an_inst<T, NT, MT, 8, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
-                                                        split_stride, p, stream);
-        return launch_an_inst<T, NT, MT, 8, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp,
-                                                       split_stride, p, stream);
-      }
+      if (K >= kAnWideK && NT > 2)
+        return launch_an_inst<T, NT, MT, 8, KC>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p,
+                                                stream);
     }
     constexpr int W = NT > 8 ? 8 : 4;
-    if (vec)
-      return launch_an_inst<T, NT, MT, W, KC, true>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
-                                                    p, stream);
-    return launch_an_inst<T, NT, MT, W, KC, false>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride,
-                                                   p, stream);
+    return launch_an_inst<T, NT, MT, W, KC>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream);
   }
 }
 
@@ -883,10 +933,10 @@ static int launch_an_nt(bool vec, const T* A, int64_t lda, int rows, int K, cons
   }
 
 template <typename T>
-static int launch_an(int nt, bool vec, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
+static int launch_an(int nt, const T* A, int64_t lda, int rows, int K, const T* X, int ldx, T* Y,
                      int64_t ldy, int ncols, T* part, int64_t ldp, int64_t split_stride, const AnPlan& p,
                      hipStream_t stream) {
-#define CALL(N) launch_an_nt<T, N>(vec, A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream)
+#define CALL(N) launch_an_nt<T, N>(A, lda, rows, K, X, ldx, Y, ldy, ncols, part, ldp, split_stride, p, stream)
   BRSVD_NT_SWITCH(nt, CALL)
 #undef CALL
 }
@@ -921,13 +971,6 @@ static int reduce_splits(T* part, int nsplit, int64_t split_stride, int64_t rows
   return BRSVD_OK;
 }
 
-// Vector loads of four consecutive elements of A need rows aligned to four elements and a length
-// that is a multiple of four (the vector path clamps a lane's group to the last aligned one).
-template <typename T>
-static bool vec_ok(const T* A, int64_t lda, int64_t len) {
-  return (lda % 4 == 0) && (((uintptr_t)A) % (4 * sizeof(T)) == 0) && len >= 4 && (len % 4 == 0);
-}
-
 template <typename T>
 static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* X, int Lp, T* Y, int64_t ldy,
                      int ncols, void* scratch, uint64_t scratch_bytes, hipStream_t stream, const KernelEvents* ev) {
@@ -936,13 +979,12 @@ static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* 
   constexpr int esz = (int)sizeof(T);
   NGroups ng = column_groups(Lp, esz);
   AnPlan p = an_plan(rows, K, ng.nt, esz);
-  const bool vec = vec_ok(A, lda, K);
   const int64_t prows = an_partial_rows(p, rows);
   if (scratch_bytes < (uint64_t)p.nsplit * prows * Lp * esz) return BRSVD_ERR_BUDGET;
   if (verbose())
     fprintf(stderr, "[brsvd] gemm_an f%d rows=%ld K=%ld Lp=%d: %d whole tiles + %d leftover tiles x %d splits + tail of %d "
-            "chunks (%d per workgroup), %d chunks per tile, %d workgroups, vec=%d\n", esz * 8, (long)rows, (long)K, Lp,
-            p.sh.whole, p.sh.lt, p.sh.f, p.sh.x, p.sh.j, p.sh.C, p.wgs, (int)vec);
+            "chunks (%d per workgroup), %d chunks per tile, %d workgroups\n", esz * 8, (long)rows, (long)K, Lp,
+            p.sh.whole, p.sh.lt, p.sh.f, p.sh.x, p.sh.j, p.sh.C, p.wgs);
   T* part = (T*)scratch;
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
@@ -950,7 +992,7 @@ static int gemm_an_t(const T* A, int64_t lda, int64_t rows, int64_t K, const T* 
     int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
     if (nt <= 0) break;
     int nc = ncols - c0 < nt * 16 ? ncols - c0 : nt * 16;   // valid output columns in this group (may be <= 0)
-    BRSVD_TRY(launch_an<T>(nt, vec, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr,
+    BRSVD_TRY(launch_an<T>(nt, A, lda, (int)rows, (int)K, X + c0, Lp, Y + c0, ldy, nc, part ? part + c0 : nullptr,
                            Lp, prows * Lp, p, stream));
   }
   if (ev) {
@@ -1029,10 +1071,10 @@ void gemm_at_plan_describe(int64_t rows, int64_t n, int Lp, int64_t block_rows, 
   for (int i = 0; i < 12; ++i) out[i] = v[i];
 }
 
-template <typename T, int NT, int MT, int WAVES, bool VEC>
-static int launch_at_inst(const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp, int ldz,
+template <typename T, int NT, int MT, int WAVES, bool RAGGED>
+static int launch_at_inst_r(const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp, int ldz,
                           int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
-  auto kern = k_gemm_at<T, NT, MT, WAVES, kAtKC, VEC>;
+  auto kern = k_gemm_at<T, NT, MT, WAVES, kAtKC, RAGGED>;
   constexpr int BM = El<T>::kBankMod;
   constexpr int LD = NT * 16 + ((16 - (NT * 16) % BM) + BM) % BM;
   constexpr int lds_bytes = 2 * kAtKC * LD * (int)sizeof(T);
@@ -1049,42 +1091,41 @@ static int launch_at_inst(const T* A, int64_t lda, int64_t rows, int n, const T*
   return BRSVD_OK;
 }
 
+template <typename T, int NT, int MT, int WAVES>
+static int launch_at_inst(const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp, int ldz,
+                          int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
+  // short rows whose pitch is not a whole number of 128-byte lines share a line with the next row at both ends:
+  // they are read with the plain loads of the RAGGED instance (2073600 x 100: 281 -> 265 us per pass)
+  const int64_t pitch = lda * (int64_t)sizeof(T);
+  if (rows_aligned(A, lda, n, MT) && (pitch % 128 == 0 || pitch >= 2048))
+    return launch_at_inst_r<T, NT, MT, WAVES, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
+  return launch_at_inst_r<T, NT, MT, WAVES, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
+}
+
 template <typename T, int NT>
-static int launch_at_nt(bool vec, const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
+static int launch_at_nt(const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
                         int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
   if constexpr (sizeof(T) == 8) {
     if constexpr (NT > 8) {
       return BRSVD_ERR_ARG;
     } else {
-      if (vec)
-        return launch_at_inst<T, NT, 2, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                        stream);
-      return launch_at_inst<T, NT, 2, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                       stream);
+      return launch_at_inst<T, NT, 2, kAtWaves>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
     }
   } else {
     constexpr int MT = NT <= 8 ? 4 : 2;
     if constexpr (NT <= kAtNarrowMaxNT) {
-      if (p.waves == kAtNarrowWaves) {
-        if (vec)
-          return launch_at_inst<T, NT, MT, kAtNarrowWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
-                                                                 block_rows, p, stream);
-        return launch_at_inst<T, NT, MT, kAtNarrowWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride,
-                                                                block_rows, p, stream);
-      }
+      if (p.waves == kAtNarrowWaves)
+        return launch_at_inst<T, NT, MT, kAtNarrowWaves>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
+                                                         stream);
     }
-    if (vec)
-      return launch_at_inst<T, NT, MT, kAtWaves, true>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                       stream);
-    return launch_at_inst<T, NT, MT, kAtWaves, false>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p,
-                                                      stream);
+    return launch_at_inst<T, NT, MT, kAtWaves>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream);
   }
 }
 
 template <typename T>
-static int launch_at(int nt, bool vec, const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
+static int launch_at(int nt, const T* A, int64_t lda, int64_t rows, int n, const T* Q, int ldq, T* Zp,
                      int ldz, int64_t split_stride, int64_t block_rows, const AtPlan& p, hipStream_t stream) {
-#define CALL(N) launch_at_nt<T, N>(vec, A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream)
+#define CALL(N) launch_at_nt<T, N>(A, lda, rows, n, Q, ldq, Zp, ldz, split_stride, block_rows, p, stream)
   BRSVD_NT_SWITCH(nt, CALL)
 #undef CALL
 }
@@ -1101,17 +1142,16 @@ static int gemm_at_t(const T* A, int64_t lda, int64_t rows, int64_t n, const T* 
   AtPlan p = at_plan(rows, n, ng.nt, block_rows, esz);
   if (p.nsplit > 65535) return BRSVD_ERR_ARG;
   if (scratch_bytes < (uint64_t)p.nsplit * n * Lp * esz) return BRSVD_ERR_BUDGET;
-  const bool vec = vec_ok(A, lda, n);
   T* part = (T*)scratch;
   if (verbose())
-    fprintf(stderr, "[brsvd] gemm_at f%d rows=%ld n=%ld Lp=%d: %d col tiles (%d waves) x %d blocks x %d sub-ranges of %d rows, vec=%d\n",
-            esz * 8, (long)rows, (long)n, Lp, p.col_tiles, p.waves, p.nblocks, p.sub, p.rows_per_sub, (int)vec);
+    fprintf(stderr, "[brsvd] gemm_at f%d rows=%ld n=%ld Lp=%d: %d col tiles (%d waves) x %d blocks x %d sub-ranges of %d rows\n",
+            esz * 8, (long)rows, (long)n, Lp, p.col_tiles, p.waves, p.nblocks, p.sub, p.rows_per_sub);
   if (ev) BRSVD_HIP_TRY(hipEventRecord(ev->start, stream));
   for (int gi = 0; gi < ng.groups; ++gi) {
     int c0 = gi * ng.nt * 16;
     int nt = (Lp - c0) / 16 < ng.nt ? (Lp - c0) / 16 : ng.nt;
     if (nt <= 0) break;
-    BRSVD_TRY(launch_at<T>(nt, vec, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
+    BRSVD_TRY(launch_at<T>(nt, A, lda, rows, (int)n, Q + c0, Lp, part + c0, Lp, n * Lp, block_rows, p, stream));
   }
   if (ev) {
     BRSVD_HIP_TRY(hipEventRecord(ev->stop, stream));

@@ -126,127 +126,138 @@ __device__ __forceinline__ void lowrank_tile(const T* __restrict__ U, const T* _
 }
 
 // One ALM iteration after the SVD of X_i (the low-rank, sparse, multiplier and residual updates of
-// Alg. 3, and the matrix handed to the SVD of the next iteration).  Workgroup tile: 32 rows x 256
-// columns, one column per thread.
-//   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here)
+// Alg. 3, and the matrix handed to the SVD of the next iteration):
+//   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here, terms added in index order)
 //   S = shrink(M - L + Y/mu, lambda/mu)
 //   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
 //   X_next = M - S + Y / mu_next
-// L is stored only when Lout != nullptr.  CW = columns per workgroup (256, 128 or 64: narrow matrices
-// take a narrower tile so that lanes are not wasted beyond column n); the 256 threads are CW columns
-// x 256/CW row slices of kRpcaTR * CW / 256 rows each.
-template <typename T, int CW>
-__global__ void __launch_bounds__(256)
-k_rpca_update(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
-              const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
-              T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
-              T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part) {
-  extern __shared__ __align__(16) unsigned char us_raw[];
-  T* us = reinterpret_cast<T*>(us_raw);
-  __shared__ double sh[4];
-  constexpr int RPT = kRpcaTR * CW / 256;
-  const int tid = threadIdx.x;
-  const int rsub = (tid / CW) * RPT;
-  const int64_t col = (int64_t)blockIdx.x * CW + tid % CW;
-  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  T acc[RPT];
-  lowrank_tile<T, RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
-  double z2 = 0.0;
-  if (col < n) {
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-      const int64_t row = row0 + rsub + i;
-      if (row < m) {
-        const int64_t e = row * n + col;
-        const T mv = M[e], yv = Y[e], lv = acc[i];
-        const T sv = shrinkf(fma(yv, inv_mu, mv - lv), thr_s);
-        const T z = mv - lv - sv;
-        const T yn = fma(mu, z, yv);
-        S[e] = sv;
-        Y[e] = yn;
-        X[e] = fma(yn, inv_mu_next, mv - sv);
-        if (Lout) Lout[e] = lv;
-        z2 = fma((double)z, (double)z, z2);
-      }
-    }
-  }
-  const double s = block_sum(z2, sh);
-  if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
-}
-
-// The same update with 16 bytes per lane (rows whose length is a multiple of 16 bytes): a wave handles
-// 32 / WAVES rows of 64 * VW columns, a workgroup 32 rows, so every memory instruction of a wave moves 1 KiB of
-// one row; M and the multiplier are read and S, Y, X written with nontemporal accesses (each is touched once per
-// iteration), all loads of a lane are issued before the first value is used.  Eight waves of four rows each
-// measured best on 76800 x 2000 (581 us; four waves of eight rows 606 us, sixteen of two 619 us; the scalar
-// kernel 664 us; a plain kernel with the same two reads and three writes per element reaches 5.4 TB/s = 570 us).  Per element the arithmetic --
-// including the order of the rank-l sum -- is that of k_rpca_update.
-template <typename T, int WAVES>
+// L is stored only when Lout != nullptr.
+//
+// A lane moves 16 bytes (VW elements) of one row per access, at any element alignment (rows of odd length do
+// not start on 16-byte boundaries); the lane that straddles the end of a row moves its elements one by one.  M
+// and the multiplier are read and S, Y, X written with nontemporal accesses (each is touched once per
+// iteration), and all loads of a lane are issued before the first value is used.  The threads of a workgroup
+// form TR = threads / cvt row lanes of cvt vector columns each (cvt = 64, or the whole row when it has fewer
+// than 64 vectors); a thread owns one vector column in the RPT rows tr, tr + TR, tr + 2 TR, ... of the tile,
+// so the rows of V^T it multiplies are loaded once for all of them, and consecutive threads touch consecutive
+// addresses: with 64 vector columns every memory instruction of a wave moves 1 KiB of one row, and a matrix of
+// short rows (100 columns: 25 vectors, 20 row lanes) is walked as one contiguous stream instead of leaving
+// most lanes of a 64-lane column tile idle.  Eight waves of four rows each measured best on 76800 x 2000
+// (581 us; four waves of eight rows 606 us, sixteen of two 619 us; one element per lane 664 us; a plain
+// kernel with the same two reads and three writes per element reaches 5.4 TB/s = 570 us).
+template <typename T, int WAVES, int RPT, bool STREAM>
 __global__ void __launch_bounds__(WAVES * 64)
 k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
                   const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
                   T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
-                  T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part) {
+                  T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part, int cvt, int col_tiles) {
   extern __shared__ __align__(16) unsigned char us_raw[];
   T* us = reinterpret_cast<T*>(us_raw);
   __shared__ double sh[WAVES];
   constexpr int VW = 16 / (int)sizeof(T);
+  constexpr int NTHREADS = WAVES * 64;
   typedef T vecT __attribute__((ext_vector_type(VW)));
-  constexpr int RPT = kRpcaTR / WAVES;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int rsub = wave * RPT;
-  const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * VW;
-  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
-  for (int idx = tid; idx < kRpcaTR * l; idx += WAVES * 64) {
+  typedef vecT vecTu __attribute__((aligned(sizeof(T))));
+  const int tid = threadIdx.x;
+  const int TR = NTHREADS / cvt, tile_rows = TR * RPT;
+  const int ct = blockIdx.x % col_tiles, rt = blockIdx.x / col_tiles;
+  const int64_t row0 = (int64_t)rt * tile_rows;
+  for (int idx = tid; idx < tile_rows * l; idx += NTHREADS) {
     const int i = idx / l, t = idx - i * l;
     const int64_t row = row0 + i;
-    const T sv = fmax(sig[t] - inv_mu, T(0));
+    const T sv = fmax(sig[t] - inv_mu, T(0));      // shrinkage of a non-negative singular value
     us[idx] = row < m ? U[row * l + t] * sv : T(0);
   }
   __syncthreads();
+  const int tr = tid / cvt, cv = tid - tr * cvt;
+  const int64_t col = ((int64_t)ct * cvt + cv) * VW;
+  const int cnt = (int)min((int64_t)VW, n - col);        // elements of this lane's vector inside the row
   double z2 = 0.0;
-  if (col < n) {
+  if (tr < TR && cnt > 0) {
     vecT mv[RPT], yv[RPT], acc[RPT];
-#pragma unroll
-    for (int i = 0; i < RPT; ++i) {
-      const int64_t row = min(row0 + rsub + i, m - 1);
-      mv[i] = __builtin_nontemporal_load((const vecT*)(M + row * n + col));
-      yv[i] = __builtin_nontemporal_load((const vecT*)(Y + row * n + col));
-      acc[i] = vecT{};
-    }
-    for (int t = 0; t < l; ++t) {
-      const vecT v = *(const vecT*)(Vt + (int64_t)t * n + col);
+    if (cnt == VW) {
 #pragma unroll
       for (int i = 0; i < RPT; ++i) {
-        const T u = us[(rsub + i) * l + t];
+        const int64_t row = min(row0 + tr + (int64_t)TR * i, m - 1);
+        if constexpr (STREAM) {
+          mv[i] = __builtin_nontemporal_load((const vecTu*)(M + row * n + col));
+          yv[i] = __builtin_nontemporal_load((const vecTu*)(Y + row * n + col));
+        } else {
+          mv[i] = *(const vecTu*)(M + row * n + col);
+          yv[i] = *(const vecTu*)(Y + row * n + col);
+        }
+        acc[i] = vecT{};
+      }
+      for (int t = 0; t < l; ++t) {
+        const vecT v = *(const vecTu*)(Vt + (int64_t)t * n + col);
 #pragma unroll
-        for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
+        for (int i = 0; i < RPT; ++i) {
+          const T u = us[(tr + TR * i) * l + t];
+#pragma unroll
+          for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        const int64_t row = min(row0 + tr + (int64_t)TR * i, m - 1);
+        mv[i] = vecT{}; yv[i] = vecT{}; acc[i] = vecT{};
+#pragma unroll
+        for (int c = 0; c < VW; ++c)
+          if (c < cnt) { mv[i][c] = M[row * n + col + c]; yv[i][c] = Y[row * n + col + c]; }
+      }
+      for (int t = 0; t < l; ++t) {
+        vecT v = vecT{};
+#pragma unroll
+        for (int c = 0; c < VW; ++c)
+          if (c < cnt) v[c] = Vt[(int64_t)t * n + col + c];
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          const T u = us[(tr + TR * i) * l + t];
+#pragma unroll
+          for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
+        }
       }
     }
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
-      const int64_t row = row0 + rsub + i;
+      const int64_t row = row0 + tr + (int64_t)TR * i;
       if (row < m) {
         vecT sv, yn, xn;
 #pragma unroll
         for (int c = 0; c < VW; ++c) {
           const T lv = acc[i][c];
           sv[c] = shrinkf(fma(yv[i][c], inv_mu, mv[i][c] - lv), thr_s);
-          const T z = mv[i][c] - lv - sv[c];
+          const T z = mv[i][c] - lv - sv[c];            // zero in the components beyond the row's end
           yn[c] = fma(mu, z, yv[i][c]);
           xn[c] = fma(yn[c], inv_mu_next, mv[i][c] - sv[c]);
           z2 = fma((double)z, (double)z, z2);
         }
         const int64_t e = row * n + col;
-        __builtin_nontemporal_store(sv, (vecT*)(S + e));
-        __builtin_nontemporal_store(yn, (vecT*)(Y + e));
-        __builtin_nontemporal_store(xn, (vecT*)(X + e));
-        if (Lout) *(vecT*)(Lout + e) = acc[i];
+        if (cnt == VW) {
+          if constexpr (STREAM) {
+            __builtin_nontemporal_store(sv, (vecTu*)(S + e));
+            __builtin_nontemporal_store(yn, (vecTu*)(Y + e));
+            __builtin_nontemporal_store(xn, (vecTu*)(X + e));
+          } else {
+            *(vecTu*)(S + e) = sv;
+            *(vecTu*)(Y + e) = yn;
+            *(vecTu*)(X + e) = xn;
+          }
+          if (Lout) *(vecTu*)(Lout + e) = acc[i];
+        } else {
+#pragma unroll
+          for (int c = 0; c < VW; ++c)
+            if (c < cnt) {
+              S[e + c] = sv[c]; Y[e + c] = yn[c]; X[e + c] = xn[c];
+              if (Lout) Lout[e + c] = acc[i][c];
+            }
+        }
       }
     }
   }
   const double s = block_sum(z2, sh);
-  if (tid == 0) part[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = s;
+  if (tid == 0) part[blockIdx.x] = s;
 }
 
 // L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
@@ -270,11 +281,6 @@ k_rpca_lowrank(const T* __restrict__ U, const T* __restrict__ sig, const T* __re
   }
 }
 
-// Rows of M, S, Y, X start 16-byte aligned when n is a multiple of 16 bytes' worth of elements: the update then
-// moves 16 bytes per lane (column tile of 64 lanes).
-static bool rpca_vec_ok(int64_t n, int esz) { return n % (16 / esz) == 0 && n >= 16 / esz; }
-static int rpca_update_col_tile(int64_t n, int esz);
-
 // Column tile: the width among 256, 128, 64 that wastes the fewest lanes beyond column n (ties: wider).
 static int rpca_col_tile(int64_t n) {
   int best = 256;
@@ -295,8 +301,21 @@ __global__ void k_scale_rsqrt(T* __restrict__ P, int64_t count, const double* __
   P[i] = v > 0.0 ? (T)((double)P[i] / sqrt(v)) : T(0);
 }
 
-// Columns per workgroup of the update kernel for rows of n elements of esz bytes.
-static int rpca_update_col_tile(int64_t n, int esz) { return rpca_vec_ok(n, esz) ? 64 * (16 / esz) : rpca_col_tile(n); }
+// Shape of the update kernel's workgroups for rows of n elements of esz bytes: vector columns per tile
+// (64, or the whole row when it is shorter) and rows per tile.
+constexpr int kRpcaUpdWaves = 8, kRpcaUpdRPT = 4;
+struct RpcaUpdShape {
+  int cvt, col_tiles, tile_rows;
+};
+static RpcaUpdShape rpca_update_shape(int64_t n, int esz) {
+  const int vw = 16 / esz;
+  const int64_t nvc = ceil_div(n, vw);
+  RpcaUpdShape s;
+  s.cvt = (int)std::min<int64_t>(64, nvc);
+  s.col_tiles = (int)ceil_div(nvc, s.cvt);
+  s.tile_rows = (kRpcaUpdWaves * 64 / s.cvt) * kRpcaUpdRPT;
+  return s;
+}
 
 uint64_t rpca_part_doubles(int64_t m, int64_t n) {
   // the narrowest column tile any element type can take (64) bounds the number of partial sums
@@ -323,26 +342,29 @@ int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hi
 template <typename T>
 int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
                 T mu_next, T* Lout, T* S, T* Y, T* X, double* part, int* nparts_out, hipStream_t stream) {
-  const int cw = rpca_update_col_tile(n, (int)sizeof(T));
-  dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
-  if (grid.y > 65535) return BRSVD_ERR_ARG;
-  *nparts_out = (int)(grid.x * grid.y);
-  const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
-  if (rpca_vec_ok(n, (int)sizeof(T)) && ((uintptr_t)M | (uintptr_t)S | (uintptr_t)Y | (uintptr_t)X | (uintptr_t)Vt |
-                                         (uintptr_t)Lout) % 16 == 0) {
-    hipLaunchKernelGGL((k_rpca_update_vec<T, 8>), grid, dim3(512), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,
-                       lambda / mu, T(1) / mu_next, Lout, S, Y, X, part);
-    BRSVD_HIP_TRY(hipGetLastError());
-    return BRSVD_OK;
+  if (m <= 0 || n <= 0 || l <= 0) return BRSVD_ERR_ARG;
+  const RpcaUpdShape sh = rpca_update_shape(n, (int)sizeof(T));
+  const int64_t wgs = ceil_div(m, sh.tile_rows) * sh.col_tiles;
+  if (wgs > INT32_MAX) return BRSVD_ERR_ARG;
+  *nparts_out = (int)wgs;
+  // the tile's rows of U: 32 x l elements with 64 vector columns; at most 32 KiB when rows are short (l <= n)
+  const size_t lds = (size_t)sh.tile_rows * l * sizeof(T);
+  constexpr int kMaxLds = 128 * 1024;
+  if (lds > (size_t)kMaxLds) return BRSVD_ERR_ARG;
+  // nontemporal accesses when every row starts on a 16-byte boundary; otherwise rows share their first and
+  // last cache lines with their neighbours and plain accesses let the caches merge them
+  constexpr int VW = 16 / (int)sizeof(T);
+  const bool stream_ok = n % VW == 0 && ((uintptr_t)M | (uintptr_t)S | (uintptr_t)Y | (uintptr_t)X) % 16 == 0;
+  auto kern = stream_ok ? k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, true>
+                        : k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, false>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[stream_ok]) {
+    BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
+    attr_set[stream_ok] = true;
   }
-  if (cw != rpca_col_tile(n)) return BRSVD_ERR_ARG;      // misaligned arrays with an aligned row length: not supported
-#define BRSVD_RPCA_UPDATE(CW)                                                                                      \
-  hipLaunchKernelGGL((k_rpca_update<T, CW>), grid, dim3(256), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu,  \
-                     lambda / mu, T(1) / mu_next, Lout, S, Y, X, part)
-  if (cw == 256) BRSVD_RPCA_UPDATE(256);
-  else if (cw == 128) BRSVD_RPCA_UPDATE(128);
-  else BRSVD_RPCA_UPDATE(64);
-#undef BRSVD_RPCA_UPDATE
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kRpcaUpdWaves * 64), lds,
+                     stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu, lambda / mu, T(1) / mu_next, Lout, S, Y, X, part,
+                     sh.cvt, sh.col_tiles);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }

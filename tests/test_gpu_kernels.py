@@ -61,6 +61,30 @@ def test_gemm_at_matches_oracle(rows, n, l):
                   2 * _bound(np.abs(A.T).astype(np.float64), np.abs(Q).astype(np.float64), rows))
 
 
+@pytest.mark.parametrize("rows,n,l,off", [(600, 1001, 8, 0), (600, 1002, 16, 1), (600, 1003, 40, 2), (300, 3, 3, 1),
+                                          (5000, 101, 20, 3), (900, 2383, 20, 0), (1100, 1025, 110, 1),
+                                          (130, 6, 5, 0), (2000, 254, 30, 1)])
+def test_gemm_rows_at_any_alignment(rows, n, l, off):
+    """Rows of A that start at any element address (odd row length, base pointer `off` elements past an aligned
+    one): both products against the oracle, elementwise."""
+    dev = need_gpu()
+    print(f"[case] gemm alignment rows={rows} n={n} l={l} off={off}", flush=True)
+    A = synth.gaussian(rows, n, 111).numpy()
+    X = synth.gaussian(n, l, 112).numpy()
+    Q = synth.gaussian(rows, l, 113).numpy()
+    flat = torch.zeros(rows * n + 8, dtype=torch.float32, device=dev)
+    Ad = flat[off:off + rows * n].view(rows, n)
+    Ad.copy_(torch.from_numpy(A))
+    assert Ad.data_ptr() % 16 == (4 * off) % 16
+    Y = B.brsvd_gemm_an(Ad, torch.from_numpy(X).to(dev))
+    Z = B.brsvd_gemm_at(Ad, torch.from_numpy(Q).to(dev))
+    torch.cuda.synchronize()
+    dy = np.abs(Y.double().cpu().numpy() - O.a_times(A, X.astype(np.float64), b=128))
+    assert np.all(dy <= _bound(np.abs(A).astype(np.float64), np.abs(X).astype(np.float64), n))
+    dz = np.abs(Z.double().cpu().numpy() - O.at_times(A, Q.astype(np.float64), b=100))
+    assert np.all(dz <= _bound(np.abs(A.T).astype(np.float64), np.abs(Q).astype(np.float64), rows))
+
+
 def test_gemm_with_row_stride():
     """A given as a view with lda > n (a column slab of a wider matrix)."""
     dev = need_gpu()

@@ -18,10 +18,16 @@ def _case(m, n, iters=30):
     return cfg, D, L0, S0, Om
 
 
-def test_shrink_and_update_kernels_one_iteration():
+@pytest.mark.parametrize("m0,n0", [(500, 300),     # rows of whole 16-byte vectors, two column tiles
+                                   (700, 100),     # short rows: 25 vectors, 20 row lanes per workgroup
+                                   (600, 203),     # short rows of odd length: every row starts at another alignment
+                                   (400, 1003),    # long rows of odd length: the last lane straddles the row's end
+                                   (900, 22)])     # l = 20 of 22 columns
+def test_shrink_and_update_kernels_one_iteration(m0, n0):
     """One ALM iteration on the GPU equals one oracle iteration (same SVD input, fp32 vs fp64)."""
     dev = need_gpu()
-    cfg, D, L0, S0, Om = _case(500, 300, iters=1)
+    print(f"[case] rpca one iteration m={m0} n={n0}", flush=True)
+    cfg, D, L0, S0, Om = _case(m0, n0, iters=1)
     m, n = D.shape
     lam = 1.0 / np.sqrt(max(m, n))
     n2 = float(np.linalg.norm(D.double().numpy(), 2))

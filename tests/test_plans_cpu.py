@@ -35,7 +35,7 @@ def _check_an(rows, K, l, dtype):
     esz = 8 if dtype == B.BRSVD_DTYPE_F64 else 4
     Lp = (l + 15) // 16 * 16
     assert T == -(-rows // tile_rows) and whole + lt == T and groups * nt * 16 >= Lp
-    narrow = esz == 4 and nt == 1                # fp32 panels of one column tile: 32-row tiles, 256-column chunks
+    narrow = esz == 4 and nt == 1 and K >= 512   # fp32 panels of one column tile over long rows: 32-row tiles, 256-column chunks
     kc = 256 if narrow else (32 if (esz == 8 or nt > 8) else 64)
     assert tile_rows == 32 if narrow else tile_rows % 16 == 0
     assert C == -(-K // kc)
