@@ -54,14 +54,11 @@ template <> struct El<double> {
   __device__ static __forceinline__ int acc_row(int g, int v) { return g + 4 * v; }
 };
 
-// Streaming (nontemporal) load where STREAM, plain load otherwise.  Rows that do not start on 16-byte boundaries
-// share their first and last cache lines with the neighbouring accesses; a streaming load does not keep a line
-// for the neighbour, so such rows are read with plain loads.
-template <bool STREAM, typename V>
-__device__ __forceinline__ V load_a(const V* p) {
-  if constexpr (STREAM) return __builtin_nontemporal_load(p);
-  else return *p;
-}
+// Streaming (nontemporal) load for the instances whose rows start on 16-byte boundaries, plain load for the
+// RAGGED ones: rows at other alignments share their first and last cache lines with the neighbouring accesses,
+// and a streaming load does not keep a line for the neighbour.  A macro, so that the pointer keeps the reduced
+// alignment of its type (a function template would deduce the fully aligned vector type).
+#define BRSVD_LOAD_A(P) (RAGGED ? *(P) : __builtin_nontemporal_load(P))
 
 // Identity the compiler cannot see through: the result is a new value living in VGPRs.  Used to
 // hand the prefetched block of A over to the MFMA stream, so that (a) the wait for the prefetch
@@ -384,7 +381,7 @@ k_gemm_an_narrow(const float* __restrict__ A, int64_t lda, int rows, int K,
       _Pragma("unroll") for (int j = 0; j < 4; ++j)                                \
         dst[i][j] = ap[min(k + j, K - 1)];                                         \
     } else {                                                                       \
-      dst[i] = load_a<!RAGGED>((const floatx4u*)(ap + min(k, K - 4)));             \
+      dst[i] = BRSVD_LOAD_A((const floatx4u*)(ap + min(k, K - 4)));             \
     }                                                                              \
   }
 #define STORE_A(src)                                                               \
@@ -544,7 +541,7 @@ k_gemm_at(const T* __restrict__ A, int64_t lda, int64_t rows_total, int n,
       _Pragma("unroll") for (int j = 0; j < MT; ++j)                               \
         dst[s][j] = p[col[j]];                                                     \
     } else {                                                                       \
-      dst[s] = load_a<!RAGGED>((const vecTu*)(p + col[0]));                        \
+      dst[s] = BRSVD_LOAD_A((const vecTu*)(p + col[0]));                        \
     }                                                                              \
   }
 
