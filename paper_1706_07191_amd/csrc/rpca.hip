@@ -265,13 +265,14 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
 template <typename T, int CW>
 __global__ void __launch_bounds__(256)
 k_rpca_lowrank(const T* __restrict__ U, const T* __restrict__ sig, const T* __restrict__ Vt,
-               int64_t m, int64_t n, int l, T inv_mu, T* __restrict__ Lout) {
+               int64_t m, int64_t n, int l, T inv_mu, T* __restrict__ Lout, int col_tiles) {
   extern __shared__ __align__(16) unsigned char us_raw[];
   T* us = reinterpret_cast<T*>(us_raw);
   constexpr int RPT = kRpcaTR * CW / 256;
   const int rsub = (threadIdx.x / CW) * RPT;
-  const int64_t col = (int64_t)blockIdx.x * CW + threadIdx.x % CW;
-  const int64_t row0 = (int64_t)blockIdx.y * kRpcaTR;
+  const int ct = blockIdx.x % col_tiles, rt = blockIdx.x / col_tiles;   // column tiles of a row tile are neighbours
+  const int64_t col = (int64_t)ct * CW + threadIdx.x % CW;
+  const int64_t row0 = (int64_t)rt * kRpcaTR;
   T acc[RPT];
   lowrank_tile<T, RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
   if (col < n) {
@@ -387,12 +388,13 @@ template <typename T>
 int rpca_lowrank(const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T* Lout,
                  hipStream_t stream) {
   const int cw = rpca_col_tile(n);
-  dim3 grid((unsigned)ceil_div(n, cw), (unsigned)ceil_div(m, kRpcaTR));
-  if (grid.y > 65535) return BRSVD_ERR_ARG;
+  const int64_t col_tiles = ceil_div(n, cw), wgs = col_tiles * ceil_div(m, kRpcaTR);
+  if (wgs > INT32_MAX) return BRSVD_ERR_ARG;
+  const dim3 grid((unsigned)wgs);
   const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
-  if (cw == 256) hipLaunchKernelGGL((k_rpca_lowrank<T, 256>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
-  else if (cw == 128) hipLaunchKernelGGL((k_rpca_lowrank<T, 128>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
-  else hipLaunchKernelGGL((k_rpca_lowrank<T, 64>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout);
+  if (cw == 256) hipLaunchKernelGGL((k_rpca_lowrank<T, 256>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
+  else if (cw == 128) hipLaunchKernelGGL((k_rpca_lowrank<T, 128>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
+  else hipLaunchKernelGGL((k_rpca_lowrank<T, 64>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }

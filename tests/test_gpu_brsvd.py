@@ -67,7 +67,7 @@ def test_largest_sketch_width():
 @pytest.mark.parametrize("m,n,k,p,q,b", [(900, 700, 20, 10, 0, 256),      # no power iteration: sketch and projection only
                                           (640, 64, 8, 8, 3, 640),        # one block, l = 16 = a single column tile, q = 3
                                           (70, 4000, 30, 10, 1, 32),      # very wide: fewer rows than a row tile per block
-                                          (4100, 33, 5, 0, 2, 1000),      # p = 0, odd n (scalar load path), ragged tail of 100 rows
+                                          (4100, 33, 5, 0, 2, 1000),      # p = 0, odd n (rows at every alignment), ragged tail of 100 rows
                                           (50, 40, 39, 1, 1, 7)])         # l = min(m, n): the sketch spans everything
 def test_degenerate_shapes_and_parameters(m, n, k, p, q, b):
     dev = need_gpu()

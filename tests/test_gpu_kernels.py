@@ -19,7 +19,7 @@ def _bound(absA, absX, K):
 
 GEMM_SHAPES = [  # rows, n, l
     (1000, 1000, 30),     # C1-like, ragged rows (1000 = 7*128 + 104)
-    (77, 1003, 20),       # unaligned n -> scalar load path, fewer rows than a tile
+    (77, 1003, 20),       # odd row length: rows at every alignment, fewer rows than a tile
     (513, 2048, 110),     # C2 width, 7 column tiles
     (300, 1024, 272),     # C3 width, 17 column tiles
     (260, 520, 300),      # two column groups
@@ -208,7 +208,7 @@ EPS64 = float(np.finfo(np.float64).eps)
 @pytest.mark.parametrize("rows,n,l", GEMM_SHAPES)
 def test_gemm_f64_matches_oracle(rows, n, l):
     """fp64 path against the fp64 oracle: elementwise within 8 sqrt(K) eps64 (|A| |X|), both products,
-    the accumulate flag, and an unaligned view (scalar load path)."""
+    the accumulate flag, and an unaligned view (rows off the 16-byte grid)."""
     dev = need_gpu()
     A = synth.gaussian(rows, n, 201, dtype=torch.float64)
     X = synth.gaussian(n, l, 202, dtype=torch.float64)
