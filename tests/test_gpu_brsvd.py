@@ -460,3 +460,50 @@ def test_config4_streaming_large_block_against_oracle():
         assert rel < 2e-5
     finally:
         pm.free()
+
+
+def test_config4_at_the_largest_pinnable_size_properties():
+    """The out-of-core configuration at 160000 of its 200000 rows (64 GB of pinned host memory, what the GPU machine lets a
+    process pin; bench.py times this size): ten blocks of 16384 x 100000 through two staging buffers under the 16 GiB
+    device budget.  The oracle takes minutes at this size, so the result is held to what holds at any size, evaluated
+    in fp64 on the GPU: orthonormal U and V, the triplet identity U^T A = diag(S) V^T, and sigma against the same
+    recipe's resident-in-HBM run."""
+    dev = need_gpu()
+    cfg = synth.CONFIGS["C4"].scaled(160000, 100000)
+    try:
+        pm = B.PinnedMatrix(cfg.m, cfg.n)
+    except MemoryError as e:                            # a box that pins less: the 40000-row test above still ran
+        pytest.skip(f"cannot pin 64 GB on this box: {e}")
+    try:
+        print("[case] C4 at 160000 rows: generating A", flush=True)
+        cfg.make_A(device="cpu", out=pm.tensor, gen_device=dev)
+        Om = cfg.make_Omega(device=dev)
+        prm = B.make_params(cfg.m, cfg.n, cfg.k, cfg.p, cfg.q, row_block=cfg.row_block,
+                            a_location=B.BRSVD_A_HOST_PINNED, device_budget_bytes=cfg.device_budget)
+        assert B.brsvd_workspace_bytes(prm) <= cfg.device_budget
+        h = B.brsvd_create(prm)
+        try:
+            print("[case] C4 at 160000 rows: streaming run", flush=True)
+            U, S, Vt, st = B.brsvd_run(h, pm.tensor, Om, pinned=True)
+        finally:
+            B.brsvd_destroy(h)
+        assert st["n_blocks"] == 10 and st["passes_over_A"] == 4 and st["bytes_A_streamed"] == 4 * 4 * cfg.m * cfg.n
+        A_rows = lambda a, b: pm.tensor[a:b].to(dev)
+        print("[case] C4 at 160000 rows: fp64 properties", flush=True)
+        orthU, orthV, triplet, err_l = _fp64_properties(A_rows, cfg.m, cfg.n, U, S, Vt, dev)
+        print(f"[C4-160000] orthU={orthU:.2e} orthV={orthV:.2e} triplet={triplet:.2e} err_l={err_l:.4e} "
+              f"seconds={st['total_seconds']:.3f} link={st['bytes_A_streamed'] / st['total_seconds'] / 1e9:.1f} GB/s", flush=True)
+        assert orthU <= 1e-5 and orthV <= 1e-5 and triplet <= 1e-4
+        sg = S.double().cpu().numpy()
+        assert np.all(np.diff(sg) <= 0) and np.all(sg >= 0)
+        # the same 64 GB resident in HBM (288 GB of it): same singular values
+        A_dev = torch.empty(cfg.m, cfg.n, device=dev, dtype=torch.float32)
+        for r0 in range(0, cfg.m, 16384):
+            A_dev[r0:r0 + 16384].copy_(pm.tensor[r0:r0 + 16384], non_blocking=False)
+        U2, S2, Vt2, _ = _run(cfg, A_dev, Om)
+        rel = ((S2[:cfg.k] - S[:cfg.k]).abs() / S[:cfg.k]).max().item()
+        print(f"[C4-160000] sigma host-resident vs device-resident: {rel:.2e}", flush=True)
+        assert rel < 2e-5
+        del A_dev
+    finally:
+        pm.free()
