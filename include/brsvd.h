@@ -193,7 +193,9 @@ int brsvd_philox_normal_f64(uint64_t seed, int64_t row0, int64_t rows, int32_t c
  *   norm2_M  spectral norm of M (multiplier initialisation Y_0 = M / max(||M||_2,
  *            max|M_ij| / lambda)); pass <= 0 to have it estimated by one randomized SVD
  *            using Omegas[0].
- *   L, S     DEVICE out, m x n: low-rank and sparse parts.
+ *   L, S     DEVICE out, m x n: low-rank and sparse parts of the last iteration run; both are written once, after
+ *            the loop (an iteration stores neither), and L serves as working storage for the multiplier while
+ *            the loop runs.  L, S, work and M must not overlap.
  *   residuals HOST out (may be NULL), iters doubles: ||M-L-S||_F / ||M||_F per iteration.
  *   work     DEVICE scratch of 2*m*n floats owned by the caller (multiplier and the
  *            matrix handed to the SVD), so the handle's budget stays panel-sized.

@@ -744,7 +744,10 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   const int64_t m = h->prm.m, n = h->prm.n, count = m * n;
   const int l = h->l;
   hipStream_t cs = h->compute;
-  T* Y = work;
+  // The multiplier alternates between the first half of `work` and L (an output nobody reads before the loop ends),
+  // so the multiplier an iteration read is still there when the loop stops and L and S are formed from it.
+  T* Ycur = work;
+  T* Yalt = L;
   T* X = work + count;
   T* Uw = h->at<T>(h->lay.rpcaU);
   T* Vtw = h->at<T>(h->lay.rpcaVt);
@@ -788,7 +791,7 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
   double mu = mu0;
   {
     Region r(h, CAT_ELEM, cs);
-    BRSVD_TRY(rpca_init<T>(M, count, (T)(1.0 / J), (T)(1.0 / mu), Y, S, X, cs));
+    BRSVD_TRY(rpca_init<T>(M, count, (T)(1.0 / J), (T)(1.0 / mu), Ycur, S, X, cs));
   }
   int it = 0;
   double mu_last = mu;
@@ -805,8 +808,9 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
         {
           Region u(h, CAT_UPD, cs);
           h->launches[CAT_UPD]++;
-          BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, nullptr, S, Y, X, part, &nparts,
+          BRSVD_TRY(rpca_update<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu, (T)lambda, (T)mu_next, Ycur, Yalt, X, part, &nparts,
                                    cs));
+          std::swap(Ycur, Yalt);                       // Yalt: what this iteration read
         }
         BRSVD_TRY(rpca_residual_sum(part, nparts, scal + 2, cs));
       }
@@ -820,10 +824,10 @@ int rpca_loop(brsvd_handle h, const T* M, const T* Omegas, int32_t max_iters, do
     if (res < tol) break;       // the stopping rule of Alg. 3: mu is not advanced any more
     mu = mu_next;
   }
-  // L of the last iteration run: its triplets and its mu are still in place
+  // L and S of the last iteration run: its triplets, its mu and the multiplier it read are still in place
   {
     Region r(h, CAT_ELEM, cs);
-    BRSVD_TRY(rpca_lowrank<T>(Uw, Sw, Vtw, m, n, l, (T)mu_last, L, cs));
+    BRSVD_TRY(rpca_finalize<T>(M, Uw, Sw, Vtw, m, n, l, (T)mu_last, (T)lambda, Yalt, L, S, cs));
   }
   BRSVD_HIP_TRY(hipStreamSynchronize(cs));
   flush_stats(0, 0);

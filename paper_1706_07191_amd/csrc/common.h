@@ -142,18 +142,20 @@ template <typename T> int rpca_norms(const T* M, int64_t count, double* part, do
 // Y0 = M * inv_J, S0 = 0, X0 = M - S0 + Y0 * inv_mu
 template <typename T>
 int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hipStream_t stream);
-// Fused update after the SVD of X_i: L = U diag(shrink(sig, 1/mu)) Vt (contraction over l),
-// S = shrink(M - L + Y/mu, lambda/mu), Y += mu (M - L - S), per-workgroup partial sums of ||M-L-S||_F^2
-// into `part` (*nparts_out of them), and the next SVD input X = M - S + Y/mu_next.  U is m x l (ld l), Vt is
-// l x n (ld n).  Lout may be null.  rpca_residual_sum then adds the partial sums into *resid2_out in a fixed order.
+// Fused update after the SVD of X_i: with L = U diag(shrink(sig, 1/mu)) Vt (contraction over l) and
+// S = shrink(M - L + Yin/mu, lambda/mu) formed in registers, writes Yout = Yin + mu (M - L - S), the next SVD input
+// X = M - S + Yout/mu_next and per-workgroup partial sums of ||M-L-S||_F^2 into `part` (*nparts_out of them); L and
+// S themselves are not stored.  U is m x l (ld l), Vt is l x n (ld n); Yout may be Yin.  rpca_residual_sum then adds
+// the partial sums into *resid2_out in a fixed order.
 template <typename T>
 int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
-                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, int* nparts_out, hipStream_t stream);
+                T mu_next, const T* Yin, T* Yout, T* X, double* part, int* nparts_out, hipStream_t stream);
 int rpca_residual_sum(double* part, int nparts, double* resid2_out, hipStream_t stream);
-// Lout = U diag(shrink(sig, 1/mu)) Vt, the low-rank part of the iteration that used (U, sig, Vt, mu).
+// L and S of the iteration that used (U, sig, Vt, mu) and read the multiplier Yin, with the arithmetic of rpca_update.
+// Lout may be Yin.
 template <typename T>
-int rpca_lowrank(const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T* Lout,
-                 hipStream_t stream);
+int rpca_finalize(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
+                  const T* Yin, T* Lout, T* S, hipStream_t stream);
 // P[0..count) *= 1 / sqrt(*s2) (device scalar; a zero scalar zeroes P).
 template <typename T> int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream);
 

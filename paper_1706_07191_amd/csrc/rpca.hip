@@ -99,39 +99,17 @@ __device__ __forceinline__ T shrinkf(T x, T eps) {
 
 constexpr int kRpcaTR = 32;
 
-// acc[i] = row (row0 + rsub + i) of U diag(shrink(sigma, inv_mu)) V^T at column `col` (zero beyond n);
-// `us` (LDS, kRpcaTR x l) receives the block's rows of U scaled by the shrunk singular values.
-template <typename T, int RPT>
-__device__ __forceinline__ void lowrank_tile(const T* __restrict__ U, const T* __restrict__ sig,
-                                             const T* __restrict__ Vt, int64_t m, int64_t n, int l,
-                                             T inv_mu, int64_t row0, int rsub, int64_t col, T* us,
-                                             T (&acc)[RPT]) {
-  const int tid = threadIdx.x;
-  for (int idx = tid; idx < kRpcaTR * l; idx += 256) {
-    const int i = idx / l, t = idx - i * l;
-    const int64_t row = row0 + i;
-    const T sv = fmax(sig[t] - inv_mu, T(0));      // shrinkage of a non-negative singular value
-    us[idx] = row < m ? U[row * l + t] * sv : T(0);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < RPT; ++i) acc[i] = T(0);
-  if (col < n) {
-    for (int t = 0; t < l; ++t) {
-      const T v = Vt[(int64_t)t * n + col];
-#pragma unroll
-      for (int i = 0; i < RPT; ++i) acc[i] = fma(us[(rsub + i) * l + t], v, acc[i]);
-    }
-  }
-}
-
 // One ALM iteration after the SVD of X_i (the low-rank, sparse, multiplier and residual updates of
 // Alg. 3, and the matrix handed to the SVD of the next iteration):
 //   L = U diag(shrink(sigma, 1/mu)) V^T        (rank-l product, recomputed here, terms added in index order)
 //   S = shrink(M - L + Y/mu, lambda/mu)
-//   Z = M - L - S;  Y += mu Z;  partial ||Z||_F^2
-//   X_next = M - S + Y / mu_next
-// L is stored only when Lout != nullptr.
+//   Z = M - L - S;  Y_out = Y_in + mu Z;  partial ||Z||_F^2
+//   X_next = M - S + Y_out / mu_next
+// Neither L nor S is stored by an iteration: nothing reads them before the loop ends, and leaving them out makes
+// an iteration two reads (M, Y_in) and two writes (Y_out, X_next) per element.  The multiplier goes from one
+// buffer to another, so that when the loop has ended the FINAL instance can repeat the last iteration's
+// arithmetic on the multiplier that iteration read and store its L and S (and nothing else); Y_in may be the
+// buffer L goes to (every thread reads its elements before it writes them).
 //
 // A lane moves 16 bytes (VW elements) of one row per access, at any element alignment (rows of odd length do
 // not start on 16-byte boundaries); the lane that straddles the end of a row moves its elements one by one.  M
@@ -145,12 +123,12 @@ __device__ __forceinline__ void lowrank_tile(const T* __restrict__ U, const T* _
 // most lanes of a 64-lane column tile idle.  Eight waves of four rows each measured best on 76800 x 2000
 // (581 us; four waves of eight rows 606 us, sixteen of two 619 us; one element per lane 664 us; a plain
 // kernel with the same two reads and three writes per element reaches 5.4 TB/s = 570 us).
-template <typename T, int WAVES, int RPT, bool STREAM>
+template <typename T, int WAVES, int RPT, bool STREAM, bool FINAL>
 __global__ void __launch_bounds__(WAVES * 64)
 k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
                   const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
-                  T thr_s, T inv_mu_next, T* __restrict__ Lout, T* __restrict__ S,
-                  T* __restrict__ Y, T* __restrict__ X, double* __restrict__ part, int cvt, int col_tiles) {
+                  T thr_s, T inv_mu_next, const T* Yin, T* Yout, T* __restrict__ X, T* Lout, T* __restrict__ S,
+                  double* __restrict__ part, int cvt, int col_tiles) {
   extern __shared__ __align__(16) unsigned char us_raw[];
   T* us = reinterpret_cast<T*>(us_raw);
   __shared__ double sh[WAVES];
@@ -181,10 +159,10 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
         const int64_t row = min(row0 + tr + (int64_t)TR * i, m - 1);
         if constexpr (STREAM) {
           mv[i] = __builtin_nontemporal_load((const vecTu*)(M + row * n + col));
-          yv[i] = __builtin_nontemporal_load((const vecTu*)(Y + row * n + col));
+          yv[i] = __builtin_nontemporal_load((const vecTu*)(Yin + row * n + col));
         } else {
           mv[i] = *(const vecTu*)(M + row * n + col);
-          yv[i] = *(const vecTu*)(Y + row * n + col);
+          yv[i] = *(const vecTu*)(Yin + row * n + col);
         }
         acc[i] = vecT{};
       }
@@ -204,7 +182,7 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
         mv[i] = vecT{}; yv[i] = vecT{}; acc[i] = vecT{};
 #pragma unroll
         for (int c = 0; c < VW; ++c)
-          if (c < cnt) { mv[i][c] = M[row * n + col + c]; yv[i][c] = Y[row * n + col + c]; }
+          if (c < cnt) { mv[i][c] = M[row * n + col + c]; yv[i][c] = Yin[row * n + col + c]; }
       }
       for (int t = 0; t < l; ++t) {
         vecT v = vecT{};
@@ -235,62 +213,32 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
         }
         const int64_t e = row * n + col;
         if (cnt == VW) {
-          if constexpr (STREAM) {
-            __builtin_nontemporal_store(sv, (vecTu*)(S + e));
-            __builtin_nontemporal_store(yn, (vecTu*)(Y + e));
+          if constexpr (FINAL) {
+            if constexpr (STREAM) __builtin_nontemporal_store(sv, (vecTu*)(S + e));
+            else *(vecTu*)(S + e) = sv;
+            *(vecTu*)(Lout + e) = acc[i];
+          } else if constexpr (STREAM) {
+            __builtin_nontemporal_store(yn, (vecTu*)(Yout + e));
             __builtin_nontemporal_store(xn, (vecTu*)(X + e));
           } else {
-            *(vecTu*)(S + e) = sv;
-            *(vecTu*)(Y + e) = yn;
+            *(vecTu*)(Yout + e) = yn;
             *(vecTu*)(X + e) = xn;
           }
-          if (Lout) *(vecTu*)(Lout + e) = acc[i];
         } else {
 #pragma unroll
           for (int c = 0; c < VW; ++c)
             if (c < cnt) {
-              S[e + c] = sv[c]; Y[e + c] = yn[c]; X[e + c] = xn[c];
-              if (Lout) Lout[e + c] = acc[i][c];
+              if constexpr (FINAL) { S[e + c] = sv[c]; Lout[e + c] = acc[i][c]; }
+              else { Yout[e + c] = yn[c]; X[e + c] = xn[c]; }
             }
         }
       }
     }
   }
-  const double s = block_sum(z2, sh);
-  if (tid == 0) part[blockIdx.x] = s;
-}
-
-// L = U diag(shrink(sigma, 1/mu)) V^T written out once (after the last ALM iteration), with the
-// same tile arithmetic as the update kernel, so it is the L that iteration used.
-template <typename T, int CW>
-__global__ void __launch_bounds__(256)
-k_rpca_lowrank(const T* __restrict__ U, const T* __restrict__ sig, const T* __restrict__ Vt,
-               int64_t m, int64_t n, int l, T inv_mu, T* __restrict__ Lout, int col_tiles) {
-  extern __shared__ __align__(16) unsigned char us_raw[];
-  T* us = reinterpret_cast<T*>(us_raw);
-  constexpr int RPT = kRpcaTR * CW / 256;
-  const int rsub = (threadIdx.x / CW) * RPT;
-  const int ct = blockIdx.x % col_tiles, rt = blockIdx.x / col_tiles;   // column tiles of a row tile are neighbours
-  const int64_t col = (int64_t)ct * CW + threadIdx.x % CW;
-  const int64_t row0 = (int64_t)rt * kRpcaTR;
-  T acc[RPT];
-  lowrank_tile<T, RPT>(U, sig, Vt, m, n, l, inv_mu, row0, rsub, col, us, acc);
-  if (col < n) {
-#pragma unroll
-    for (int i = 0; i < RPT; ++i)
-      if (row0 + rsub + i < m) Lout[(row0 + rsub + i) * n + col] = acc[i];
+  if constexpr (!FINAL) {
+    const double s = block_sum(z2, sh);
+    if (tid == 0) part[blockIdx.x] = s;
   }
-}
-
-// Column tile: the width among 256, 128, 64 that wastes the fewest lanes beyond column n (ties: wider).
-static int rpca_col_tile(int64_t n) {
-  int best = 256;
-  int64_t waste = ceil_div(n, 256) * 256 - n;
-  for (int cw : {128, 64}) {
-    const int64_t w = ceil_div(n, cw) * cw - n;
-    if (w < waste) { waste = w; best = cw; }
-  }
-  return best;
 }
 
 // P *= 1 / sqrt(*s2)  (normalisation of a power-method vector held in a padded panel)
@@ -340,14 +288,15 @@ int rpca_init(const T* M, int64_t count, T inv_J, T inv_mu, T* Y, T* S, T* X, hi
   return BRSVD_OK;
 }
 
-template <typename T>
-int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
-                T mu_next, T* Lout, T* S, T* Y, T* X, double* part, int* nparts_out, hipStream_t stream) {
+template <typename T, bool FINAL>
+static int rpca_update_launch(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu,
+                              T lambda, T mu_next, const T* Yin, T* Yout, T* X, T* Lout, T* S, double* part,
+                              int* nparts_out, hipStream_t stream) {
   if (m <= 0 || n <= 0 || l <= 0) return BRSVD_ERR_ARG;
   const RpcaUpdShape sh = rpca_update_shape(n, (int)sizeof(T));
   const int64_t wgs = ceil_div(m, sh.tile_rows) * sh.col_tiles;
   if (wgs > INT32_MAX) return BRSVD_ERR_ARG;
-  *nparts_out = (int)wgs;
+  if (nparts_out) *nparts_out = (int)wgs;
   // the tile's rows of U: 32 x l elements with 64 vector columns; at most 32 KiB when rows are short (l <= n)
   const size_t lds = (size_t)sh.tile_rows * l * sizeof(T);
   constexpr int kMaxLds = 128 * 1024;
@@ -355,19 +304,34 @@ int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, in
   // nontemporal accesses when every row starts on a 16-byte boundary; otherwise rows share their first and
   // last cache lines with their neighbours and plain accesses let the caches merge them
   constexpr int VW = 16 / (int)sizeof(T);
-  const bool stream_ok = n % VW == 0 && ((uintptr_t)M | (uintptr_t)S | (uintptr_t)Y | (uintptr_t)X) % 16 == 0;
-  auto kern = stream_ok ? k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, true>
-                        : k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, false>;
+  const uintptr_t bits = FINAL ? ((uintptr_t)M | (uintptr_t)Yin | (uintptr_t)S | (uintptr_t)Lout)
+                               : ((uintptr_t)M | (uintptr_t)Yin | (uintptr_t)Yout | (uintptr_t)X);
+  const bool stream_ok = n % VW == 0 && bits % 16 == 0;
+  auto kern = stream_ok ? k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, true, FINAL>
+                        : k_rpca_update_vec<T, kRpcaUpdWaves, kRpcaUpdRPT, false, FINAL>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[stream_ok]) {
     BRSVD_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds));
     attr_set[stream_ok] = true;
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kRpcaUpdWaves * 64), lds,
-                     stream, M, U, sig, Vt, m, n, l, T(1) / mu, mu, lambda / mu, T(1) / mu_next, Lout, S, Y, X, part,
-                     sh.cvt, sh.col_tiles);
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kRpcaUpdWaves * 64), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu,
+                     mu, lambda / mu, T(1) / mu_next, Yin, Yout, X, Lout, S, part, sh.cvt, sh.col_tiles);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
+}
+
+template <typename T>
+int rpca_update(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
+                T mu_next, const T* Yin, T* Yout, T* X, double* part, int* nparts_out, hipStream_t stream) {
+  return rpca_update_launch<T, false>(M, U, sig, Vt, m, n, l, mu, lambda, mu_next, Yin, Yout, X, nullptr, nullptr, part,
+                                      nparts_out, stream);
+}
+
+template <typename T>
+int rpca_finalize(const T* M, const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T lambda,
+                  const T* Yin, T* Lout, T* S, hipStream_t stream) {
+  return rpca_update_launch<T, true>(M, U, sig, Vt, m, n, l, mu, lambda, mu /* unused */, Yin, nullptr, nullptr, Lout, S,
+                                     nullptr, nullptr, stream);
 }
 
 // *resid2_out = sum of the per-workgroup partial sums rpca_update left in `part`, in two levels when
@@ -385,21 +349,6 @@ int rpca_residual_sum(double* part, int nparts, double* resid2_out, hipStream_t 
 }
 
 template <typename T>
-int rpca_lowrank(const T* U, const T* sig, const T* Vt, int64_t m, int64_t n, int l, T mu, T* Lout,
-                 hipStream_t stream) {
-  const int cw = rpca_col_tile(n);
-  const int64_t col_tiles = ceil_div(n, cw), wgs = col_tiles * ceil_div(m, kRpcaTR);
-  if (wgs > INT32_MAX) return BRSVD_ERR_ARG;
-  const dim3 grid((unsigned)wgs);
-  const size_t lds = (size_t)kRpcaTR * l * sizeof(T);
-  if (cw == 256) hipLaunchKernelGGL((k_rpca_lowrank<T, 256>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
-  else if (cw == 128) hipLaunchKernelGGL((k_rpca_lowrank<T, 128>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
-  else hipLaunchKernelGGL((k_rpca_lowrank<T, 64>), grid, dim3(256), lds, stream, U, sig, Vt, m, n, l, T(1) / mu, Lout, (int)col_tiles);
-  BRSVD_HIP_TRY(hipGetLastError());
-  return BRSVD_OK;
-}
-
-template <typename T>
 int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream) {
   hipLaunchKernelGGL(k_scale_rsqrt<T>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, stream, P, count, s2);
   BRSVD_HIP_TRY(hipGetLastError());
@@ -409,9 +358,10 @@ int scale_rsqrt(T* P, int64_t count, const double* s2, hipStream_t stream) {
 #define BRSVD_RPCA_INSTANTIATE(T)                                                                                   \
   template int rpca_norms<T>(const T*, int64_t, double*, double*, hipStream_t);                                     \
   template int rpca_init<T>(const T*, int64_t, T, T, T*, T*, T*, hipStream_t);                                      \
-  template int rpca_update<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, T, T*, T*, T*,   \
+  template int rpca_update<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, T, const T*, T*, \
                               T*, double*, int*, hipStream_t);                                                      \
-  template int rpca_lowrank<T>(const T*, const T*, const T*, int64_t, int64_t, int, T, T*, hipStream_t);            \
+  template int rpca_finalize<T>(const T*, const T*, const T*, const T*, int64_t, int64_t, int, T, T, const T*, T*,  \
+                                T*, hipStream_t);                                                                   \
   template int scale_rsqrt<T>(T*, int64_t, const double*, hipStream_t);
 BRSVD_RPCA_INSTANTIATE(float)
 BRSVD_RPCA_INSTANTIATE(double)
