@@ -772,6 +772,17 @@ static AnCfg an_cfg(int nt, int esz, int64_t K) {
 }
 // Discount of partial-panel traffic: 1 for HBM-bound widths, smaller once 2*Lp/8 flop/B is past the ridge.
 static double traffic_weight(int nt) { return nt <= 2 ? 1.0 : (nt <= 4 ? 0.6 : 0.3); }
+// Workgroups per CU assumed when a launch is cut to fill the chip.  The registers alone would allow more of
+// the narrowest kernels (four-wave k_gemm_an with one or two column tiles: 112-128 registers, four workgroups per
+// CU; eight-wave k_gemm_at with one or two column tiles: 104-124 registers, two), but plans made for those counts
+// cut the contraction finer, and the extra partial panels and shorter workgroups cost more than the occupancy
+// gains on the named shapes (76800 x 2000, l = 20: 135 -> 140 us and 109 -> 114 us), so the estimates stay at two
+// and one.  The two-wave k_gemm_at (short rows) has 104 / 132 / 156 / 184 registers for one to four column tiles.
+static int an_wg_per_cu_regs(int esz, int waves) { return esz == 8 ? 2 : (waves == 8 ? 1 : 2); }
+static int at_wg_per_cu_regs(int nt, int waves) {
+  if (waves == 8) return 1;
+  return nt == 1 ? 8 : (nt <= 3 ? 6 : 4);
+}
 struct AnPlan {
   int row_tiles, tile_rows, nsplit, wgs;      // nsplit = partial panels per leftover tile (0: none)
   AnShape sh;
@@ -786,8 +797,7 @@ static AnPlan an_plan(int64_t rows, int64_t K, int nt, int esz) {
   const int T = p.row_tiles, C = (int)ceil_div(K, c.kc);
   const bool narrow = esz == 4 && nt <= kAnNarrowMaxNT && K >= kAnNarrowMinK;
   const int lds_bytes = narrow ? an_narrow_lds_bytes(nt) : 2 * c.kc * (nt * 16 + 4) * esz;
-  const int wg_regs = esz == 8 ? 2 : (c.waves == 8 ? 1 : 2);   // workgroups per CU the registers allow
-  const int S = wg_slots(lds_bytes, wg_regs);
+  const int S = wg_slots(lds_bytes, an_wg_per_cu_regs(esz, c.waves));
   AnShape sh = {C, T, 0, 1, 0, 0};
   // a split or a strip is worth its partial panel from about 512 columns on: 8 chunks of 64, 2 of 256
   const int min_piece = c.kc >= 256 ? 2 : 8, min_strip = c.kc >= 256 ? 1 : 4;
@@ -1044,7 +1054,7 @@ static AtPlan at_plan(int64_t rows, int64_t n, int nt, int64_t block_rows, int e
   const int max_sub = (int)ceil_div(block_rows, kAtKC);
   const int lds_bytes = 2 * kAtKC * at_ld(nt, esz) * esz;
   // one partial panel (n x Lp) per split, against block_rows x n of A read per block
-  const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, p.waves == kAtWaves ? 1 : 8), max_sub,
+  const int want = pick_splits((int64_t)p.col_tiles * p.nblocks, wg_slots(lds_bytes, at_wg_per_cu_regs(nt, p.waves)), max_sub,
                                (double)(nt * 16) / (double)block_rows, traffic_weight(nt));
   int64_t rps = ceil_div(block_rows, want);
   rps = ceil_div(rps, kAtKC) * kAtKC;
