@@ -408,6 +408,7 @@ class PinnedMatrix:
         ptr = C.c_void_p()
         err = self._hip.hipHostMalloc(C.byref(ptr), rows * cols * 4, 0)
         if err != 0 or not ptr.value:
+            self._hip.hipGetLastError()          # the failure is reported here; do not leave it for the next HIP call
             raise MemoryError(f"hipHostMalloc of {rows * cols * 4} bytes failed (hip error {err})")
         self.ptr = ptr.value
         buf = (C.c_float * (rows * cols)).from_address(self.ptr)
