@@ -121,8 +121,9 @@ constexpr int kRpcaTR = 32;
 // addresses: with 64 vector columns every memory instruction of a wave moves 1 KiB of one row, and a matrix of
 // short rows (100 columns: 25 vectors, 20 row lanes) is walked as one contiguous stream instead of leaving
 // most lanes of a 64-lane column tile idle.  Eight waves of four rows each measured best on 76800 x 2000
-// (581 us; four waves of eight rows 606 us, sixteen of two 619 us; one element per lane 664 us; a plain
-// kernel with the same two reads and three writes per element reaches 5.4 TB/s = 570 us).
+// (with S still stored by every iteration, i.e. three writes: 581 us; four waves of eight rows 606 us, sixteen of
+// two 619 us; one element per lane 664 us; a plain kernel with the same two reads and three writes per element
+// reaches 5.4 TB/s = 570 us; without the store of S the kernel takes 476 us).
 template <typename T, int WAVES, int RPT, bool STREAM, bool FINAL>
 __global__ void __launch_bounds__(WAVES * 64)
 k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
