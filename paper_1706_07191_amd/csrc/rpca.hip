@@ -120,16 +120,19 @@ constexpr int kRpcaTR = 32;
 // so the rows of V^T it multiplies are loaded once for all of them, and consecutive threads touch consecutive
 // addresses: with 64 vector columns every memory instruction of a wave moves 1 KiB of one row, and a matrix of
 // short rows (100 columns: 25 vectors, 20 row lanes) is walked as one contiguous stream instead of leaving
-// most lanes of a 64-lane column tile idle.  Eight waves of four rows each measured best on 76800 x 2000
+// most lanes of a 64-lane column tile idle.  The loads of M and of the multiplier are issued before the rows of U are
+// staged, and the rows of V^T are fetched four at a time.  Eight waves of four rows each measured best on 76800 x 2000
 // (with S still stored by every iteration, i.e. three writes: 581 us; four waves of eight rows 606 us, sixteen of
 // two 619 us; one element per lane 664 us; a plain kernel with the same two reads and three writes per element
-// reaches 5.4 TB/s = 570 us; without the store of S the kernel takes 476 us).
+// reaches 5.4 TB/s = 570 us; without the store of S the kernel takes 476 us, with the loads hoisted 458 us, with
+// line-aligned accesses 443 us; plain kernels with two reads and two writes per element: 401 us as one flat array,
+// 456 us in this kernel's tiles, 434 us in the tiles with line-aligned accesses).
 template <typename T, int WAVES, int RPT, bool STREAM, bool FINAL>
 __global__ void __launch_bounds__(WAVES * 64)
 k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __restrict__ sig,
                   const T* __restrict__ Vt, int64_t m, int64_t n, int l, T inv_mu, T mu,
                   T thr_s, T inv_mu_next, const T* Yin, T* Yout, T* __restrict__ X, T* Lout, T* __restrict__ S,
-                  double* __restrict__ part, int cvt, int col_tiles) {
+                  double* __restrict__ part, int cvt, int col_tiles, int line_shift) {
   extern __shared__ __align__(16) unsigned char us_raw[];
   T* us = reinterpret_cast<T*>(us_raw);
   __shared__ double sh[WAVES];
@@ -141,19 +144,24 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
   const int TR = NTHREADS / cvt, tile_rows = TR * RPT;
   const int ct = blockIdx.x % col_tiles, rt = blockIdx.x / col_tiles;
   const int64_t row0 = (int64_t)rt * tile_rows;
-  for (int idx = tid; idx < tile_rows * l; idx += NTHREADS) {
-    const int i = idx / l, t = idx - i * l;
-    const int64_t row = row0 + i;
-    const T sv = fmax(sig[t] - inv_mu, T(0));      // shrinkage of a non-negative singular value
-    us[idx] = row < m ? U[row * l + t] * sv : T(0);
-  }
-  __syncthreads();
   const int tr = tid / cvt, cv = tid - tr * cvt;
-  const int64_t col = ((int64_t)ct * cvt + cv) * VW;
-  const int cnt = (int)min((int64_t)VW, n - col);        // elements of this lane's vector inside the row
-  double z2 = 0.0;
-  if (tr < TR && cnt > 0) {
-    vecT mv[RPT], yv[RPT], acc[RPT];
+  // With 64 vector columns a wave moves 1 KiB of one row per access.  Rows whose pitch is not a whole number of
+  // 128-byte lines start inside a line, and an access that starts inside a line shares its first and last line
+  // with the neighbouring tiles' accesses (fetched and written twice by streaming accesses).  The rows of one
+  // thread are TR = 8 apart, i.e. a whole number of lines when a row is a whole number of 16-byte vectors, so they
+  // all start at the same offset within a line, and the wave shifts its columns left by that offset: every access
+  // then starts on a line (76800 x 2000: 458 -> 436 us).  The host enables this when all four arrays sit at the
+  // same offset within a line and has added the column tile the shift may need at the end of a row.
+  const int delta = line_shift ? (int)(((uintptr_t)(M + (row0 + tr) * n) % 128) / sizeof(T)) : 0;
+  const int64_t col = ((int64_t)ct * cvt + cv) * VW - delta;
+  const int cnt = col < 0 ? 0 : (int)min((int64_t)VW, n - col);   // elements of this lane's vector inside the row
+  const bool active = tr < TR && cnt > 0;
+  // the lane's elements of M and of the multiplier are requested first: they are on their way while the tile's
+  // rows of U are staged and while the rows of V^T are fetched
+  vecT mv[RPT], yv[RPT], acc[RPT];
+#pragma unroll
+  for (int i = 0; i < RPT; ++i) { mv[i] = vecT{}; yv[i] = vecT{}; acc[i] = vecT{}; }
+  if (active) {
     if (cnt == VW) {
 #pragma unroll
       for (int i = 0; i < RPT; ++i) {
@@ -165,39 +173,51 @@ k_rpca_update_vec(const T* __restrict__ M, const T* __restrict__ U, const T* __r
           mv[i] = *(const vecTu*)(M + row * n + col);
           yv[i] = *(const vecTu*)(Yin + row * n + col);
         }
-        acc[i] = vecT{};
-      }
-      for (int t = 0; t < l; ++t) {
-        const vecT v = *(const vecTu*)(Vt + (int64_t)t * n + col);
-#pragma unroll
-        for (int i = 0; i < RPT; ++i) {
-          const T u = us[(tr + TR * i) * l + t];
-#pragma unroll
-          for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
-        }
       }
     } else {
 #pragma unroll
       for (int i = 0; i < RPT; ++i) {
         const int64_t row = min(row0 + tr + (int64_t)TR * i, m - 1);
-        mv[i] = vecT{}; yv[i] = vecT{}; acc[i] = vecT{};
 #pragma unroll
         for (int c = 0; c < VW; ++c)
           if (c < cnt) { mv[i][c] = M[row * n + col + c]; yv[i][c] = Yin[row * n + col + c]; }
       }
-      for (int t = 0; t < l; ++t) {
-        vecT v = vecT{};
-#pragma unroll
-        for (int c = 0; c < VW; ++c)
-          if (c < cnt) v[c] = Vt[(int64_t)t * n + col + c];
-#pragma unroll
-        for (int i = 0; i < RPT; ++i) {
-          const T u = us[(tr + TR * i) * l + t];
-#pragma unroll
-          for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
-        }
-      }
     }
+  }
+  for (int idx = tid; idx < tile_rows * l; idx += NTHREADS) {
+    const int i = idx / l, t = idx - i * l;
+    const int64_t row = row0 + i;
+    const T sv = fmax(sig[t] - inv_mu, T(0));      // shrinkage of a non-negative singular value
+    us[idx] = row < m ? U[row * l + t] * sv : T(0);
+  }
+  __syncthreads();
+  double z2 = 0.0;
+  if (active) {
+    // rank-l product, terms added in index order; the rows of V^T are fetched four at a time so that their
+    // latencies overlap
+    const T* vp = Vt + col;
+    auto load_v = [&](int t) -> vecT {
+      if (cnt == VW) return *(const vecTu*)(vp + (int64_t)t * n);
+      vecT v = vecT{};
+#pragma unroll
+      for (int c = 0; c < VW; ++c)
+        if (c < cnt) v[c] = vp[(int64_t)t * n + c];
+      return v;
+    };
+    auto add_term = [&](int t, const vecT& v) {
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        const T u = us[(tr + TR * i) * l + t];
+#pragma unroll
+        for (int c = 0; c < VW; ++c) acc[i][c] = fma(u, v[c], acc[i][c]);
+      }
+    };
+    int t = 0;
+    for (; t + 4 <= l; t += 4) {
+      const vecT v0 = load_v(t), v1 = load_v(t + 1), v2 = load_v(t + 2), v3 = load_v(t + 3);
+      add_term(t, v0); add_term(t + 1, v1); add_term(t + 2, v2); add_term(t + 3, v3);
+    }
+    for (; t < l; ++t) add_term(t, load_v(t));
 #pragma unroll
     for (int i = 0; i < RPT; ++i) {
       const int64_t row = row0 + tr + (int64_t)TR * i;
@@ -294,9 +314,17 @@ static int rpca_update_launch(const T* M, const T* U, const T* sig, const T* Vt,
                               T lambda, T mu_next, const T* Yin, T* Yout, T* X, T* Lout, T* S, double* part,
                               int* nparts_out, hipStream_t stream) {
   if (m <= 0 || n <= 0 || l <= 0) return BRSVD_ERR_ARG;
-  const RpcaUpdShape sh = rpca_update_shape(n, (int)sizeof(T));
+  RpcaUpdShape sh = rpca_update_shape(n, (int)sizeof(T));
+  constexpr int VW = 16 / (int)sizeof(T);
+  // line-aligned accesses (see the kernel): whole vectors per row, 64 vector columns, all arrays at one offset
+  // within a 128-byte line; the shift is at most 7 vectors, which may take one more column tile
+  const uintptr_t a0 = (uintptr_t)M % 128;
+  const bool same_line = FINAL ? ((uintptr_t)Yin % 128 == a0 && (uintptr_t)S % 128 == a0 && (uintptr_t)Lout % 128 == a0)
+                               : ((uintptr_t)Yin % 128 == a0 && (uintptr_t)Yout % 128 == a0 && (uintptr_t)X % 128 == a0);
+  const bool line_shift = sh.cvt == 64 && n % VW == 0 && a0 % 16 == 0 && same_line && (n * sizeof(T)) % 128 != 0;
+  if (line_shift) sh.col_tiles = (int)ceil_div(ceil_div(n, VW) + 7, sh.cvt);
   const int64_t wgs = ceil_div(m, sh.tile_rows) * sh.col_tiles;
-  if (wgs > INT32_MAX) return BRSVD_ERR_ARG;
+  if (wgs > INT32_MAX || (uint64_t)wgs + 64 > rpca_part_doubles(m, n)) return BRSVD_ERR_ARG;   // one partial sum per workgroup
   if (nparts_out) *nparts_out = (int)wgs;
   // the tile's rows of U: 32 x l elements with 64 vector columns; at most 32 KiB when rows are short (l <= n)
   const size_t lds = (size_t)sh.tile_rows * l * sizeof(T);
@@ -304,7 +332,6 @@ static int rpca_update_launch(const T* M, const T* U, const T* sig, const T* Vt,
   if (lds > (size_t)kMaxLds) return BRSVD_ERR_ARG;
   // nontemporal accesses when every row starts on a 16-byte boundary; otherwise rows share their first and
   // last cache lines with their neighbours and plain accesses let the caches merge them
-  constexpr int VW = 16 / (int)sizeof(T);
   const uintptr_t bits = FINAL ? ((uintptr_t)M | (uintptr_t)Yin | (uintptr_t)S | (uintptr_t)Lout)
                                : ((uintptr_t)M | (uintptr_t)Yin | (uintptr_t)Yout | (uintptr_t)X);
   const bool stream_ok = n % VW == 0 && bits % 16 == 0;
@@ -316,7 +343,7 @@ static int rpca_update_launch(const T* M, const T* U, const T* sig, const T* Vt,
     attr_set[stream_ok] = true;
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(kRpcaUpdWaves * 64), lds, stream, M, U, sig, Vt, m, n, l, T(1) / mu,
-                     mu, lambda / mu, T(1) / mu_next, Yin, Yout, X, Lout, S, part, sh.cvt, sh.col_tiles);
+                     mu, lambda / mu, T(1) / mu_next, Yin, Yout, X, Lout, S, part, sh.cvt, sh.col_tiles, line_shift ? 1 : 0);
   BRSVD_HIP_TRY(hipGetLastError());
   return BRSVD_OK;
 }
