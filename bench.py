@@ -41,7 +41,7 @@ C4_ROWS = 160000              # the GPU machine pins at most about 64 GB of host mem
 OFFLINE_HBM_TRAFFIC = {
     "C3:gemm_an": 2.2266e10, "C3:gemm_at": 2.4204e10,
     "C2:gemm_an": 1.7246e9, "C2:gemm_at": 1.8517e9,
-    "C5:gemm_an": 6.8064e8, "C5:gemm_at": 7.0227e8, "C5:rpca_update": 2.5866e9,
+    "C5:gemm_an": 6.8064e8, "C5:gemm_at": 7.0227e8, "C5:rpca_update": 2.5175e9,
 }
 OFFLINE_HBM_TRAFFIC_SOURCE = {
     "C3:gemm_an": "profiles/gemm_thin_C3_hbm_traffic.md", "C3:gemm_at": "profiles/gemm_thin_C3_hbm_traffic.md",
