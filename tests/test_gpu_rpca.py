@@ -22,7 +22,9 @@ def _case(m, n, iters=30):
                                    (700, 100),     # short rows: 25 vectors, 20 row lanes per workgroup
                                    (600, 203),     # short rows of odd length: every row starts at another alignment
                                    (400, 1003),    # long rows of odd length: the last lane straddles the row's end
-                                   (900, 22)])     # l = 20 of 22 columns
+                                   (900, 22),      # l = 20 of 22 columns
+                                   (256, 2000),    # rows of 8000 bytes: every second row starts half a 128-byte line off
+                                   (512, 1000)])   # rows of 4000 bytes: four different offsets within a line
 def test_shrink_and_update_kernels_one_iteration(m0, n0):
     """One ALM iteration on the GPU equals one oracle iteration (same SVD input, fp32 vs fp64)."""
     dev = need_gpu()
